@@ -1,0 +1,166 @@
+/*
+ * unisparse.h -- C ABI of the MI355X (gfx950) sparse-format customization library.
+ *
+ * The calls follow the paper's own statement of the problem (Section 3, Figure 3c and
+ * Section 6): a matrix arrives as COO; `decompose` splits it into two COO sub-tensors by a
+ * `sum` query over groups of entries; `convert` turns a COO tensor into the storage that a
+ * format encoding (index map + trim/merge mutation primitives, Section 4.1, Figure 7)
+ * describes, i.e. the size/ptr/idx/val arrays inferred by the rules of Section 5.1; a
+ * compute op (SpMV / SpMM, Figure 3c and Section 7.2) then runs over the formatted tensor.
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer (HBM of the current HIP device) unless its
+ *     comment says "host".  Structs themselves (us_ctx, us_coo, descriptors) live on the host.
+ *   - The library never takes ownership of caller memory.  Arrays of a us_formatted are
+ *     obtained through us_ctx.alloc and released by us_free through us_ctx.free.
+ *   - Work is enqueued on us_ctx.hip_stream.  us_convert / us_decompose synchronise that
+ *     stream once before returning (output sizes and the validation flags are data
+ *     dependent); us_spmv / us_spmm only enqueue.
+ *   - Every call returns a us_status; on error no output object is produced (*out = NULL)
+ *     and nothing is leaked.  The library never aborts, throws or prints.
+ *   - Indices are int32, values fp32 (fp32 accumulate), element counts must stay below 2^31.
+ */
+#ifndef UNISPARSE_H
+#define UNISPARSE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t us_status;
+enum {
+  US_OK = 0,
+  US_ERR_NULL = -1,             /* a required pointer is NULL                                   */
+  US_ERR_SHAPE = -2,            /* non-positive dims, bad N / leading dimension, entry beyond a fixed ELL width */
+  US_ERR_INDEX_RANGE = -3,      /* a COO coordinate lies outside nrows x ncols                   */
+  US_ERR_UNSUPPORTED_DESC = -4, /* descriptor matches none of the supported encodings           */
+  US_ERR_DUPLICATE = -5,        /* two COO entries share one coordinate                          */
+  US_ERR_ALLOC = -6,            /* allocator returned NULL                                       */
+  US_ERR_OVERFLOW = -7,         /* an output array would need 2^31 or more elements             */
+  US_ERR_HIP = -8,              /* a HIP runtime call or kernel launch failed                    */
+  US_ERR_FORMAT_MISMATCH = -9   /* compute op not available for this formatted tensor            */
+};
+
+/* Execution context.  alloc/free may be NULL: the library then uses hipMalloc/hipFree.
+ * alloc must return device memory aligned to at least 256 bytes, or NULL on failure. */
+typedef struct us_ctx {
+  void *(*alloc)(size_t bytes, void *user);
+  void (*free)(void *ptr, void *user);
+  void *user;
+  void *hip_stream; /* hipStream_t, NULL = the null stream */
+  void *profile;    /* us_profile* or NULL: per-kernel HIP-event timing (see us_profile_*) */
+} us_ctx;
+
+/* Unsorted COO input (Figure 7, #COO): borrowed device arrays of length nnz; coordinates unique. */
+typedef struct us_coo {
+  int64_t nrows, ncols, nnz;
+  const int32_t *row; /* d0 of every entry */
+  const int32_t *col; /* d1 of every entry */
+  const float *val;
+} us_coo;
+
+/* One destination expression of an index map (Figure 5a): e = c0*d0 + c1*d1 + c, optionally
+ * followed by "/ factor" (floor) or "% factor", or the indirect function of ELL (Figure 7:
+ * sum + enum grouped by the affine part, traversed by the other dimension). */
+enum { US_E_AFFINE = 0, US_E_DIV = 1, US_E_MOD = 2, US_E_INDIRECT_ENUM = 3 };
+typedef struct us_expr {
+  int32_t kind;
+  int32_t c0, c1, c;
+  int32_t factor;
+} us_expr;
+
+/* Format encoding: index map (major level first) + trim(S,E) + merge(L...), Section 4.1.
+ * Supported encodings (anything else -> US_ERR_UNSUPPORTED_DESC):
+ *   COO  (d0,d1) trim(0,1)              CSR  (d0,d1) merge(0) trim(1,1)
+ *   DCSR (d0,d1) merge(0) trim(0,1)     CSC / DCSC: the same with map (d1,d0)
+ *   DIA  (d1-d0,d0) merge(0) trim(0,0)  DIA variant (d1-d0,d1)
+ *   BCSR (d0/bh,d1/bw,d0%bh,d1%bw) merge(0,1) trim(1,1), 1 <= bh,bw <= 16
+ *   ELL  (indirect(d1),d0,d1) merge(0) trim(0,0)                                            */
+typedef struct us_format_desc {
+  int32_t nlevels;
+  us_expr level[4];
+  int32_t trim_s, trim_e; /* -1,-1 = no trim */
+  uint32_t merge_mask;    /* bit L set = merge(L) */
+  int64_t ell_width;      /* ELL only: 0 = longest row, >0 = fixed number of slots */
+} us_format_desc;
+
+enum { US_F_COO = 0, US_F_CSR, US_F_DCSR, US_F_CSC, US_F_DCSC, US_F_DIA, US_F_DIA_VARIANT, US_F_BCSR, US_F_ELL };
+/* Fill *out with the encoding of Figure 7 for `format`; b0,b1 = block height,width (BCSR) or
+ * b0 = fixed width (ELL, 0 = longest row).  host pointers. */
+us_status us_desc_preset(int32_t format, int64_t b0, int64_t b1, us_format_desc *out);
+
+/* Decomposition predicate: the `sum` query of Section 4.1.2 (groupBy map, stored entry -> 1)
+ * compared with a threshold, as in unisparse.decompose(%A, %thld){query=#sum}; entries for
+ * which it holds go to part A.
+ *   US_P_SUM_GE_ABS              count(group) >= abs                     (the paper's %thld)
+ *   US_P_SUM_GE_FRAC_OF_CAPACITY den*count(group) >= num*capacity(group), capacity = number of
+ *                                in-bounds matrix positions of the group (diagonal length, ...)
+ *   US_P_RANK_LT_ABS             rank of the entry in its row (ascending column) < abs
+ *   US_P_RANK_LT_PERCENTILE      rank < K, K = nearest-rank num/den percentile of the row
+ *                                lengths over all rows (empty rows included)
+ * group maps supported: (d1-d0), (d0), (d1) for the sum predicates; (d0) for the rank ones. */
+enum { US_P_SUM_GE_ABS = 0, US_P_SUM_GE_FRAC_OF_CAPACITY = 1, US_P_RANK_LT_ABS = 2, US_P_RANK_LT_PERCENTILE = 3 };
+typedef struct us_predicate {
+  us_expr group[2];
+  int32_t ngroup;
+  int32_t kind;
+  int64_t num, den, abs;
+} us_predicate;
+
+typedef struct us_formatted us_formatted; /* opaque; owns arrays obtained through us_ctx.alloc */
+
+/* COO -> target format (Figure 8: index-map alignment incl. Sort, then Trim/Fill/Merge).
+ * The result is canonical: ordered by the full target tuple whatever the input order.
+ * Errors: NULL, SHAPE, INDEX_RANGE, DUPLICATE, UNSUPPORTED_DESC, OVERFLOW, ALLOC, HIP. */
+us_status us_convert(const us_ctx *ctx, const us_coo *coo, const us_format_desc *target, us_formatted **out);
+
+/* decompose + convert of a hybrid (Figure 3c lines "decompose" and "convert"): entries that
+ * satisfy `pred` form part A (stored as desc_a), the rest part B (desc_b).  Both parts keep
+ * the shape of the whole matrix, so A*x = out_a*x + out_b*x. */
+us_status us_decompose(const us_ctx *ctx, const us_coo *coo, const us_format_desc *desc_a,
+                       const us_format_desc *desc_b, const us_predicate *pred,
+                       us_formatted **out_a, us_formatted **out_b);
+
+/* y = A x (accumulate = 0) or y += A x (accumulate != 0; the generic op of Figure 3c reads Y).
+ * x: ncols floats, y: nrows floats, both device.  For a hybrid call it on part A, then on
+ * part B with accumulate = 1. */
+us_status us_spmv(const us_ctx *ctx, const us_formatted *A, const float *x, float *y, int32_t accumulate);
+
+/* Y = A X or Y += A X with dense row-major X (ncols x N, leading dimension ldx >= N) and
+ * Y (nrows x N, ldy >= N), device (Section 7.2.2). */
+us_status us_spmm(const us_ctx *ctx, const us_formatted *A, const float *X, int64_t N, int64_t ldx,
+                  float *Y, int64_t ldy, int32_t accumulate);
+
+/* Level-wise view of the storage (Section 5.1).  level = tree level, which = one of:
+ *   US_A_SIZE: *count = extent of a dense level (dev_ptr = NULL)
+ *   US_A_PTR / US_A_IDX: int32 device array of *count entries
+ *   US_A_VAL: fp32 value array (level ignored)
+ * An array the format does not have yields *dev_ptr = NULL, *count = -1 and US_OK. */
+enum { US_A_SIZE = 0, US_A_PTR = 1, US_A_IDX = 2, US_A_VAL = 3 };
+us_status us_formatted_array(const us_formatted *f, int32_t level, int32_t which,
+                             const void **dev_ptr, int64_t *count);
+us_status us_formatted_info(const us_formatted *f, int64_t *nrows, int64_t *ncols, int64_t *nnz,
+                            us_format_desc *desc);
+void us_free(const us_ctx *ctx, us_formatted *f);
+const char *us_status_str(us_status s); /* static storage */
+
+/* Optional per-kernel timing: HIP events recorded on ctx->hip_stream around every kernel the
+ * library launches while ctx->profile is set.  us_profile_collect synchronises the recorded
+ * events and folds them into per-kernel totals; entry i (0 <= i < *n) is then read with
+ * us_profile_entry: name (static storage), number of launches, summed milliseconds and the
+ * summed algorithmic bytes (bytes each launch must read + write at least once). */
+typedef struct us_profile us_profile;
+us_status us_profile_create(us_profile **out);
+void us_profile_destroy(us_profile *p);
+us_status us_profile_reset(us_profile *p);
+us_status us_profile_collect(us_profile *p, int32_t *n);
+us_status us_profile_entry(const us_profile *p, int32_t i, const char **name, int64_t *launches,
+                           double *total_ms, double *alg_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* UNISPARSE_H */

@@ -1,0 +1,168 @@
+// Internal host/device helpers shared by the translation units of the library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "unisparse.h"
+
+namespace us {
+
+constexpr int WAVE = 64;
+
+template <typename T>
+__host__ __device__ inline T ceil_div(T a, T b) { return (a + b - 1) / b; }
+
+inline int bits_for(uint64_t max_value) {  // bits needed to hold values 0..max_value
+  int b = 0;
+  while (max_value) { ++b; max_value >>= 1; }
+  return b;
+}
+
+// ------------------------------------------------------------------ profiling
+struct Profile {
+  struct Pending { int name; hipEvent_t a, b; double bytes; };
+  struct Entry { const char *name; int64_t launches; double ms; double bytes; };
+  std::vector<Pending> pending;
+  std::vector<hipEvent_t> pool;
+  std::vector<Entry> entries;
+  int intern(const char *name);
+  hipEvent_t get_event();
+};
+
+// ------------------------------------------------------------------ per-call environment
+struct Env {
+  const us_ctx *ctx;
+  hipStream_t stream;
+  Profile *prof;
+  us_status status = US_OK;
+  std::vector<void *> temps;  // temporaries, released by release_temps() after the stream is idle
+
+  explicit Env(const us_ctx *c)
+      : ctx(c), stream(c ? (hipStream_t)c->hip_stream : nullptr), prof(c ? (Profile *)c->profile : nullptr) {}
+  ~Env() { release_temps(); }
+
+  void *alloc_raw(size_t bytes);
+  void free_raw(void *p);
+  template <typename T>
+  T *temp(size_t count) {  // never returns NULL for count == 0 callers: allocates at least 256 B
+    void *p = alloc_raw(count * sizeof(T) < 256 ? 256 : count * sizeof(T));
+    if (!p) { fail(US_ERR_ALLOC); return nullptr; }
+    temps.push_back(p);
+    return (T *)p;
+  }
+  template <typename T>
+  T *owned(size_t count) {  // for arrays that end up in a us_formatted
+    void *p = alloc_raw(count * sizeof(T) < 256 ? 256 : count * sizeof(T));
+    if (!p) fail(US_ERR_ALLOC);
+    return (T *)p;
+  }
+  void release_temps();
+  bool ok() const { return status == US_OK; }
+  void fail(us_status s) { if (status == US_OK) status = s; }
+  void check(hipError_t e) { if (e != hipSuccess) fail(US_ERR_HIP); }
+  void sync() { check(hipStreamSynchronize(stream)); }
+};
+
+struct LaunchScope {  // brackets one kernel launch with events when profiling is on
+  Env &env; int idx = -1; hipEvent_t a{}, b{}; double bytes;
+  LaunchScope(Env &e, const char *name, double alg_bytes);
+  ~LaunchScope();
+};
+
+// US_LAUNCH(env, "name", algorithmic_bytes, kernel<...>, grid, block, args...)
+#define US_LAUNCH(env, name, algbytes, kern, grid, block, ...)                         \
+  do {                                                                                 \
+    if ((env).ok()) {                                                                  \
+      ::us::LaunchScope _ls((env), (name), (double)(algbytes));                        \
+      hipLaunchKernelGGL(kern, dim3((unsigned)(grid)), dim3((unsigned)(block)), 0,     \
+                         (env).stream, __VA_ARGS__);                                   \
+      (env).check(hipGetLastError());                                                  \
+    }                                                                                  \
+  } while (0)
+
+// ------------------------------------------------------------------ formatted tensor
+enum Pattern { P_COO = 0, P_CSR, P_DCSR, P_DIA, P_BCSR, P_ELL };
+
+struct LevelStore {
+  int64_t size = -1;      // extent of a dense level, -1 if none
+  int32_t *ptr = nullptr; int64_t nptr = -1;
+  int32_t *idx = nullptr; int64_t nidx = -1;
+};
+
+}  // namespace us
+
+struct us_formatted {
+  us_format_desc desc{};
+  int pattern = 0;       // us::Pattern
+  bool swapped = false;  // map (d1,d0): CSC / DCSC; DIA: slab indexed by d1 (DIA variant)
+  int64_t nrows = 0, ncols = 0, nnz = 0;
+  int nlevels = 0;
+  us::LevelStore level[4];
+  float *val = nullptr; int64_t nval = 0;
+  // derived sizes
+  int64_t nmajor = 0;   // CSR: rows (cols if swapped); DCSR: stored rows; DIA: ndiag; BCSR: block rows; ELL: K
+  int64_t bh = 1, bw = 1, nblk = 0;
+  // scratch for the compute kernels (partial sums of rows cut by a tile boundary); grown on
+  // demand by ensure_workspace and released by us_free.  One compute call at a time per tensor.
+  mutable void *ws = nullptr; mutable size_t ws_bytes = 0;
+};
+
+namespace us {
+
+// device-side status flags written by kernels, read back once per call
+struct Flags {
+  int32_t index_range;  // != 0: some coordinate out of range
+  int32_t duplicate;    // != 0: two equal keys
+  int32_t ell_overflow; // != 0: an entry's rank >= fixed ELL width
+  int32_t scalar[5];    // data-dependent sizes (nnr, ndiag, nblk, K, nnz_a ...)
+};
+
+// primitives.hip
+void fill_u32(Env &env, uint32_t *p, uint64_t n, uint32_t v);
+void exclusive_scan_i32(Env &env, const int32_t *in, int32_t *out, int64_t n, int32_t *total_dev);
+// in-place exclusive scan of nb per-tile sums by one workgroup; grand total to *total_dev
+void scan_partials_launch(Env &env, uint32_t *partial, int64_t nb, int32_t *total_dev);
+void lower_bound_ptr(Env &env, const int32_t *sorted_major, int64_t n, int64_t ngroups, int32_t *ptr);
+
+// how the 64/32-bit sort key is built from a COO entry
+struct KeySpec {
+  int mode;        // 0: (a,b) with a = row (or col if swap), b = the other; 1: block (a/bh, b/bw, a%bh, b%bw)
+  int swap;        // 1: a = col, b = row
+  int b_bits;      // bits of b (mode 0) / of b/bw (mode 1)
+  int ih_bits, iw_bits;
+  uint32_t bh, bw;
+  uint32_t a_extent, b_extent;  // for range validation: row < a_extent ... (after swap)
+  int total_bits;
+};
+
+// Sort COO entries by key.  Output either unpacked (major, minor, val) or (key, val).
+struct SortOut {
+  int32_t *major = nullptr, *minor = nullptr;  // unpacked output (mode 0 only)
+  uint64_t *key64 = nullptr; uint32_t *key32 = nullptr;  // packed output
+  float *val = nullptr;
+};
+void sort_coo(Env &env, const int32_t *row, const int32_t *col, const float *val, int64_t nnz,
+              const KeySpec &ks, const SortOut &out, Flags *flags_dev);
+// sort pre-built 64-bit keys (used for the remainder part of a decomposition)
+void sort_keys(Env &env, const uint64_t *key, const float *val, int64_t nnz, const KeySpec &ks,
+               const SortOut &out, Flags *flags_dev);
+
+// convert.hip
+us_status convert_impl(Env &env, const us_coo &coo, const us_format_desc &desc, us_formatted **out);
+us_status decompose_impl(Env &env, const us_coo &coo, const us_format_desc &da, const us_format_desc &db,
+                         const us_predicate &pred, us_formatted **oa, us_formatted **ob);
+void free_formatted(Env &env, us_formatted *f);
+
+// device scratch attached to a formatted tensor, at least `bytes` large (contents undefined)
+void *ensure_workspace(Env &env, const us_formatted &A, size_t bytes);
+
+// spmv.hip / spmm.hip
+us_status spmv_impl(Env &env, const us_formatted &A, const float *x, float *y, bool accumulate);
+us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, int64_t ldx, float *Y,
+                    int64_t ldy, bool accumulate);
+
+}  // namespace us

@@ -1,0 +1,320 @@
+// Y (+)= A X with dense row-major X, Y (Section 7.2.2 evaluates SpMM over a hybrid blocked
+// ELL / COO layout).  One kernel per storage layout; lanes of a wavefront run across the
+// columns of X so every gathered X row is one contiguous read.
+#include "common.h"
+#include "device.h"
+
+namespace us {
+
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Map launch index i
+// to a tile so that every XCD works on one contiguous range of tiles and neighbouring tiles
+// (which gather overlapping X rows for banded matrices) share an L2.
+__device__ __forceinline__ int64_t xcd_tile(int64_t i, int64_t per_xcd) { return (i & 7) * per_xcd + (i >> 3); }
+
+// ------------------------------------------------------------------ BCSR 4x4 on the matrix cores
+// One wavefront owns one block row and 64 columns of X.  v_mfma_f32_4x4x1 computes 16
+// independent 4x4 += (4x1)(1x4) products; feeding the same A column to all 16 and 64
+// different X columns gives Y[4 x 64] += A[:,k] X[k, 64 cols] per instruction, i.e. lane l
+// ends up holding column l of the 4 output rows.
+__global__ __launch_bounds__(256) void bcsr44_spmm_mfma_kernel(const int32_t *ptr, const int32_t *idx,
+                                                              const float *val, int64_t nbr, int64_t per_xcd,
+                                                              int64_t nrows, int64_t ncols, const float *X,
+                                                              int64_t N, int64_t ldx, float *Y, int64_t ldy,
+                                                              int accumulate) {
+  const int lane = lane_id();
+  const int64_t br = xcd_tile(blockIdx.x, per_xcd) * 4 + wave_id();
+  if (br >= nbr) return;
+  const int64_t c = (int64_t)blockIdx.y * 64 + lane;
+  const bool col_ok = c < N;
+  float4v acc = {0.f, 0.f, 0.f, 0.f};
+  const int b0 = ptr[br], b1 = ptr[br + 1];
+  const int arow = lane & 3;
+  for (int b = b0; b < b1; ++b) {
+    const int64_t xr = (int64_t)idx[b] * 4;
+    const float4v a = *reinterpret_cast<const float4v *>(val + (int64_t)b * 16 + arow * 4);
+    float xv[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) xv[k] = (col_ok && xr + k < ncols) ? X[(xr + k) * ldx + c] : 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) acc = __builtin_amdgcn_mfma_f32_4x4x1f32(a[k], xv[k], acc, 0, 0, 0);
+  }
+  if (col_ok) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      int64_t row = br * 4 + r;
+      if (row < nrows) {
+        float *yp = Y + row * ldy + c;
+        *yp = (accumulate ? *yp : 0.f) + acc[r];
+      }
+    }
+  }
+}
+
+// any block size: one wavefront per (block row, 64 columns), plain FMAs
+__global__ __launch_bounds__(256) void bcsr_spmm_kernel(const int32_t *ptr, const int32_t *idx, const float *val,
+                                                       int64_t nbr, int bh, int bw, int64_t nrows, int64_t ncols,
+                                                       const float *X, int64_t N, int64_t ldx, float *Y,
+                                                       int64_t ldy, int accumulate) {
+  const int lane = lane_id();
+  const int64_t br = (int64_t)blockIdx.x * 4 + wave_id();
+  if (br >= nbr) return;
+  const int64_t c = (int64_t)blockIdx.y * 64 + lane;
+  if (c >= N) return;
+  const int bsz = bh * bw;
+  for (int r = 0; r < bh; ++r) {
+    int64_t row = br * bh + r;
+    if (row >= nrows) break;
+    float s = accumulate ? Y[row * ldy + c] : 0.f;
+    for (int b = ptr[br]; b < ptr[br + 1]; ++b)
+      for (int k = 0; k < bw; ++k) {
+        int64_t xr = (int64_t)idx[b] * bw + k;
+        if (xr < ncols) s += val[(int64_t)b * bsz + r * bw + k] * X[xr * ldx + c];
+      }
+    Y[row * ldy + c] = s;
+  }
+}
+
+// ------------------------------------------------------------------ row-grouped layouts, one wavefront per (row, 64 columns)
+__global__ __launch_bounds__(256) void ell_spmm_kernel(const int32_t *ecol, const float *ev, int64_t K, int64_t nrows,
+                                                      const float *X, int64_t N, int64_t ldx, float *Y, int64_t ldy,
+                                                      int accumulate) {
+  const int64_t i = (int64_t)blockIdx.x * 4 + wave_id();
+  if (i >= nrows) return;
+  const int64_t c = (int64_t)blockIdx.y * 64 + lane_id();
+  if (c >= N) return;
+  float s = accumulate ? Y[i * ldy + c] : 0.f;
+  for (int64_t k = 0; k < K; ++k) {
+    int32_t col = ecol[k * nrows + i];
+    if (col >= 0) s += ev[k * nrows + i] * X[(int64_t)col * ldx + c];
+  }
+  Y[i * ldy + c] = s;
+}
+
+__global__ __launch_bounds__(256) void csr_spmm_kernel(const int32_t *ptr, const int32_t *idx, const float *val,
+                                                      const int32_t *row_ids, int64_t nrows_stored, const float *X,
+                                                      int64_t N, int64_t ldx, float *Y, int64_t ldy, int accumulate) {
+  const int64_t i = (int64_t)blockIdx.x * 4 + wave_id();
+  if (i >= nrows_stored) return;
+  const int64_t c = (int64_t)blockIdx.y * 64 + lane_id();
+  if (c >= N) return;
+  const int64_t row = row_ids ? row_ids[i] : i;
+  float s = accumulate ? Y[row * ldy + c] : 0.f;
+  for (int e = ptr[i]; e < ptr[i + 1]; ++e) s += val[e] * X[(int64_t)idx[e] * ldx + c];
+  Y[row * ldy + c] = s;
+}
+
+__global__ __launch_bounds__(256) void dia_spmm_kernel(const int32_t *off, const float *val, int64_t ndiag,
+                                                      int64_t nrows, int64_t ncols, const float *X, int64_t N,
+                                                      int64_t ldx, float *Y, int64_t ldy, int accumulate) {
+  const int64_t i = (int64_t)blockIdx.x * 4 + wave_id();
+  if (i >= nrows) return;
+  const int64_t c = (int64_t)blockIdx.y * 64 + lane_id();
+  if (c >= N) return;
+  float s = accumulate ? Y[i * ldy + c] : 0.f;
+  for (int64_t k = 0; k < ndiag; ++k) {
+    int64_t j = i + off[k];
+    if (j >= 0 && j < ncols) s += val[k * nrows + i] * X[j * ldx + c];
+  }
+  Y[i * ldy + c] = s;
+}
+
+// ------------------------------------------------------------------ COO sorted by row: equal shares of non-zeros per wavefront
+// A wavefront walks CS_CHUNK consecutive entries; for each it adds val * X[col, :] into a
+// register accumulator and flushes when the row changes.  Row pieces cut by a chunk boundary
+// go to a carry buffer and are summed in chunk order by the fix-up kernel (reproducible).
+constexpr int CS_CHUNK = 512;
+
+__global__ __launch_bounds__(256) void coo_spmm_kernel(const int32_t *row, const int32_t *col, const float *val,
+                                                      int64_t nnz, const float *X, int64_t N, int64_t ldx, float *Y,
+                                                      int64_t ldy, int32_t *carry_row, float *carry) {
+  const int lane = lane_id();
+  const int64_t chunk = (int64_t)blockIdx.x * 4 + wave_id();
+  const int64_t e0 = chunk * CS_CHUNK;
+  if (e0 >= nnz) return;
+  const int64_t e1 = min(e0 + CS_CHUNK, nnz);
+  const int64_t c = (int64_t)blockIdx.y * 64 + lane;
+  const bool col_ok = c < N;
+  const int32_t row_before = e0 > 0 ? row[e0 - 1] : -1;
+  const int32_t row_after = e1 < nnz ? row[e1] : -1;
+  const int32_t first_row = row[e0], last_row = row[e1 - 1];
+  float *carry_head = carry + ((chunk * 2 + 0) * gridDim.y + blockIdx.y) * 64;
+  float *carry_tail = carry + ((chunk * 2 + 1) * gridDim.y + blockIdx.y) * 64;
+  const bool head_cut = first_row == row_before, tail_cut = last_row == row_after;
+  float acc = 0.f;
+  int32_t cur = first_row;
+  bool in_head = true;  // still inside the first row piece of the chunk
+  for (int64_t base = e0; base < e1; base += 64) {
+    const int64_t e = base + lane;
+    int32_t r = e < e1 ? row[e] : -1, cc = e < e1 ? col[e] : 0;
+    float v = e < e1 ? val[e] : 0.f;
+    const int cnt = (int)min((int64_t)64, e1 - base);
+    for (int t = 0; t < cnt; ++t) {
+      int32_t rt = __shfl(r, t), ct = __shfl(cc, t);
+      float vt = __shfl(v, t);
+      if (rt != cur) {  // flush the finished piece of row `cur`
+        if (col_ok) {
+          if (in_head && head_cut) carry_head[lane] = acc;
+          else Y[(int64_t)cur * ldy + c] += acc;
+        }
+        in_head = false;
+        acc = 0.f;
+        cur = rt;
+      }
+      if (col_ok) acc += vt * X[(int64_t)ct * ldx + c];
+    }
+  }
+  // last piece
+  const bool single = in_head;  // the whole chunk lies inside one row
+  if (col_ok) {
+    if (single) {
+      if (head_cut || tail_cut) { carry_head[lane] = acc; carry_tail[lane] = 0.f; }
+      else Y[(int64_t)cur * ldy + c] += acc;
+    } else {
+      if (tail_cut) carry_tail[lane] = acc;
+      else Y[(int64_t)cur * ldy + c] += acc;
+    }
+  }
+  if (lane == 0 && blockIdx.y == 0) {
+    bool head_used = single ? (head_cut || tail_cut) : head_cut;
+    bool tail_used = single ? (head_cut || tail_cut) : tail_cut;
+    carry_row[chunk * 2 + 0] = head_used ? first_row : -1;
+    carry_row[chunk * 2 + 1] = tail_used ? last_row : -1;
+  }
+}
+
+__global__ __launch_bounds__(256) void coo_spmm_fixup_kernel(const int32_t *carry_row, const float *carry,
+                                                            int64_t nentries, int64_t ncb, int64_t N, float *Y,
+                                                            int64_t ldy) {
+  const int lane = lane_id();
+  const int64_t e = (int64_t)blockIdx.x * 4 + wave_id();
+  if (e >= nentries) return;
+  const int32_t r = carry_row[e];
+  if (r < 0) return;
+  // first entry of the run of row r (entries marked -1 in between belong to no run of r:
+  // a run never skips an entry, see the kernel above)
+  if (e > 0 && carry_row[e - 1] == r) return;
+  const int64_t c = (int64_t)blockIdx.y * 64 + lane;
+  if (c >= N) return;
+  float s = 0.f;
+  for (int64_t j = e; j < nentries && carry_row[j] == r; ++j) s += carry[(j * ncb + blockIdx.y) * 64 + lane];
+  Y[(int64_t)r * ldy + c] += s;
+}
+
+// scatter form for the column-major layouts (CSC / DCSC / column-major COO)
+__global__ __launch_bounds__(256) void coo_spmm_atomic_kernel(const int32_t *r, const int32_t *c, const float *val,
+                                                             int64_t nnz, const float *X, int64_t N, int64_t ldx,
+                                                             float *Y, int64_t ldy) {
+  const int64_t e = (int64_t)blockIdx.x * 4 + wave_id();
+  if (e >= nnz) return;
+  const int64_t cc = (int64_t)blockIdx.y * 64 + lane_id();
+  if (cc < N) atomicAdd(&Y[(int64_t)r[e] * ldy + cc], val[e] * X[(int64_t)c[e] * ldx + cc]);
+}
+
+static void zero_rows(Env &env, float *Y, int64_t nrows, int64_t N, int64_t ldy) {
+  if (ldy == N) { fill_u32(env, (uint32_t *)Y, (uint64_t)nrows * N, 0u); return; }
+  for (int64_t i = 0; i < nrows && env.ok(); ++i) fill_u32(env, (uint32_t *)(Y + i * ldy), N, 0u);
+}
+
+us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, int64_t ldx, float *Y, int64_t ldy,
+                    bool accumulate) {
+  const int64_t ncb = ceil_div<int64_t>(N, 64);
+  const int acc = accumulate ? 1 : 0;
+  const double xy = 4.0 * N * (A.ncols + A.nrows);
+  switch (A.pattern) {
+    case P_BCSR: {
+      if (A.bh == 4 && A.bw == 4) {
+        const int64_t tiles = ceil_div<int64_t>(A.nmajor, 4), per_xcd = ceil_div<int64_t>(tiles, 8);
+        if (env.ok()) {
+          LaunchScope ls(env, "spmm_bcsr44_mfma", 4.0 * A.nval + 4.0 * A.nblk + 4.0 * (A.nmajor + 1) + xy);
+          hipLaunchKernelGGL(bcsr44_spmm_mfma_kernel, dim3((unsigned)(per_xcd * 8), (unsigned)ncb), dim3(256), 0,
+                             env.stream, (const int32_t *)A.level[1].ptr, (const int32_t *)A.level[1].idx,
+                             (const float *)A.val, A.nmajor, per_xcd, A.nrows, A.ncols, X, N, ldx, Y, ldy, acc);
+          env.check(hipGetLastError());
+        }
+      } else if (env.ok()) {
+        LaunchScope ls(env, "spmm_bcsr", 4.0 * A.nval + 4.0 * A.nblk + xy);
+        hipLaunchKernelGGL(bcsr_spmm_kernel, dim3((unsigned)ceil_div<int64_t>(A.nmajor, 4), (unsigned)ncb), dim3(256),
+                           0, env.stream, (const int32_t *)A.level[1].ptr, (const int32_t *)A.level[1].idx,
+                           (const float *)A.val, A.nmajor, (int)A.bh, (int)A.bw, A.nrows, A.ncols, X, N, ldx, Y, ldy, acc);
+        env.check(hipGetLastError());
+      }
+      return env.status;
+    }
+    case P_ELL:
+      if (env.ok()) {
+        LaunchScope ls(env, "spmm_ell", 8.0 * A.nval + xy);
+        hipLaunchKernelGGL(ell_spmm_kernel, dim3((unsigned)ceil_div<int64_t>(A.nrows, 4), (unsigned)ncb), dim3(256), 0,
+                           env.stream, (const int32_t *)A.level[2].idx, (const float *)A.val, A.nmajor, A.nrows, X, N,
+                           ldx, Y, ldy, acc);
+        env.check(hipGetLastError());
+      }
+      return env.status;
+    case P_CSR:
+    case P_DCSR: {
+      if (A.swapped) break;
+      const bool d = A.pattern == P_DCSR;
+      if (d && !accumulate) zero_rows(env, Y, A.nrows, N, ldy);
+      if (env.ok() && A.nmajor > 0) {
+        LaunchScope ls(env, "spmm_csr", 8.0 * A.nnz + xy);
+        hipLaunchKernelGGL(csr_spmm_kernel, dim3((unsigned)ceil_div<int64_t>(A.nmajor, 4), (unsigned)ncb), dim3(256), 0,
+                           env.stream, (const int32_t *)A.level[1].ptr, (const int32_t *)A.level[1].idx,
+                           (const float *)A.val, (const int32_t *)(d ? A.level[0].idx : nullptr), A.nmajor, X, N, ldx,
+                           Y, ldy, d ? 1 : acc);
+        env.check(hipGetLastError());
+      }
+      return env.status;
+    }
+    case P_DIA:
+      if (A.swapped) break;
+      if (env.ok()) {
+        LaunchScope ls(env, "spmm_dia", 4.0 * A.nval + xy);
+        hipLaunchKernelGGL(dia_spmm_kernel, dim3((unsigned)ceil_div<int64_t>(A.nrows, 4), (unsigned)ncb), dim3(256), 0,
+                           env.stream, (const int32_t *)A.level[0].idx, (const float *)A.val, A.nmajor, A.nrows, A.ncols,
+                           X, N, ldx, Y, ldy, acc);
+        env.check(hipGetLastError());
+      }
+      return env.status;
+    case P_COO: {
+      if (!accumulate) zero_rows(env, Y, A.nrows, N, ldy);
+      if (A.nnz == 0) return env.status;
+      if (A.swapped) {
+        if (env.ok()) {
+          LaunchScope ls(env, "spmm_coo_atomic", 12.0 * A.nnz + xy);
+          hipLaunchKernelGGL(coo_spmm_atomic_kernel, dim3((unsigned)ceil_div<int64_t>(A.nnz, 4), (unsigned)ncb),
+                             dim3(256), 0, env.stream, (const int32_t *)A.level[1].idx, (const int32_t *)A.level[0].idx,
+                             (const float *)A.val, A.nnz, X, N, ldx, Y, ldy);
+          env.check(hipGetLastError());
+        }
+        return env.status;
+      }
+      const int64_t nchunks = ceil_div<int64_t>(A.nnz, CS_CHUNK);
+      const size_t rows_bytes = (size_t)nchunks * 2 * sizeof(int32_t);
+      const size_t rows_pad = (rows_bytes + 255) / 256 * 256;
+      char *ws = (char *)ensure_workspace(env, A, rows_pad + (size_t)nchunks * 2 * ncb * 64 * sizeof(float));
+      if (!env.ok()) return env.status;
+      int32_t *carry_row = (int32_t *)ws;
+      float *carry = (float *)(ws + rows_pad);
+      {
+        LaunchScope ls(env, "spmm_coo", 12.0 * A.nnz + xy);
+        hipLaunchKernelGGL(coo_spmm_kernel, dim3((unsigned)ceil_div<int64_t>(nchunks, 4), (unsigned)ncb), dim3(256), 0,
+                           env.stream, (const int32_t *)A.level[0].idx, (const int32_t *)A.level[1].idx,
+                           (const float *)A.val, A.nnz, X, N, ldx, Y, ldy, carry_row, carry);
+        env.check(hipGetLastError());
+      }
+      if (env.ok()) {
+        LaunchScope ls(env, "spmm_coo_fixup", 8.0 * nchunks);
+        hipLaunchKernelGGL(coo_spmm_fixup_kernel, dim3((unsigned)ceil_div<int64_t>(nchunks * 2, 4), (unsigned)ncb),
+                           dim3(256), 0, env.stream, (const int32_t *)carry_row, (const float *)carry, nchunks * 2, ncb,
+                           N, Y, ldy);
+        env.check(hipGetLastError());
+      }
+      return env.status;
+    }
+    default: break;
+  }
+  return US_ERR_FORMAT_MISMATCH;
+}
+
+}  // namespace us

@@ -1,0 +1,251 @@
+// y (+)= A x over a formatted tensor: the SpMV of Figure 3c specialised per storage layout
+// (what the two-step kernel generator of Section 5.3 would emit for each: walk the levels,
+// recover (d0,d1) with the inverse index map, guard the bounds, multiply-accumulate).
+#include "common.h"
+#include "device.h"
+
+namespace us {
+
+// ------------------------------------------------------------------ compressed rows (CSR / DCSR / CSC-transposed use)
+// Work is split evenly over the merged sequence {row ends} U {non-zeros}, so a 20,000-entry
+// row and 20,000 one-entry rows cost the same.  Each workgroup takes MP_TILE consecutive steps of
+// that sequence, stages the products in LDS, every thread walks MP_IPT steps, and partial row
+// sums are stitched together with a segmented scan (fixed order: bitwise reproducible).
+constexpr int MP_T = 256, MP_IPT = 8, MP_TILE = MP_T * MP_IPT;
+
+// number of row ends consumed before step `diag`: largest r with ptr_end[r-1] <= diag - r ...
+__device__ __forceinline__ int64_t merge_path_rows(const int32_t *row_end, int64_t nrows, int64_t nnz, int64_t diag) {
+  int64_t lo = diag > nnz ? diag - nnz : 0, hi = diag < nrows ? diag : nrows;
+  while (lo < hi) {
+    int64_t mid = (lo + hi) >> 1;
+    if ((int64_t)row_end[mid] <= diag - mid - 1) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+struct SegPair { int32_t key; float val; };
+
+template <bool INDIRECT_ROWS>
+__global__ __launch_bounds__(MP_T) void csr_spmv_kernel(const int32_t *ptr, const int32_t *idx, const float *val,
+                                                       const int32_t *row_ids, int64_t nrows, int64_t nnz,
+                                                       const float *x, float *y, int accumulate,
+                                                       int32_t *carry_row, float *carry_val) {
+  __shared__ float s_prod[MP_TILE];
+  __shared__ int32_t s_end[MP_TILE + 1];
+  __shared__ int64_t s_range[4];
+  __shared__ int32_t s_wkey[MP_T / 64];
+  __shared__ float s_wval[MP_T / 64];
+  const int32_t *row_end = ptr + 1;
+  const int64_t total = nrows + nnz;
+  const int64_t diag0 = (int64_t)blockIdx.x * MP_TILE;
+  const int64_t diag1 = min(diag0 + MP_TILE, total);
+  if (threadIdx.x < 2) {
+    int64_t d = threadIdx.x == 0 ? diag0 : diag1;
+    int64_t r = merge_path_rows(row_end, nrows, nnz, d);
+    s_range[threadIdx.x * 2] = r;
+    s_range[threadIdx.x * 2 + 1] = d - r;
+  }
+  __syncthreads();
+  const int64_t r0 = s_range[0], z0 = s_range[1], r1 = s_range[2], z1 = s_range[3];
+  const int nr = (int)(r1 - r0), nz = (int)(z1 - z0);
+  for (int i = threadIdx.x; i < nz; i += MP_T) s_prod[i] = val[z0 + i] * x[idx[z0 + i]];
+  for (int i = threadIdx.x; i < nr; i += MP_T) s_end[i] = (int32_t)(row_end[r0 + i] - z0);
+  __syncthreads();
+
+  // this thread's slice of the tile's merge sequence
+  const int steps = (int)(diag1 - diag0);
+  int d = min((int)threadIdx.x * MP_IPT, steps);
+  int lo = d > nz ? d - nz : 0, hi = d < nr ? d : nr;
+  while (lo < hi) {
+    int mid = (lo + hi) >> 1;
+    if (s_end[mid] <= d - mid - 1) lo = mid + 1; else hi = mid;
+  }
+  int ri = lo, zi = d - lo;
+  const int dend = min(d + MP_IPT, steps);
+  float sum = 0.f, first_sum = 0.f;
+  int first_row = -1;  // first row that ends inside this thread's slice
+  for (int s = d; s < dend; ++s) {
+    bool take_nz = zi < nz && (ri >= nr || zi < s_end[ri]);
+    if (take_nz) {
+      sum += s_prod[zi++];
+    } else {
+      if (first_row < 0) { first_row = ri; first_sum = sum; }
+      else {
+        int64_t row = r0 + ri;
+        int64_t out = INDIRECT_ROWS ? row_ids[row] : row;
+        y[out] = (accumulate ? y[out] : 0.f) + sum;
+      }
+      sum = 0.f;
+      ++ri;
+    }
+  }
+  // Inclusive segmented scan over the workgroup of (row the thread stopped in, unfinished sum).
+  // Rows only grow from thread to thread, so equal keys are contiguous.
+  SegPair p{ri, sum};
+  const int lane = lane_id(), w = wave_id();
+#pragma unroll
+  for (int dd = 1; dd < 64; dd <<= 1) {
+    int32_t k = __shfl_up(p.key, dd);
+    float v = __shfl_up(p.val, dd);
+    if (lane >= dd && k == p.key) p.val += v;
+  }
+  if (lane == 63) { s_wkey[w] = p.key; s_wval[w] = p.val; }
+  __syncthreads();
+  // state of the scan at the end of the previous wave (fixed left-to-right order)
+  int32_t head_key = -2;
+  float wave_carry = 0.f;
+  for (int ww = 0; ww < w; ++ww) {
+    if (s_wkey[ww] == head_key) wave_carry += s_wval[ww];
+    else { head_key = s_wkey[ww]; wave_carry = s_wval[ww]; }
+  }
+  const float incl = p.val + (p.key == head_key ? wave_carry : 0.f);
+  // what the previous thread hands over: it stopped in the row this thread starts in
+  int32_t prev_key = __shfl_up(p.key, 1);
+  float prev_val = __shfl_up(incl, 1);
+  if (lane == 0) { prev_key = head_key; prev_val = wave_carry; }
+  if (first_row >= 0) {
+    float inherit = (prev_key == first_row) ? prev_val : 0.f;
+    int64_t row = r0 + first_row;
+    int64_t out = INDIRECT_ROWS ? row_ids[row] : row;
+    y[out] = (accumulate ? y[out] : 0.f) + (first_sum + inherit);
+  }
+  if (threadIdx.x == MP_T - 1) {
+    carry_row[blockIdx.x] = (int32_t)min(r0 + (int64_t)p.key, nrows);
+    carry_val[blockIdx.x] = incl;
+  }
+}
+
+// rows that span several workgroups: add the unfinished sums of the earlier workgroups
+template <bool INDIRECT_ROWS>
+__global__ __launch_bounds__(256) void csr_spmv_fixup_kernel(const int32_t *carry_row, const float *carry_val,
+                                                            int64_t nblocks, int64_t nrows,
+                                                            const int32_t *row_ids, float *y) {
+  int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (b >= nblocks) return;
+  int32_t row = carry_row[b];
+  if (row >= nrows) return;
+  if (b > 0 && carry_row[b - 1] == row) return;  // not the first workgroup of this run
+  float s = 0.f;
+  for (int64_t j = b; j < nblocks && carry_row[j] == row; ++j) s += carry_val[j];
+  int64_t out = INDIRECT_ROWS ? row_ids[row] : row;
+  y[out] += s;
+}
+
+static void spmv_compressed(Env &env, const us_formatted &A, const int32_t *ptr, const int32_t *idx, const float *val,
+                            const int32_t *row_ids, int64_t nrows_stored, int64_t nnz, const float *x, float *y,
+                            bool accumulate) {
+  const int64_t total = nrows_stored + nnz;
+  if (total == 0) return;
+  const int64_t nb = ceil_div<int64_t>(total, MP_TILE);
+  const size_t half = ((size_t)nb * 4 + 255) / 256 * 256;
+  char *ws = (char *)ensure_workspace(env, A, 2 * half);
+  if (!env.ok()) return;
+  int32_t *carry_row = (int32_t *)ws;
+  float *carry_val = (float *)(ws + half);
+  const double bytes = 8.0 * nnz + 4.0 * (nrows_stored + 1) + 4.0 * nnz /*x gather*/ + 4.0 * nrows_stored;
+  if (row_ids) {
+    US_LAUNCH(env, "spmv_csr", bytes, (csr_spmv_kernel<true>), nb, MP_T, ptr, idx, val, row_ids, nrows_stored, nnz,
+              x, y, accumulate ? 1 : 0, carry_row, carry_val);
+    US_LAUNCH(env, "spmv_csr_fixup", 8.0 * nb, (csr_spmv_fixup_kernel<true>), ceil_div<int64_t>(nb, 256), 256,
+              (const int32_t *)carry_row, (const float *)carry_val, nb, nrows_stored, row_ids, y);
+  } else {
+    US_LAUNCH(env, "spmv_csr", bytes, (csr_spmv_kernel<false>), nb, MP_T, ptr, idx, val, row_ids, nrows_stored, nnz,
+              x, y, accumulate ? 1 : 0, carry_row, carry_val);
+    US_LAUNCH(env, "spmv_csr_fixup", 8.0 * nb, (csr_spmv_fixup_kernel<false>), ceil_div<int64_t>(nb, 256), 256,
+              (const int32_t *)carry_row, (const float *)carry_val, nb, nrows_stored, row_ids, y);
+  }
+}
+
+// ------------------------------------------------------------------ DIA: y[i] (+)= sum_k val[k*nrows+i] * x[i+off_k]
+__global__ __launch_bounds__(256) void dia_spmv_kernel(const int32_t *off, const float *val, int64_t ndiag,
+                                                      int64_t nrows, int64_t ncols, const float *x, float *y,
+                                                      int accumulate) {
+  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= nrows) return;
+  float s = accumulate ? y[i] : 0.f;
+  for (int64_t k = 0; k < ndiag; ++k) {
+    int64_t j = i + off[k];
+    if (j >= 0 && j < ncols) s += val[k * nrows + i] * x[j];
+  }
+  y[i] = s;
+}
+
+// generic scatter form used by the layouts whose leaves are not grouped by output row
+// (COO, CSC/DCSC, DIA variant, ELL): y[d0] += val * x[d1] with float atomics.
+__global__ __launch_bounds__(256) void coo_spmv_atomic_kernel(const int32_t *r, const int32_t *c, const float *val,
+                                                             int64_t n, const float *x, float *y) {
+  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) atomicAdd(&y[r[i]], val[i] * x[c[i]]);
+}
+
+__global__ __launch_bounds__(256) void ell_spmv_kernel(const int32_t *ecol, const float *ev, int64_t K, int64_t nrows,
+                                                      const float *x, float *y, int accumulate) {
+  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= nrows) return;
+  float s = accumulate ? y[i] : 0.f;
+  for (int64_t k = 0; k < K; ++k) {
+    int32_t c = ecol[k * nrows + i];
+    if (c >= 0) s += ev[k * nrows + i] * x[c];
+  }
+  y[i] = s;
+}
+
+// BCSR: one wavefront per block row, lanes over the entries of the blocks
+__global__ __launch_bounds__(256) void bcsr_spmv_kernel(const int32_t *ptr, const int32_t *idx, const float *val,
+                                                       int64_t nbr, int bh, int bw, int64_t nrows, int64_t ncols,
+                                                       const float *x, float *y, int accumulate) {
+  int64_t br = (int64_t)blockIdx.x * 4 + wave_id();
+  if (br >= nbr) return;
+  const int bsz = bh * bw, lane = lane_id();
+  for (int r = 0; r < bh; ++r) {
+    float s = 0.f;
+    for (int64_t e = (int64_t)ptr[br] * bw + lane; e < (int64_t)ptr[br + 1] * bw; e += 64) {
+      int64_t blk = e / bw; int c = (int)(e - blk * bw);
+      int64_t col = (int64_t)idx[blk] * bw + c;
+      if (col < ncols) s += val[blk * bsz + r * bw + c] * x[col];
+    }
+    s = wave_sum(s);
+    int64_t row = br * bh + r;
+    if (lane == 0 && row < nrows) y[row] = (accumulate ? y[row] : 0.f) + s;
+  }
+}
+
+us_status spmv_impl(Env &env, const us_formatted &A, const float *x, float *y, bool accumulate) {
+  switch (A.pattern) {
+    case P_CSR:
+      if (A.swapped) break;
+      spmv_compressed(env, A, A.level[1].ptr, A.level[1].idx, A.val, nullptr, A.nrows, A.nnz, x, y, accumulate);
+      return env.status;
+    case P_DCSR:
+      if (A.swapped) break;
+      if (!accumulate) fill_u32(env, (uint32_t *)y, A.nrows, 0u);
+      spmv_compressed(env, A, A.level[1].ptr, A.level[1].idx, A.val, A.level[0].idx, A.nmajor, A.nnz, x, y, true);
+      return env.status;
+    case P_DIA:
+      if (A.swapped) break;
+      US_LAUNCH(env, "spmv_dia", 4.0 * A.nval + 8.0 * A.nrows + 4.0 * A.ncols, dia_spmv_kernel,
+                ceil_div<int64_t>(A.nrows, 256), 256, (const int32_t *)A.level[0].idx, (const float *)A.val,
+                A.nmajor, A.nrows, A.ncols, x, y, accumulate ? 1 : 0);
+      return env.status;
+    case P_ELL:
+      US_LAUNCH(env, "spmv_ell", 8.0 * A.nval + 8.0 * A.nrows, ell_spmv_kernel, ceil_div<int64_t>(A.nrows, 256), 256,
+                (const int32_t *)A.level[2].idx, (const float *)A.val, A.nmajor, A.nrows, x, y, accumulate ? 1 : 0);
+      return env.status;
+    case P_BCSR:
+      US_LAUNCH(env, "spmv_bcsr", 4.0 * A.nval + 4.0 * A.nblk + 8.0 * A.nrows, bcsr_spmv_kernel,
+                ceil_div<int64_t>(A.nmajor, 4), 256, (const int32_t *)A.level[1].ptr, (const int32_t *)A.level[1].idx,
+                (const float *)A.val, A.nmajor, (int)A.bh, (int)A.bw, A.nrows, A.ncols, x, y, accumulate ? 1 : 0);
+      return env.status;
+    case P_COO:
+      if (!accumulate) fill_u32(env, (uint32_t *)y, A.nrows, 0u);
+      if (A.nnz > 0)
+        US_LAUNCH(env, "spmv_coo", 16.0 * A.nnz, coo_spmv_atomic_kernel, ceil_div<int64_t>(A.nnz, 256), 256,
+                  (const int32_t *)(A.swapped ? A.level[1].idx : A.level[0].idx),
+                  (const int32_t *)(A.swapped ? A.level[0].idx : A.level[1].idx), (const float *)A.val, A.nnz, x, y);
+      return env.status;
+    default: break;
+  }
+  return US_ERR_FORMAT_MISMATCH;
+}
+
+}  // namespace us

@@ -1,0 +1,75 @@
+"""Shared by the GPU parity tests: descriptor translation and array comparison."""
+import numpy as np
+import torch
+
+from oracle import unisparse_oracle as O
+from paper_2403_05802_amd import binding as B
+
+KIND = {O.AFFINE: B.US_E_AFFINE, O.DIV: B.US_E_DIV, O.MOD: B.US_E_MOD, O.ENUM: B.US_E_INDIRECT_ENUM}
+PRED = {O.SUM_GE_ABS: B.US_P_SUM_GE_ABS, O.SUM_GE_FRAC_OF_CAPACITY: B.US_P_SUM_GE_FRAC_OF_CAPACITY,
+        O.RANK_LT_ABS: B.US_P_RANK_LT_ABS, O.RANK_LT_PERCENTILE: B.US_P_RANK_LT_PERCENTILE}
+
+
+def us_expr_of(e: O.Expr):
+    return B.expr(KIND[e.kind], e.c0, e.c1, e.c, e.factor)
+
+
+def us_desc_of(d: O.FormatDesc):
+    return B.make_desc([us_expr_of(e) for e in d.levels], d.trim, d.merge, d.ell_width)
+
+
+def us_pred_of(p: O.Predicate):
+    return B.make_predicate([us_expr_of(e) for e in p.group], PRED[p.kind], p.num, p.den, p.abs)
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def coo_to_dev(coo):
+    return dev(coo.row), dev(coo.col), dev(coo.val)
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+def assert_same_layout(g: "B.Formatted", o: "O.Formatted", what=""):
+    """Bit-exact comparison of every size / ptr / idx / val array with the oracle's."""
+    assert (g.nrows, g.ncols, g.nnz) == (o.nrows, o.ncols, o.nnz), what
+    assert g.desc.nlevels == len(o.levels), what
+    for L, lvl in enumerate(o.levels):
+        if lvl.kind == "dense":
+            assert g.size(L) == lvl.size, f"{what} size L{L}: {g.size(L)} vs {lvl.size}"
+        else:
+            assert g.size(L) == -1, f"{what} unexpected size at L{L}"
+        gp, gi = g.ptr(L), g.idx(L)
+        if lvl.ptr is None:
+            assert gp is None, f"{what} unexpected ptr at L{L}"
+        else:
+            assert gp is not None, f"{what} missing ptr at L{L}"
+            np.testing.assert_array_equal(host(gp), lvl.ptr, err_msg=f"{what} ptr L{L}")
+        if lvl.idx is None:
+            assert gi is None, f"{what} unexpected idx at L{L}"
+        else:
+            assert gi is not None, f"{what} missing idx at L{L}"
+            np.testing.assert_array_equal(host(gi), lvl.idx, err_msg=f"{what} idx L{L}")
+    gv = host(g.val())
+    assert gv.shape == o.val.shape, f"{what} val count {gv.shape} vs {o.val.shape}"
+    np.testing.assert_array_equal(gv.view(np.int32), o.val.view(np.int32), err_msg=f"{what} val bits")
+
+
+def rel_err(y, yref, scale):
+    """max_i |y_i - yref_i| / max(|yref_i|, scale_i * 2^-10): plain relative error, floored by a
+    small fraction of the row's absolute sum (fp32 summation error is bounded by the
+    latter, not by |yref| when terms cancel)."""
+    y = np.asarray(y, dtype=np.float64)
+    den = np.maximum(np.abs(yref), scale * 2.0 ** -10)
+    den[den == 0] = 1.0
+    return float(np.max(np.abs(y - yref) / den)) if y.size else 0.0
+
+
+TOL = 1e-4   # max relative error of fp32 SpMV / SpMM against the fp64 oracle
