@@ -277,17 +277,24 @@ static us_status build_from_sorted(Env &env, const Plan &plan, const us_format_d
   return finish(US_ERR_UNSUPPORTED_DESC);
 }
 
-// ------------------------------------------------------------------ DIA
-// Sum query grouped by d1-d0: one counter per diagonal, bin = d1 - d0 + (nrows-1).
-// Entries of a wavefront that hit the same bin are combined before the atomic.
-__global__ __launch_bounds__(256) void diag_hist_kernel(const int32_t *row, const int32_t *col, int64_t n,
-                                                       uint32_t nrows, uint32_t ncols, uint32_t *count,
-                                                       Flags *flags) {
+// ------------------------------------------------------------------ Sum query (group histogram) and DIA
+// Groups supported by the groupBy map of the sum query: diagonals (d1-d0), rows (d0), columns (d1).
+enum { G_DIAG = 0, G_ROW = 1, G_COL = 2 };
+
+__device__ __forceinline__ uint32_t group_bin(int gkind, uint32_t r, uint32_t c, uint32_t nrows) {
+  return gkind == G_DIAG ? c - r + (nrows - 1) : (gkind == G_ROW ? r : c);
+}
+
+// One counter per group.  Entries of a wavefront that hit the same bin are combined before
+// the atomic, so a matrix whose entries sit on a handful of diagonals does not serialise.
+__global__ __launch_bounds__(256) void group_hist_kernel(const int32_t *row, const int32_t *col, int64_t n,
+                                                        int gkind, uint32_t nrows, uint32_t ncols, uint32_t *count,
+                                                        Flags *flags) {
   int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   bool valid = i < n;
   uint32_t r = valid ? (uint32_t)row[i] : 0u, c = valid ? (uint32_t)col[i] : 0u;
   if (valid && (r >= nrows || c >= ncols)) { flags->index_range = 1; valid = false; }
-  uint32_t bin = c - r + (nrows - 1);
+  uint32_t bin = group_bin(gkind, r, c, nrows);
   uint64_t todo = __ballot(valid);
   while (todo) {
     int leader = __ffsll((unsigned long long)todo) - 1;
@@ -298,10 +305,32 @@ __global__ __launch_bounds__(256) void diag_hist_kernel(const int32_t *row, cons
   }
 }
 
-// flag of a diagonal: stored (count > 0) for a plain conversion
-__global__ __launch_bounds__(256) void diag_flag_nonempty_kernel(const uint32_t *count, int64_t nbins, int32_t *flag) {
-  int64_t d = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (d < nbins) flag[d] = count[d] > 0 ? 1 : 0;
+// flag[g] = group g goes to part A.  pkind < 0: every non-empty group (plain conversion).
+// Adds the number of entries in flagged groups to *nnz_a.
+__global__ __launch_bounds__(256) void group_flag_kernel(const uint32_t *count, int64_t nbins, int gkind, int pkind,
+                                                        int64_t num, int64_t den, int64_t thr, int64_t nrows,
+                                                        int64_t ncols, int32_t *flag, int32_t *nnz_a) {
+  int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  uint32_t cnt = g < nbins ? count[g] : 0u;
+  bool f = false;
+  if (cnt > 0) {
+    if (pkind < 0) f = true;
+    else if (pkind == US_P_SUM_GE_ABS) f = (int64_t)cnt >= thr;
+    else {
+      int64_t cap;
+      if (gkind == G_DIAG) {
+        int64_t off = g - (nrows - 1);
+        int64_t hi = nrows < ncols - off ? nrows : ncols - off, lo = off < 0 ? -off : 0;
+        cap = hi > lo ? hi - lo : 0;
+      } else cap = gkind == G_ROW ? ncols : nrows;
+      f = den * (int64_t)cnt >= num * cap;
+    }
+  }
+  if (g < nbins) flag[g] = f ? 1 : 0;
+  uint32_t mine = f ? cnt : 0u;
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) mine += __shfl_xor(mine, d);
+  if (lane_id() == 0 && mine) atomicAdd(nnz_a, (int32_t)mine);
 }
 
 __global__ __launch_bounds__(256) void diag_offsets_kernel(const int32_t *flag, const int32_t *pos, int64_t nbins,
@@ -327,19 +356,13 @@ __global__ __launch_bounds__(256) void dia_scatter_kernel(const int32_t *row, co
   slab[slot] = val[i];
 }
 
-static us_status convert_dia(Env &env, const us_coo &coo, const Plan &plan, const us_format_desc &desc,
-                             Flags *flags, us_formatted **out) {
+// DIA from per-diagonal flags (flags->scalar[1] already holds the number of flagged entries)
+static us_status dia_from_flags(Env &env, const us_coo &coo, const Plan &plan, const us_format_desc &desc,
+                                Flags *flags, const int32_t *flag, us_formatted **out) {
   const int64_t nbins = coo.nrows + coo.ncols - 1, n = coo.nnz;
   const int64_t L = plan.swapped ? coo.ncols : coo.nrows;
-  uint32_t *count = env.temp<uint32_t>(nbins);
-  int32_t *flag = env.temp<int32_t>(nbins), *pos = env.temp<int32_t>(nbins);
+  int32_t *pos = env.temp<int32_t>(nbins);
   if (!env.ok()) return env.status;
-  fill_u32(env, count, nbins, 0);
-  if (n > 0)
-    US_LAUNCH(env, "diag_hist", 8.0 * n, diag_hist_kernel, ceil_div<int64_t>(n, 256), 256, coo.row, coo.col, n,
-              (uint32_t)coo.nrows, (uint32_t)coo.ncols, count, flags);
-  US_LAUNCH(env, "diag_flag", 8.0 * nbins, diag_flag_nonempty_kernel, ceil_div<int64_t>(nbins, 256), 256,
-            (const uint32_t *)count, nbins, flag);
   exclusive_scan_i32(env, flag, pos, nbins, &flags->scalar[0]);
   Flags h{};
   if (!read_flags(env, flags, &h)) return env.status;
@@ -348,25 +371,53 @@ static us_status convert_dia(Env &env, const us_coo &coo, const Plan &plan, cons
   if (ndiag * L >= (1ll << 31)) return US_ERR_OVERFLOW;
   us_formatted *f = new us_formatted();
   f->desc = desc; f->pattern = P_DIA; f->swapped = plan.swapped;
-  f->nrows = coo.nrows; f->ncols = coo.ncols; f->nnz = n;
+  f->nrows = coo.nrows; f->ncols = coo.ncols; f->nnz = h.scalar[1];
   f->nlevels = 2;
   f->level[0].idx = env.owned<int32_t>(ndiag); f->level[0].nidx = ndiag;
   f->level[1].size = L;
   f->val = env.owned<float>(ndiag * L); f->nval = ndiag * L; f->nmajor = ndiag;
-  uint32_t *bitmap = env.temp<uint32_t>(ceil_div<int64_t>(ndiag * L, 32) + 1);
+  const int64_t nwords = ceil_div<int64_t>(ndiag * L, 32) + 1;
+  uint32_t *bitmap = env.temp<uint32_t>(nwords);
   if (!env.ok()) { free_formatted(env, f); return env.status; }
   fill_u32(env, (uint32_t *)f->val, ndiag * L, 0u);
-  fill_u32(env, bitmap, ceil_div<int64_t>(ndiag * L, 32) + 1, 0u);
-  US_LAUNCH(env, "diag_offsets", 8.0 * nbins, diag_offsets_kernel, ceil_div<int64_t>(nbins, 256), 256,
-            (const int32_t *)flag, (const int32_t *)pos, nbins, (int32_t)coo.nrows, f->level[0].idx);
+  fill_u32(env, bitmap, nwords, 0u);
+  US_LAUNCH(env, "diag_offsets", 8.0 * nbins, diag_offsets_kernel, ceil_div<int64_t>(nbins, 256), 256, flag,
+            (const int32_t *)pos, nbins, (int32_t)coo.nrows, f->level[0].idx);
   if (n > 0)
     US_LAUNCH(env, "dia_scatter", 16.0 * n, dia_scatter_kernel, ceil_div<int64_t>(n, 256), 256, coo.row, coo.col,
-              coo.val, n, (uint32_t)coo.nrows, (const int32_t *)flag, (const int32_t *)pos, L,
-              plan.swapped ? 1 : 0, f->val, bitmap, flags);
+              coo.val, n, (uint32_t)coo.nrows, flag, (const int32_t *)pos, L, plan.swapped ? 1 : 0, f->val, bitmap,
+              flags);
   if (!read_flags(env, flags, &h)) { free_formatted(env, f); return env.status; }
   if (flag_status(h) != US_OK) { free_formatted(env, f); return flag_status(h); }
   *out = f;
   return US_OK;
+}
+
+struct GroupCounts { uint32_t *count; int32_t *flag; int64_t nbins; };
+
+// histogram of the groups + predicate flags; pkind < 0 flags every non-empty group
+static GroupCounts group_flags(Env &env, const us_coo &coo, int gkind, int pkind, int64_t num, int64_t den,
+                               int64_t thr, Flags *flags) {
+  GroupCounts g{};
+  g.nbins = gkind == G_DIAG ? coo.nrows + coo.ncols - 1 : (gkind == G_ROW ? coo.nrows : coo.ncols);
+  g.count = env.temp<uint32_t>(g.nbins);
+  g.flag = env.temp<int32_t>(g.nbins);
+  if (!env.ok()) return g;
+  fill_u32(env, g.count, g.nbins, 0);
+  if (coo.nnz > 0)
+    US_LAUNCH(env, "group_hist", 8.0 * coo.nnz, group_hist_kernel, ceil_div<int64_t>(coo.nnz, 256), 256, coo.row,
+              coo.col, coo.nnz, gkind, (uint32_t)coo.nrows, (uint32_t)coo.ncols, g.count, flags);
+  US_LAUNCH(env, "group_flag", 8.0 * g.nbins, group_flag_kernel, ceil_div<int64_t>(g.nbins, 256), 256,
+            (const uint32_t *)g.count, g.nbins, gkind, pkind, num, den, thr, coo.nrows, coo.ncols, g.flag,
+            &flags->scalar[1]);
+  return g;
+}
+
+static us_status convert_dia(Env &env, const us_coo &coo, const Plan &plan, const us_format_desc &desc,
+                             Flags *flags, us_formatted **out) {
+  GroupCounts g = group_flags(env, coo, G_DIAG, -1, 0, 1, 0, flags);
+  if (!env.ok()) return env.status;
+  return dia_from_flags(env, coo, plan, desc, flags, g.flag, out);
 }
 
 // ------------------------------------------------------------------ BCSR
@@ -525,10 +576,219 @@ us_status convert_impl(Env &env, const us_coo &coo, const us_format_desc &desc, 
   return s;
 }
 
+// ------------------------------------------------------------------ decompose
+// entries whose group is flagged go to list A, the others to list B (order inside a list is
+// irrelevant: each part is put into canonical order by its conversion)
+__global__ __launch_bounds__(256) void partition_kernel(const int32_t *row, const int32_t *col, const float *val,
+                                                       int64_t n, int gkind, uint32_t nrows, const int32_t *flag,
+                                                       int32_t *ar, int32_t *ac, float *av, int32_t *br,
+                                                       int32_t *bc, float *bv, int32_t *cursors) {
+  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  bool valid = i < n;
+  uint32_t r = valid ? (uint32_t)row[i] : 0u, c = valid ? (uint32_t)col[i] : 0u;
+  float v = valid ? val[i] : 0.f;
+  bool to_a = valid && flag[group_bin(gkind, r, c, nrows)] != 0;
+  bool to_b = valid && !to_a;
+  const int lane = lane_id();
+  uint64_t ma = __ballot(to_a), mb = __ballot(to_b);
+  int32_t base_a = 0, base_b = 0;
+  if (lane == 0) {
+    if (ma && ar) base_a = atomicAdd(&cursors[0], (int32_t)__popcll(ma));
+    if (mb) base_b = atomicAdd(&cursors[1], (int32_t)__popcll(mb));
+  }
+  base_a = __shfl(base_a, 0); base_b = __shfl(base_b, 0);
+  if (to_a && ar) {
+    int32_t p = base_a + (int32_t)__popcll(ma & lanes_below());
+    ar[p] = (int32_t)r; ac[p] = (int32_t)c; av[p] = v;
+  }
+  if (to_b) {
+    int32_t p = base_b + (int32_t)__popcll(mb & lanes_below());
+    br[p] = (int32_t)r; bc[p] = (int32_t)c; bv[p] = v;
+  }
+}
+
+__global__ __launch_bounds__(256) void row_len_kernel(const int32_t *ptr, int64_t n, uint32_t *len) {
+  int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (g < n) len[g] = (uint32_t)(ptr[g + 1] - ptr[g]);
+}
+__global__ void pick_kernel(const uint32_t *sorted, int64_t at, int32_t *out) { *out = (int32_t)sorted[at]; }
+
+__global__ __launch_bounds__(256) void clipped_len_kernel(const int32_t *ptr, int64_t n, int64_t K, int32_t *out) {
+  int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (g < n) { int64_t l = ptr[g + 1] - ptr[g]; out[g] = (int32_t)(l < K ? l : K); }
+}
+
+// stable split of the sorted list by rank-in-row: rank < K -> part A, else part B
+__global__ __launch_bounds__(256) void rank_split_kernel(const int32_t *major, const int32_t *minor, const float *val,
+                                                        const int32_t *ptr, const int32_t *ptr_a, int64_t n,
+                                                        int64_t K, int32_t *ar, int32_t *ac, float *av, int32_t *br,
+                                                        int32_t *bc, float *bv) {
+  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  int32_t r = major[i];
+  int64_t rank = i - ptr[r];
+  if (rank < K) {
+    int64_t p = ptr_a[r] + rank;
+    ar[p] = r; ac[p] = minor[i]; av[p] = val[i];
+  } else {
+    int64_t p = (int64_t)(ptr[r] - ptr_a[r]) + (rank - K);
+    br[p] = r; bc[p] = minor[i]; bv[p] = val[i];
+  }
+}
+
+static bool row_major_family(const Plan &p) {
+  return !p.swapped && (p.pattern == P_COO || p.pattern == P_CSR || p.pattern == P_DCSR || p.pattern == P_ELL);
+}
+
+struct CooLists { int32_t *r = nullptr, *c = nullptr; float *v = nullptr; };
+static CooLists alloc_lists(Env &env, int64_t n) {
+  CooLists l;
+  l.r = env.owned<int32_t>(n); l.c = env.owned<int32_t>(n); l.v = env.owned<float>(n);
+  return l;
+}
+static void free_lists(Env &env, CooLists &l) {
+  env.free_raw(l.r); env.free_raw(l.c); env.free_raw(l.v);
+  l = CooLists();
+}
+
+static us_status decompose_sum(Env &env, const us_coo &coo, const Plan &pa, const us_format_desc &da, const Plan &pb,
+                               const us_format_desc &db, const us_predicate &pred, int gkind, us_formatted **oa,
+                               us_formatted **ob) {
+  Flags *flags = new_flags(env);
+  if (!env.ok()) return env.status;
+  GroupCounts g = group_flags(env, coo, gkind, pred.kind, pred.num, pred.den, pred.abs, flags);
+  Flags h{};
+  if (!read_flags(env, flags, &h)) return env.status;
+  if (flag_status(h) != US_OK) return flag_status(h);
+  const int64_t n = coo.nnz, na = h.scalar[1], nb = n - na;
+  const bool dia_direct = gkind == G_DIAG && pa.pattern == P_DIA;  // part A goes straight into the slab
+  CooLists la, lb = alloc_lists(env, nb);
+  if (!dia_direct) la = alloc_lists(env, na);
+  int32_t *cursors = env.temp<int32_t>(2);
+  us_status st = env.status;
+  if (st == US_OK) {
+    fill_u32(env, (uint32_t *)cursors, 2, 0u);
+    if (n > 0)
+      US_LAUNCH(env, "partition", 12.0 * n + 12.0 * (dia_direct ? nb : n), partition_kernel,
+                ceil_div<int64_t>(n, 256), 256, coo.row, coo.col, coo.val, n, gkind, (uint32_t)coo.nrows,
+                (const int32_t *)g.flag, la.r, la.c, la.v, lb.r, lb.c, lb.v, cursors);
+    st = env.status;
+  }
+  if (st == US_OK) {
+    if (dia_direct) st = dia_from_flags(env, coo, pa, da, flags, g.flag, oa);
+    else {
+      us_coo ca{coo.nrows, coo.ncols, na, la.r, la.c, la.v};
+      st = convert_with_plan(env, ca, pa, da, oa);
+    }
+  }
+  if (st == US_OK) {
+    us_coo cb{coo.nrows, coo.ncols, nb, lb.r, lb.c, lb.v};
+    st = convert_with_plan(env, cb, pb, db, ob);
+  }
+  env.sync();
+  free_lists(env, la);
+  free_lists(env, lb);
+  return st;
+}
+
+void sort_u32(Env &env, const uint32_t *key, int64_t n, int bits, uint32_t *out);
+
+static us_status decompose_rank(Env &env, const us_coo &coo, const Plan &pa, const us_format_desc &da, const Plan &pb,
+                                const us_format_desc &db, const us_predicate &pred, us_formatted **oa,
+                                us_formatted **ob) {
+  Flags *flags = new_flags(env);
+  const int64_t n = coo.nnz, nrows = coo.nrows;
+  int32_t *major = env.temp<int32_t>(n), *minor = env.temp<int32_t>(n);
+  float *val = env.temp<float>(n);
+  int32_t *ptr = env.temp<int32_t>(nrows + 1), *ptr_a = env.temp<int32_t>(nrows + 1), *clip = env.temp<int32_t>(nrows + 1);
+  if (!env.ok()) return env.status;
+  SortOut so{};
+  so.major = major; so.minor = minor; so.val = val;
+  sort_coo(env, coo.row, coo.col, coo.val, n, rowcol_keyspec(coo, false), so, flags);
+  if (n > 1)
+    US_LAUNCH(env, "check_unique", 8.0 * n, check_unique_unpacked_kernel, ceil_div<int64_t>(n, 256), 256,
+              (const int32_t *)major, (const int32_t *)minor, n, flags);
+  lower_bound_ptr(env, major, n, nrows, ptr);
+  Flags h{};
+  int64_t K = pred.abs;
+  if (pred.kind == US_P_RANK_LT_PERCENTILE) {
+    // nearest-rank percentile of the row lengths over all rows: sort the lengths, pick one
+    uint32_t *len = env.temp<uint32_t>(nrows), *slen = env.temp<uint32_t>(nrows);
+    if (!env.ok()) return env.status;
+    US_LAUNCH(env, "row_len", 8.0 * nrows, row_len_kernel, ceil_div<int64_t>(nrows, 256), 256, (const int32_t *)ptr,
+              nrows, len);
+    const int64_t maxlen = n < coo.ncols ? n : coo.ncols;
+    sort_u32(env, len, nrows, bits_for((uint64_t)maxlen), slen);
+    int64_t k = (pred.num * nrows + pred.den - 1) / pred.den;
+    if (k < 1) k = 1;
+    if (k > nrows) k = nrows;
+    US_LAUNCH(env, "pick", 8.0, pick_kernel, 1, 1, (const uint32_t *)slen, k - 1, &flags->scalar[2]);
+    if (!read_flags(env, flags, &h)) return env.status;
+    if (flag_status(h) != US_OK) return flag_status(h);
+    K = h.scalar[2];
+  }
+  US_LAUNCH(env, "clipped_len", 8.0 * nrows, clipped_len_kernel, ceil_div<int64_t>(nrows, 256), 256,
+            (const int32_t *)ptr, nrows, K, clip);
+  exclusive_scan_i32(env, clip, ptr_a, nrows, &flags->scalar[1]);
+  if (!read_flags(env, flags, &h)) return env.status;
+  if (flag_status(h) != US_OK) return flag_status(h);
+  const int64_t na = h.scalar[1], nb = n - na;
+  CooLists la = alloc_lists(env, na), lb = alloc_lists(env, nb);
+  us_status st = env.status;
+  if (st == US_OK && n > 0) {
+    US_LAUNCH(env, "rank_split", 16.0 * n + 12.0 * n, rank_split_kernel, ceil_div<int64_t>(n, 256), 256,
+              (const int32_t *)major, (const int32_t *)minor, (const float *)val, (const int32_t *)ptr,
+              (const int32_t *)ptr_a, n, K, la.r, la.c, la.v, lb.r, lb.c, lb.v);
+    st = env.status;
+  }
+  auto finish_part = [&](const Plan &p, const us_format_desc &d, CooLists &l, int64_t cnt, us_formatted **o) {
+    if (row_major_family(p)) {   // the list is already in (row, col) order: no second sort
+      Flags *fl = new_flags(env);
+      if (!env.ok()) return env.status;
+      us_status s = build_from_sorted(env, p, d, coo.nrows, coo.ncols, cnt, l.r, l.c, l.v, fl, o);
+      l = CooLists();  // ownership moved
+      return s;
+    }
+    us_coo c{coo.nrows, coo.ncols, cnt, l.r, l.c, l.v};
+    return convert_with_plan(env, c, p, d, o);
+  };
+  if (st == US_OK) st = finish_part(pa, da, la, na, oa);
+  if (st == US_OK) st = finish_part(pb, db, lb, nb, ob);
+  env.sync();
+  free_lists(env, la);
+  free_lists(env, lb);
+  return st;
+}
+
 us_status decompose_impl(Env &env, const us_coo &coo, const us_format_desc &da, const us_format_desc &db,
                          const us_predicate &pred, us_formatted **oa, us_formatted **ob) {
   *oa = *ob = nullptr;
-  return US_ERR_UNSUPPORTED_DESC;
+  us_status s = validate_coo(coo);
+  if (s != US_OK) return s;
+  Plan pa, pb;
+  if (!match_desc(da, &pa) || !match_desc(db, &pb)) return US_ERR_UNSUPPORTED_DESC;
+  if ((pa.pattern == P_ELL && pa.swapped) || (pb.pattern == P_ELL && pb.swapped)) return US_ERR_UNSUPPORTED_DESC;
+  if (pred.ngroup != 1) return US_ERR_UNSUPPORTED_DESC;
+  const us_expr &ge = pred.group[0];
+  int gkind = aff(ge, -1, 1) ? G_DIAG : aff(ge, 1, 0) ? G_ROW : aff(ge, 0, 1) ? G_COL : -1;
+  if (gkind < 0) return US_ERR_UNSUPPORTED_DESC;
+  if (pred.kind == US_P_SUM_GE_ABS || pred.kind == US_P_SUM_GE_FRAC_OF_CAPACITY) {
+    if (pred.kind == US_P_SUM_GE_FRAC_OF_CAPACITY && (pred.den <= 0 || pred.num < 0)) return US_ERR_SHAPE;
+    s = decompose_sum(env, coo, pa, da, pb, db, pred, gkind, oa, ob);
+  } else if (pred.kind == US_P_RANK_LT_ABS || pred.kind == US_P_RANK_LT_PERCENTILE) {
+    if (gkind != G_ROW) return US_ERR_UNSUPPORTED_DESC;
+    if (pred.kind == US_P_RANK_LT_PERCENTILE && (pred.den <= 0 || pred.num < 0 || pred.num > pred.den)) return US_ERR_SHAPE;
+    if (pred.kind == US_P_RANK_LT_ABS && pred.abs < 0) return US_ERR_SHAPE;
+    s = decompose_rank(env, coo, pa, da, pb, db, pred, oa, ob);
+  } else {
+    return US_ERR_UNSUPPORTED_DESC;
+  }
+  if (s == US_OK && !env.ok()) s = env.status;
+  if (s != US_OK) {
+    if (*oa) { free_formatted(env, *oa); *oa = nullptr; }
+    if (*ob) { free_formatted(env, *ob); *ob = nullptr; }
+  }
+  return s;
 }
 
 }  // namespace us

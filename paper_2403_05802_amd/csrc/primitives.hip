@@ -398,6 +398,18 @@ void sort_coo(Env &env, const int32_t *row, const int32_t *col, const float *val
   else sort_generic<uint64_t>(env, row, col, nullptr, val, nnz, ks, out, flags_dev);
 }
 
+// ascending sort of 32-bit keys (no payload of interest)
+void sort_u32(Env &env, const uint32_t *key, int64_t n, int bits, uint32_t *out) {
+  if (n <= 0) return;
+  KeySpec ks{};
+  ks.total_bits = bits;
+  float *dummy_in = env.temp<float>(n), *dummy_out = env.temp<float>(n);
+  if (!env.ok()) return;
+  SortOut so{};
+  so.key32 = out; so.val = dummy_out;
+  sort_generic<uint32_t>(env, nullptr, nullptr, key, dummy_in, n, ks, so, nullptr);
+}
+
 void sort_keys(Env &env, const uint64_t *key, const float *val, int64_t nnz, const KeySpec &ks,
                const SortOut &out, Flags *flags_dev) {
   sort_generic<uint64_t>(env, nullptr, nullptr, key, val, nnz, ks, out, flags_dev);

@@ -106,8 +106,8 @@ __global__ __launch_bounds__(256) void csr_spmm_kernel(const int32_t *ptr, const
 }
 
 __global__ __launch_bounds__(256) void dia_spmm_kernel(const int32_t *off, const float *val, int64_t ndiag,
-                                                      int64_t nrows, int64_t ncols, const float *X, int64_t N,
-                                                      int64_t ldx, float *Y, int64_t ldy, int accumulate) {
+                                                      int64_t nrows, int64_t ncols, int by_col, const float *X,
+                                                      int64_t N, int64_t ldx, float *Y, int64_t ldy, int accumulate) {
   const int64_t i = (int64_t)blockIdx.x * 4 + wave_id();
   if (i >= nrows) return;
   const int64_t c = (int64_t)blockIdx.y * 64 + lane_id();
@@ -115,7 +115,7 @@ __global__ __launch_bounds__(256) void dia_spmm_kernel(const int32_t *off, const
   float s = accumulate ? Y[i * ldy + c] : 0.f;
   for (int64_t k = 0; k < ndiag; ++k) {
     int64_t j = i + off[k];
-    if (j >= 0 && j < ncols) s += val[k * nrows + i] * X[j * ldx + c];
+    if (j >= 0 && j < ncols) s += val[k * (by_col ? ncols : nrows) + (by_col ? j : i)] * X[j * ldx + c];
   }
   Y[i * ldy + c] = s;
 }
@@ -202,7 +202,20 @@ __global__ __launch_bounds__(256) void coo_spmm_fixup_kernel(const int32_t *carr
   Y[(int64_t)r * ldy + c] += s;
 }
 
-// scatter form for the column-major layouts (CSC / DCSC / column-major COO)
+// scatter form for CSC / DCSC: one wavefront per (stored column, 64 columns of X)
+__global__ __launch_bounds__(256) void csc_spmm_atomic_kernel(const int32_t *ptr, const int32_t *idx, const float *val,
+                                                             const int32_t *col_ids, int64_t ncols_stored,
+                                                             const float *X, int64_t N, int64_t ldx, float *Y,
+                                                             int64_t ldy) {
+  const int64_t j = (int64_t)blockIdx.x * 4 + wave_id();
+  if (j >= ncols_stored) return;
+  const int64_t cc = (int64_t)blockIdx.y * 64 + lane_id();
+  if (cc >= N) return;
+  const float xv = X[(int64_t)(col_ids ? col_ids[j] : j) * ldx + cc];
+  for (int e = ptr[j]; e < ptr[j + 1]; ++e) atomicAdd(&Y[(int64_t)idx[e] * ldy + cc], val[e] * xv);
+}
+
+// scatter form for the column-major COO
 __global__ __launch_bounds__(256) void coo_spmm_atomic_kernel(const int32_t *r, const int32_t *c, const float *val,
                                                              int64_t nnz, const float *X, int64_t N, int64_t ldx,
                                                              float *Y, int64_t ldy) {
@@ -253,8 +266,19 @@ us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, 
       return env.status;
     case P_CSR:
     case P_DCSR: {
-      if (A.swapped) break;
       const bool d = A.pattern == P_DCSR;
+      if (A.swapped) {
+        if (!accumulate) zero_rows(env, Y, A.nrows, N, ldy);
+        if (env.ok() && A.nmajor > 0) {
+          LaunchScope ls(env, "spmm_csc", 8.0 * A.nnz + xy);
+          hipLaunchKernelGGL(csc_spmm_atomic_kernel, dim3((unsigned)ceil_div<int64_t>(A.nmajor, 4), (unsigned)ncb),
+                             dim3(256), 0, env.stream, (const int32_t *)A.level[1].ptr,
+                             (const int32_t *)A.level[1].idx, (const float *)A.val,
+                             (const int32_t *)(d ? A.level[0].idx : nullptr), A.nmajor, X, N, ldx, Y, ldy);
+          env.check(hipGetLastError());
+        }
+        return env.status;
+      }
       if (d && !accumulate) zero_rows(env, Y, A.nrows, N, ldy);
       if (env.ok() && A.nmajor > 0) {
         LaunchScope ls(env, "spmm_csr", 8.0 * A.nnz + xy);
@@ -267,12 +291,11 @@ us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, 
       return env.status;
     }
     case P_DIA:
-      if (A.swapped) break;
       if (env.ok()) {
         LaunchScope ls(env, "spmm_dia", 4.0 * A.nval + xy);
         hipLaunchKernelGGL(dia_spmm_kernel, dim3((unsigned)ceil_div<int64_t>(A.nrows, 4), (unsigned)ncb), dim3(256), 0,
                            env.stream, (const int32_t *)A.level[0].idx, (const float *)A.val, A.nmajor, A.nrows, A.ncols,
-                           X, N, ldx, Y, ldy, acc);
+                           A.swapped ? 1 : 0, X, N, ldx, Y, ldy, acc);
         env.check(hipGetLastError());
       }
       return env.status;

@@ -157,17 +157,29 @@ static void spmv_compressed(Env &env, const us_formatted &A, const int32_t *ptr,
 }
 
 // ------------------------------------------------------------------ DIA: y[i] (+)= sum_k val[k*nrows+i] * x[i+off_k]
+// (the DIA variant keeps the slab indexed by column: val[k*ncols + j], j = i + off_k)
 __global__ __launch_bounds__(256) void dia_spmv_kernel(const int32_t *off, const float *val, int64_t ndiag,
-                                                      int64_t nrows, int64_t ncols, const float *x, float *y,
-                                                      int accumulate) {
+                                                      int64_t nrows, int64_t ncols, int by_col, const float *x,
+                                                      float *y, int accumulate) {
   int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= nrows) return;
   float s = accumulate ? y[i] : 0.f;
+  const int64_t L = by_col ? ncols : nrows;
   for (int64_t k = 0; k < ndiag; ++k) {
     int64_t j = i + off[k];
-    if (j >= 0 && j < ncols) s += val[k * nrows + i] * x[j];
+    if (j >= 0 && j < ncols) s += val[k * L + (by_col ? j : i)] * x[j];
   }
   y[i] = s;
+}
+
+// column-major compressed layouts (CSC / DCSC): scatter form, one thread per stored column
+__global__ __launch_bounds__(256) void csc_spmv_atomic_kernel(const int32_t *ptr, const int32_t *idx, const float *val,
+                                                             const int32_t *col_ids, int64_t ncols_stored,
+                                                             const float *x, float *y) {
+  int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (j >= ncols_stored) return;
+  const float xj = x[col_ids ? col_ids[j] : j];
+  for (int e = ptr[j]; e < ptr[j + 1]; ++e) atomicAdd(&y[idx[e]], val[e] * xj);
 }
 
 // generic scatter form used by the layouts whose leaves are not grouped by output row
@@ -213,19 +225,26 @@ __global__ __launch_bounds__(256) void bcsr_spmv_kernel(const int32_t *ptr, cons
 us_status spmv_impl(Env &env, const us_formatted &A, const float *x, float *y, bool accumulate) {
   switch (A.pattern) {
     case P_CSR:
-      if (A.swapped) break;
+    case P_DCSR:
+      if (A.swapped) {
+        if (!accumulate) fill_u32(env, (uint32_t *)y, A.nrows, 0u);
+        if (A.nmajor > 0)
+          US_LAUNCH(env, "spmv_csc", 16.0 * A.nnz, csc_spmv_atomic_kernel, ceil_div<int64_t>(A.nmajor, 256), 256,
+                    (const int32_t *)A.level[1].ptr, (const int32_t *)A.level[1].idx, (const float *)A.val,
+                    (const int32_t *)(A.pattern == P_DCSR ? A.level[0].idx : nullptr), A.nmajor, x, y);
+        return env.status;
+      }
+      if (A.pattern == P_DCSR) {
+        if (!accumulate) fill_u32(env, (uint32_t *)y, A.nrows, 0u);
+        spmv_compressed(env, A, A.level[1].ptr, A.level[1].idx, A.val, A.level[0].idx, A.nmajor, A.nnz, x, y, true);
+        return env.status;
+      }
       spmv_compressed(env, A, A.level[1].ptr, A.level[1].idx, A.val, nullptr, A.nrows, A.nnz, x, y, accumulate);
       return env.status;
-    case P_DCSR:
-      if (A.swapped) break;
-      if (!accumulate) fill_u32(env, (uint32_t *)y, A.nrows, 0u);
-      spmv_compressed(env, A, A.level[1].ptr, A.level[1].idx, A.val, A.level[0].idx, A.nmajor, A.nnz, x, y, true);
-      return env.status;
     case P_DIA:
-      if (A.swapped) break;
       US_LAUNCH(env, "spmv_dia", 4.0 * A.nval + 8.0 * A.nrows + 4.0 * A.ncols, dia_spmv_kernel,
                 ceil_div<int64_t>(A.nrows, 256), 256, (const int32_t *)A.level[0].idx, (const float *)A.val,
-                A.nmajor, A.nrows, A.ncols, x, y, accumulate ? 1 : 0);
+                A.nmajor, A.nrows, A.ncols, A.swapped ? 1 : 0, x, y, accumulate ? 1 : 0);
       return env.status;
     case P_ELL:
       US_LAUNCH(env, "spmv_ell", 8.0 * A.nval + 8.0 * A.nrows, ell_spmv_kernel, ceil_div<int64_t>(A.nrows, 256), 256,
