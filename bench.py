@@ -1,0 +1,251 @@
+#!/usr/bin/env python3
+"""Benchmark of the format-customization hot path on one MI355X.
+
+One step = one pass of the whole path over the headline workload (BASELINE config 2:
+1,048,576^2 power-law matrix, ~16.8 M nnz, unsorted COO resident in HBM):
+COO->CSR, COO->DCSR, SpMV over each.  The other four workloads are run as well and
+reported under "workloads" (DIA+CSR and ELL+COO decompositions, BCSR, SpMM).
+
+Prints ONE JSON line.  `value` = matrix non-zeros pushed through the whole step per second.
+Per-kernel figures come from HIP events recorded by the library around every kernel launch
+on its own stream during the timed steps (us_profile_*).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix peak, published
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--only-headline", action="store_true", help="skip the four other workloads")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def timed(torch, fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps * 1e3
+
+
+def kernel_table(report):
+    rows = []
+    for e in report:
+        avg_ms = e["total_ms"] / e["launches"]
+        per_launch = e["alg_bytes"] / e["launches"]
+        rows.append({"kernel": e["kernel"], "launches": e["launches"], "total_ms": round(e["total_ms"], 4),
+                     "avg_us": round(avg_ms * 1e3, 2), "alg_bytes_per_launch": per_launch,
+                     "gbps": round(per_launch / (avg_ms * 1e-3) / 1e9, 1) if avg_ms > 0 else None})
+    rows.sort(key=lambda r: -r["total_ms"])
+    return rows
+
+
+def profile_of(B, torch, ctx, fn, steps):
+    ctx.enable_profile()
+    ctx.profile_reset()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    rep = ctx.profile_report()
+    ctx.disable_profile()
+    for e in rep:
+        e["launches_per_step"] = e["launches"] / steps
+    return rep
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2403_05802_amd import binding as B
+    from paper_2403_05802_amd import workloads as W
+    B.lib()  # fails loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    ctx = B.Context("cuda:0")
+    up = lambda a: torch.from_numpy(a).to(dev)
+    K, Wm = args.steps, args.warmup
+    CSR, DCSR = B.us_desc_preset(B.US_F_CSR), B.us_desc_preset(B.US_F_DCSR)
+    out = {}
+
+    # ------------------------------------------------------------------ headline: config 2
+    m = W.cfg2_powerlaw()
+    r, c, v = up(m.row), up(m.col), up(m.val)
+    x = up(W.dense_operand(2, m.ncols))
+    y = torch.empty(m.nrows, device=dev)
+    nnz = m.nnz
+
+    def step():
+        a = B.us_convert(ctx, m.nrows, m.ncols, r, c, v, CSR)
+        b = B.us_convert(ctx, m.nrows, m.ncols, r, c, v, DCSR)
+        B.us_spmv(ctx, a, x, y)
+        B.us_spmv(ctx, b, x, y)
+        a.free(); b.free()
+
+    ms_plain = timed(torch, step, max(3, K // 4), Wm)          # without event recording
+    ctx.enable_profile(); ctx.profile_reset()
+    for _ in range(Wm):
+        step()
+    torch.cuda.synchronize(); ctx.profile_reset()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        step()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) / K * 1e3
+    rep = ctx.profile_report()
+    ctx.disable_profile()
+    table = kernel_table(rep)
+    dom = table[0]
+    roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["gbps"], "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(dom["gbps"] / HBM_PEAK_GBS, 4),
+                "avg_launch_us": dom["avg_us"], "alg_bytes_per_launch": dom["alg_bytes_per_launch"],
+                "traffic": None}
+
+    # separate timings of the pieces (each its own timed loop)
+    fa = B.us_convert(ctx, m.nrows, m.ncols, r, c, v, CSR)
+    fb = B.us_convert(ctx, m.nrows, m.ncols, r, c, v, DCSR)
+    ms_csr = timed(torch, lambda: B.us_convert(ctx, m.nrows, m.ncols, r, c, v, CSR).free(), K, 1)
+    ms_dcsr = timed(torch, lambda: B.us_convert(ctx, m.nrows, m.ncols, r, c, v, DCSR).free(), K, 1)
+    ms_spmv = timed(torch, lambda: B.us_spmv(ctx, fa, x, y), K * 5, 3)
+    ms_spmv_d = timed(torch, lambda: B.us_spmv(ctx, fb, x, y), K * 5, 3)
+    conv_bytes = 20.0 * nnz + 4.0 * (m.nrows + 1)
+    spmv_bytes = 8.0 * nnz + 4.0 * (m.nrows + 1) + 8.0 * m.nrows
+    headline = {
+        "nnz": nnz, "nrows": m.nrows,
+        "coo_to_csr": {"ms": round(ms_csr, 4), "mnnz_s": round(nnz / ms_csr / 1e3, 1),
+                       "useful_gbps": round(conv_bytes / ms_csr / 1e6, 1),
+                       "useful_frac_of_hbm": round(conv_bytes / ms_csr / 1e6 / HBM_PEAK_GBS, 4)},
+        "coo_to_dcsr": {"ms": round(ms_dcsr, 4), "mnnz_s": round(nnz / ms_dcsr / 1e3, 1)},
+        "spmv_csr": {"ms": round(ms_spmv, 4), "gflop_s": round(2.0 * nnz / ms_spmv / 1e6, 1),
+                     "useful_gbps": round(spmv_bytes / ms_spmv / 1e6, 1),
+                     "useful_frac_of_hbm": round(spmv_bytes / ms_spmv / 1e6 / HBM_PEAK_GBS, 4)},
+        "spmv_dcsr": {"ms": round(ms_spmv_d, 4), "gflop_s": round(2.0 * nnz / ms_spmv_d / 1e6, 1)},
+        "ms_per_step_without_event_recording": round(ms_plain, 4),
+        "kernels": table,
+    }
+    fa.free(); fb.free()
+
+    # ------------------------------------------------------------------ CPU baseline: the oracle, bounded sample
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import unisparse_oracle as O
+        ns = min(nnz, 3_000_000)
+        sr, sc, sv = m.row[:ns], m.col[:ns], m.val[:ns]   # the list is randomly permuted: a uniform sample
+        xs = W.dense_operand(2, m.ncols)
+        t0 = time.perf_counter()
+        oa = O.convert(m.nrows, m.ncols, sr, sc, sv, O.CSR())
+        ob = O.convert(m.nrows, m.ncols, sr, sc, sv, O.DCSR())
+        O.spmv(oa, xs); O.spmv(ob, xs)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(ns / dt / 1e6, 3), "unit": "Mnnz/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {ns} of the {nnz} randomly ordered entries of config 2 (same shape), same step: "
+                         f"COO->CSR, COO->DCSR, SpMV over each; {dt:.1f} s"}
+        del oa, ob
+    del r, c, v, m
+    torch.cuda.empty_cache()
+
+    # ------------------------------------------------------------------ the other workloads
+    if not args.only_headline:
+        out["workloads"] = other_workloads(B, W, torch, ctx, up, max(3, K // 2), 2)
+
+    line = {
+        "metric": "conversion Mnnz/s + SpMV GFLOP/s; achieved HBM GB/s as % of MI355X peak",
+        "value": round(nnz / ms_step / 1e3, 1), "unit": "Mnnz/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32 indices / u64 keys / f32 values",
+        "data": "synthetic",
+        "config": {"workload": "config 2: 1,048,576^2 fp32, Zipf(1.8) row lengths 1..20000, uniform columns, "
+                               f"{nnz} nnz, unsorted COO in HBM; step = COO->CSR + COO->DCSR + SpMV over each"},
+        "conversion_mnnz_s": headline["coo_to_csr"]["mnnz_s"],
+        "spmv_gflop_s": headline["spmv_csr"]["gflop_s"],
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "headline": headline,
+    }
+    line.update(out)
+    print(json.dumps(line))
+
+
+def other_workloads(B, W, torch, ctx, up, K, Wm):
+    """Configs 1, 3, 4, 5: conversion / decomposition and the product each names."""
+    dev = torch.device("cuda:0")
+    res = {}
+    E = B.expr
+
+    def run(name, m, conv, prod, flops, conv_bytes):
+        r, c, v = up(m.row), up(m.col), up(m.val)
+        parts = conv(r, c, v)
+        ms_conv = timed(torch, lambda: [p.free() for p in conv(r, c, v)], K, Wm)
+        ms_prod = timed(torch, lambda: prod(parts), K * 2, Wm)
+        rep = profile_of(B, torch, ctx, lambda: ([p.free() for p in conv(r, c, v)], prod(parts)), 3)
+        res[name] = {"nnz": m.nnz, "convert_ms": round(ms_conv, 4), "convert_mnnz_s": round(m.nnz / ms_conv / 1e3, 1),
+                     "convert_useful_gbps": round(conv_bytes(parts) / ms_conv / 1e6, 1),
+                     "product_ms": round(ms_prod, 4), "product_gflop_s": round(flops / ms_prod / 1e6, 1),
+                     "kernels": kernel_table(rep)[:8]}
+        for p in parts:
+            p.free()
+        del r, c, v
+        torch.cuda.empty_cache()
+
+    CSR, COO = B.us_desc_preset(B.US_F_CSR), B.us_desc_preset(B.US_F_COO)
+    # config 1
+    m = W.cfg1_uniform()
+    x = up(W.dense_operand(1, m.ncols)); y = torch.empty(m.nrows, device=dev)
+    run("config1_csr_spmv", m, lambda r, c, v: [B.us_convert(ctx, m.nrows, m.ncols, r, c, v, CSR)],
+        lambda p: B.us_spmv(ctx, p[0], x, y), 2.0 * m.nnz, lambda p: 20.0 * m.nnz + 4.0 * m.nrows)
+    # config 3
+    m = W.cfg3_banded()
+    x = up(W.dense_operand(3, m.ncols)); y = torch.empty(m.nrows, device=dev)
+    DIA = B.us_desc_preset(B.US_F_DIA)
+    pd = B.make_predicate([E(B.US_E_AFFINE, -1, 1)], B.US_P_SUM_GE_FRAC_OF_CAPACITY, 9, 10)
+
+    def prod3(p):
+        B.us_spmv(ctx, p[0], x, y); B.us_spmv(ctx, p[1], x, y, accumulate=True)
+    run("config3_dia_csr_spmv", m, lambda r, c, v: list(B.us_decompose(ctx, m.nrows, m.ncols, r, c, v, DIA, CSR, pd)),
+        prod3, 2.0 * m.nnz,
+        lambda p: 12.0 * m.nnz + 4.0 * p[0].val().numel() + 8.0 * p[1].nnz + 4.0 * m.nrows)
+    # config 4
+    m = W.cfg4_blockfem()
+    X = up(W.dense_operand(4, (m.ncols, 64))); Y = torch.empty(m.nrows, 64, device=dev)
+    BC = B.us_desc_preset(B.US_F_BCSR, 4, 4)
+    run("config4_bcsr_spmm64", m, lambda r, c, v: [B.us_convert(ctx, m.nrows, m.ncols, r, c, v, BC)],
+        lambda p: B.us_spmm(ctx, p[0], X, Y), 2.0 * m.nnz * 64,
+        lambda p: 12.0 * m.nnz + 4.0 * p[0].val().numel() + 4.0 * p[0].idx(1).numel())
+    del X, Y
+    # config 5
+    m = W.cfg5_powerlaw_local()
+    X = up(W.dense_operand(5, (m.ncols, 128))); Y = torch.empty(m.nrows, 128, device=dev)
+    ELL = B.us_desc_preset(B.US_F_ELL)
+    pr = B.make_predicate([E(B.US_E_AFFINE, 1, 0)], B.US_P_RANK_LT_PERCENTILE, 9, 10)
+
+    def prod5(p):
+        B.us_spmm(ctx, p[0], X, Y); B.us_spmm(ctx, p[1], X, Y, accumulate=True)
+    run("config5_ell_coo_spmm128", m,
+        lambda r, c, v: list(B.us_decompose(ctx, m.nrows, m.ncols, r, c, v, ELL, COO, pr)), prod5,
+        2.0 * m.nnz * 128, lambda p: 12.0 * m.nnz + 8.0 * p[0].val().numel() + 12.0 * p[1].nnz)
+    return res
+
+
+if __name__ == "__main__":
+    main()
