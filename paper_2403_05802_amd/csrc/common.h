@@ -106,6 +106,9 @@ struct us_formatted {
   // derived sizes
   int64_t nmajor = 0;   // CSR: rows (cols if swapped); DCSR: stored rows; DIA: ndiag; BCSR: block rows; ELL: K
   int64_t bh = 1, bw = 1, nblk = 0;
+  // CSR / DCSR: where every SpMV tile starts on the merge path of row ends and non-zeros
+  // (rows consumed before step t * tile), computed once at conversion
+  int32_t *mp_split = nullptr; int64_t mp_tiles = 0;
   // scratch for the compute kernels (partial sums of rows cut by a tile boundary); grown on
   // demand by ensure_workspace and released by us_free.  One compute call at a time per tensor.
   mutable void *ws = nullptr; mutable size_t ws_bytes = 0;
@@ -118,10 +121,11 @@ struct Flags {
   int32_t index_range;  // != 0: some coordinate out of range
   int32_t duplicate;    // != 0: two equal keys
   int32_t ell_overflow; // != 0: an entry's rank >= fixed ELL width
-  int32_t scalar[5];    // data-dependent sizes (nnr, ndiag, nblk, K, nnz_a ...)
+  int32_t sort_abort;   // != 0: a look-back wait in the sort gave up (reported as US_ERR_HIP)
+  int32_t scalar[4];    // data-dependent sizes (nnr, ndiag, nblk, K, nnz_a ...)
 };
 
-// primitives.hip
+// primitives.hip / sort.hip
 void fill_u32(Env &env, uint32_t *p, uint64_t n, uint32_t v);
 void exclusive_scan_i32(Env &env, const int32_t *in, int32_t *out, int64_t n, int32_t *total_dev);
 // in-place exclusive scan of nb per-tile sums by one workgroup; grand total to *total_dev
@@ -147,7 +151,9 @@ struct SortOut {
 };
 void sort_coo(Env &env, const int32_t *row, const int32_t *col, const float *val, int64_t nnz,
               const KeySpec &ks, const SortOut &out, Flags *flags_dev);
-// sort pre-built 64-bit keys (used for the remainder part of a decomposition)
+// ascending sort of 32-bit keys
+void sort_u32(Env &env, const uint32_t *key, int64_t n, int bits, uint32_t *out, Flags *flags_dev);
+// sort pre-built 64-bit keys
 void sort_keys(Env &env, const uint64_t *key, const float *val, int64_t nnz, const KeySpec &ks,
                const SortOut &out, Flags *flags_dev);
 
@@ -161,6 +167,7 @@ void free_formatted(Env &env, us_formatted *f);
 void *ensure_workspace(Env &env, const us_formatted &A, size_t bytes);
 
 // spmv.hip / spmm.hip
+void spmv_prepare(Env &env, us_formatted *f);  // fills mp_split for row-major CSR / DCSR
 us_status spmv_impl(Env &env, const us_formatted &A, const float *x, float *y, bool accumulate);
 us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, int64_t ldx, float *Y,
                     int64_t ldy, bool accumulate);

@@ -127,6 +127,7 @@ static bool read_flags(Env &env, Flags *dev, Flags *host) {
 }
 
 static us_status flag_status(const Flags &h) {
+  if (h.sort_abort) return US_ERR_HIP;
   if (h.index_range) return US_ERR_INDEX_RANGE;
   if (h.duplicate) return US_ERR_DUPLICATE;
   if (h.ell_overflow) return US_ERR_SHAPE;
@@ -141,6 +142,7 @@ void free_formatted(Env &env, us_formatted *f) {
   }
   env.free_raw(f->val);
   env.free_raw(f->ws);
+  env.free_raw(f->mp_split);
   delete f;
 }
 
@@ -222,6 +224,7 @@ static us_status build_from_sorted(Env &env, const Plan &plan, const us_format_d
     f->level[1].idx = minor; f->level[1].nidx = nnz;
     f->val = val; f->nval = nnz; f->nmajor = nmaj;
     minor_loose = val_loose = false;
+    spmv_prepare(env, f);
     return finish(flags_ok(&h));
   }
 
@@ -245,6 +248,7 @@ static us_status build_from_sorted(Env &env, const Plan &plan, const us_format_d
     if (!env.ok()) return finish(env.status);
     US_LAUNCH(env, "dcsr_compact", 12.0 * nmaj + 8.0 * nnr, dcsr_compact_kernel, ceil_div<int64_t>(nmaj, 256), 256,
               (const int32_t *)ptr, (const int32_t *)pos, nmaj, nnr, (int32_t)nnz, idx0, ptr1);
+    spmv_prepare(env, f);
     env.sync();
     return finish(env.status);
   }
@@ -285,24 +289,60 @@ __device__ __forceinline__ uint32_t group_bin(int gkind, uint32_t r, uint32_t c,
   return gkind == G_DIAG ? c - r + (nrows - 1) : (gkind == G_ROW ? r : c);
 }
 
-// One counter per group.  Entries of a wavefront that hit the same bin are combined before
-// the atomic, so a matrix whose entries sit on a handful of diagonals does not serialise.
-__global__ __launch_bounds__(256) void group_hist_kernel(const int32_t *row, const int32_t *col, int64_t n,
-                                                        int gkind, uint32_t nrows, uint32_t ncols, uint32_t *count,
-                                                        Flags *flags) {
-  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  bool valid = i < n;
-  uint32_t r = valid ? (uint32_t)row[i] : 0u, c = valid ? (uint32_t)col[i] : 0u;
-  if (valid && (r >= nrows || c >= ncols)) { flags->index_range = 1; valid = false; }
-  uint32_t bin = group_bin(gkind, r, c, nrows);
-  uint64_t todo = __ballot(valid);
-  while (todo) {
-    int leader = __ffsll((unsigned long long)todo) - 1;
-    uint32_t lb = __shfl(bin, leader);
-    uint64_t same = __ballot(valid && bin == lb) & todo;
-    if (lane_id() == leader) atomicAdd(&count[lb], (uint32_t)__popcll(same));
-    todo &= ~same;
+// One counter per group.  A matrix whose entries sit on a handful of diagonals would send
+// almost every update to the same few counters, so updates are combined twice before they
+// reach HBM: lanes of a wavefront that hit the same bin elect a leader (a few rounds), and the
+// leaders accumulate into a small LDS hash table that the workgroup flushes once.
+constexpr int GH_T = 256, GH_IPT = 16, GH_TILE = GH_T * GH_IPT, GH_SLOTS = 1024, GH_ROUNDS = 8, GH_PROBES = 8;
+
+__global__ __launch_bounds__(GH_T) void group_hist_kernel(const int32_t *row, const int32_t *col, int64_t n,
+                                                         int gkind, uint32_t nrows, uint32_t ncols, uint32_t *count,
+                                                         Flags *flags) {
+  __shared__ uint32_t s_key[GH_SLOTS];
+  __shared__ uint32_t s_cnt[GH_SLOTS];
+  for (int i = threadIdx.x; i < GH_SLOTS; i += GH_T) { s_key[i] = 0xFFFFFFFFu; s_cnt[i] = 0; }
+  __syncthreads();
+  const int64_t base = (int64_t)blockIdx.x * GH_TILE;
+  uint32_t bin[GH_IPT];
+  bool bad = false;
+#pragma unroll
+  for (int k = 0; k < GH_IPT; ++k) {
+    int64_t i = base + k * GH_T + threadIdx.x;
+    bin[k] = 0xFFFFFFFFu;
+    if (i < n) {
+      uint32_t r = (uint32_t)row[i], c = (uint32_t)col[i];
+      if (r >= nrows || c >= ncols) bad = true;
+      else bin[k] = group_bin(gkind, r, c, nrows);
+    }
   }
+  if (bad) flags->index_range = 1;
+  const int lane = lane_id();
+#pragma unroll 1
+  for (int k = 0; k < GH_IPT; ++k) {
+    uint32_t b = bin[k], add = b != 0xFFFFFFFFu ? 1u : 0u;
+    uint64_t todo = __ballot(add != 0);
+    for (int round = 0; round < GH_ROUNDS && todo; ++round) {
+      int leader = __ffsll((unsigned long long)todo) - 1;
+      uint32_t lb = __shfl(b, leader);
+      uint64_t same = __ballot(add != 0 && b == lb) & todo;
+      if (lane == leader) add = (uint32_t)__popcll(same);
+      else if ((same >> lane) & 1ull) add = 0;   // counted by the leader
+      todo &= ~same;
+    }
+    if (add) {
+      uint32_t h = (b * 2654435761u) >> 22;
+      bool done = false;
+      for (int probe = 0; probe < GH_PROBES && !done; ++probe) {
+        uint32_t old = atomicCAS(&s_key[h], 0xFFFFFFFFu, b);
+        if (old == 0xFFFFFFFFu || old == b) { atomicAdd(&s_cnt[h], add); done = true; }
+        h = (h + 1) & (GH_SLOTS - 1);
+      }
+      if (!done) atomicAdd(&count[b], add);
+    }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < GH_SLOTS; i += GH_T)
+    if (s_key[i] != 0xFFFFFFFFu && s_cnt[i]) atomicAdd(&count[s_key[i]], s_cnt[i]);
 }
 
 // flag[g] = group g goes to part A.  pkind < 0: every non-empty group (plain conversion).
@@ -333,62 +373,150 @@ __global__ __launch_bounds__(256) void group_flag_kernel(const uint32_t *count, 
   if (lane_id() == 0 && mine) atomicAdd(nnz_a, (int32_t)mine);
 }
 
-__global__ __launch_bounds__(256) void diag_offsets_kernel(const int32_t *flag, const int32_t *pos, int64_t nbins,
-                                                          int32_t nrows, int32_t *off) {
+// gmap[g] = position of group g among the flagged groups, or -1; offsets of the flagged diagonals
+__global__ __launch_bounds__(256) void group_map_kernel(const int32_t *flag, const int32_t *pos, int64_t nbins,
+                                                       int32_t *gmap) {
   int64_t d = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (d < nbins && flag[d]) off[pos[d]] = (int32_t)(d - (nrows - 1));
+  if (d < nbins) gmap[d] = flag[d] ? pos[d] : -1;
+}
+__global__ __launch_bounds__(256) void diag_offsets_kernel(const int32_t *gmap, int64_t nbins, int32_t nrows,
+                                                          int32_t *off) {
+  int64_t d = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (d < nbins && gmap[d] >= 0) off[gmap[d]] = (int32_t)(d - (nrows - 1));
 }
 
-// scatter into the zero-filled slab val[k*L + i]; a bitmap with one bit per slot detects duplicates
-__global__ __launch_bounds__(256) void dia_scatter_kernel(const int32_t *row, const int32_t *col, const float *val,
-                                                         int64_t n, uint32_t nrows, const int32_t *flag,
-                                                         const int32_t *pos, int64_t L, int by_col, float *slab,
-                                                         uint32_t *bitmap, Flags *flags) {
-  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= n) return;
-  uint32_t r = (uint32_t)row[i], c = (uint32_t)col[i];
-  uint32_t bin = c - r + (nrows - 1);
-  if (!flag[bin]) return;
-  int64_t slot = (int64_t)pos[bin] * L + (by_col ? c : r);
-  uint32_t bit = 1u << (slot & 31);
-  uint32_t old = atomicOr(&bitmap[slot >> 5], bit);
-  if (old & bit) flags->duplicate = 1;
-  slab[slot] = val[i];
+struct CooLists { int32_t *r = nullptr, *c = nullptr; float *v = nullptr; };
+
+// One pass over the COO list that sends every entry to its part of a decomposition.
+//   TO_SLAB: entries of flagged diagonals go straight into the zero-filled DIA slab
+//            val[k*L + i] (Devectorize/Fill/Vectorize) and mark their slot in a byte map (a
+//            slot marked twice = duplicate coordinate: the number of marked slots then falls
+//            short of the number of entries, checked afterwards);
+//   otherwise they are appended to list A.  Entries of unflagged groups are appended to list B.
+// Appends reserve space once per workgroup (one atomic per list), so order inside a list is
+// arbitrary; each part is put into canonical order by its conversion.
+constexpr int SP_T = 512, SP_IPT = 16, SP_TILE = SP_T * SP_IPT;
+
+template <bool TO_SLAB>
+__global__ __launch_bounds__(SP_T) void split_kernel(const int32_t *row, const int32_t *col, const float *val,
+                                                    int64_t n, int gkind, uint32_t nrows, const int32_t *gmap,
+                                                    int64_t L, int by_col, float *slab, uint8_t *slotmap,
+                                                    CooLists la, CooLists lb, int32_t *cursors) {
+  __shared__ uint32_t s_wave[SP_T / 64 + 1];
+  __shared__ int32_t s_base[2];
+  const int64_t base = (int64_t)blockIdx.x * SP_TILE;
+  uint32_t r[SP_IPT], c[SP_IPT];
+  float v[SP_IPT];
+  int32_t g[SP_IPT];
+#pragma unroll
+  for (int k = 0; k < SP_IPT; ++k) {
+    int64_t i = base + k * SP_T + threadIdx.x;
+    r[k] = c[k] = 0; v[k] = 0.f;
+    if (i < n) { r[k] = (uint32_t)row[i]; c[k] = (uint32_t)col[i]; v[k] = val[i]; }
+  }
+  uint32_t na = 0, nb = 0;
+#pragma unroll
+  for (int k = 0; k < SP_IPT; ++k) {
+    int64_t i = base + k * SP_T + threadIdx.x;
+    g[k] = -2;  // no entry
+    if (i < n) {
+      g[k] = gmap[group_bin(gkind, r[k], c[k], nrows)];
+      if (g[k] >= 0) ++na; else ++nb;
+    }
+  }
+  uint32_t ta, tb;
+  uint32_t pa = (!TO_SLAB && la.r) ? block_exclusive_sum<SP_T>(na, s_wave, &ta) : 0u;
+  uint32_t pb = lb.r ? block_exclusive_sum<SP_T>(nb, s_wave, &tb) : 0u;
+  if (threadIdx.x == 0) {
+    s_base[0] = (!TO_SLAB && la.r && ta) ? atomicAdd(&cursors[0], (int32_t)ta) : 0;
+    s_base[1] = (lb.r && tb) ? atomicAdd(&cursors[1], (int32_t)tb) : 0;
+  }
+  __syncthreads();
+  pa += s_base[0]; pb += s_base[1];
+#pragma unroll
+  for (int k = 0; k < SP_IPT; ++k) {
+    if (g[k] >= 0) {
+      if (TO_SLAB) {
+        int64_t slot = (int64_t)g[k] * L + (by_col ? c[k] : r[k]);
+        slab[slot] = v[k];
+        slotmap[slot] = 1;
+      } else if (la.r) {
+        la.r[pa] = (int32_t)r[k]; la.c[pa] = (int32_t)c[k]; la.v[pa] = v[k]; ++pa;
+      }
+    } else if (g[k] == -1 && lb.r) {
+      lb.r[pb] = (int32_t)r[k]; lb.c[pb] = (int32_t)c[k]; lb.v[pb] = v[k]; ++pb;
+    }
+  }
 }
 
-// DIA from per-diagonal flags (flags->scalar[1] already holds the number of flagged entries)
+// number of marked slots (bytes are 0 or 1; the map is padded with zeros to a multiple of 16)
+__global__ __launch_bounds__(256) void count_marks_kernel(const uint4 *m, int64_t nvec, int32_t *out) {
+  __shared__ uint32_t s_wave[256 / 64 + 1];
+  uint32_t cnt = 0;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * 256) {
+    uint4 w = m[i];
+    cnt += __popc(w.x) + __popc(w.y) + __popc(w.z) + __popc(w.w);
+  }
+  uint32_t total;
+  block_exclusive_sum<256>(cnt, s_wave, &total);
+  if (threadIdx.x == 0 && total) atomicAdd(out, (int32_t)total);
+}
+
+static CooLists alloc_lists(Env &env, int64_t n) {
+  CooLists l;
+  l.r = env.owned<int32_t>(n); l.c = env.owned<int32_t>(n); l.v = env.owned<float>(n);
+  return l;
+}
+static void free_lists(Env &env, CooLists &l) {
+  env.free_raw(l.r); env.free_raw(l.c); env.free_raw(l.v);
+  l = CooLists();
+}
+
+// DIA from per-diagonal flags (flags->scalar[1] already holds the number of flagged entries).
+// If `rest` is given, the entries of the unflagged diagonals are collected into it in the same
+// pass (its arrays are allocated here; the caller owns them afterwards) and *nrest is their number.
 static us_status dia_from_flags(Env &env, const us_coo &coo, const Plan &plan, const us_format_desc &desc,
-                                Flags *flags, const int32_t *flag, us_formatted **out) {
+                                Flags *flags, const int32_t *flag, us_formatted **out, CooLists *rest,
+                                int64_t *nrest) {
   const int64_t nbins = coo.nrows + coo.ncols - 1, n = coo.nnz;
   const int64_t L = plan.swapped ? coo.ncols : coo.nrows;
-  int32_t *pos = env.temp<int32_t>(nbins);
+  int32_t *pos = env.temp<int32_t>(nbins), *gmap = env.temp<int32_t>(nbins);
+  int32_t *cursors = env.temp<int32_t>(2);
   if (!env.ok()) return env.status;
   exclusive_scan_i32(env, flag, pos, nbins, &flags->scalar[0]);
+  US_LAUNCH(env, "group_map", 12.0 * nbins, group_map_kernel, ceil_div<int64_t>(nbins, 256), 256, flag,
+            (const int32_t *)pos, nbins, gmap);
   Flags h{};
   if (!read_flags(env, flags, &h)) return env.status;
   if (flag_status(h) != US_OK) return flag_status(h);
-  const int64_t ndiag = h.scalar[0];
+  const int64_t ndiag = h.scalar[0], na = h.scalar[1];
   if (ndiag * L >= (1ll << 31)) return US_ERR_OVERFLOW;
   us_formatted *f = new us_formatted();
   f->desc = desc; f->pattern = P_DIA; f->swapped = plan.swapped;
-  f->nrows = coo.nrows; f->ncols = coo.ncols; f->nnz = h.scalar[1];
+  f->nrows = coo.nrows; f->ncols = coo.ncols; f->nnz = na;
   f->nlevels = 2;
   f->level[0].idx = env.owned<int32_t>(ndiag); f->level[0].nidx = ndiag;
   f->level[1].size = L;
   f->val = env.owned<float>(ndiag * L); f->nval = ndiag * L; f->nmajor = ndiag;
-  const int64_t nwords = ceil_div<int64_t>(ndiag * L, 32) + 1;
-  uint32_t *bitmap = env.temp<uint32_t>(nwords);
+  const int64_t nvec = ceil_div<int64_t>(ndiag * L, 16) + 1;
+  uint8_t *slotmap = (uint8_t *)env.temp<uint4>(nvec);
+  CooLists lb;
+  if (rest) { *nrest = n - na; lb = alloc_lists(env, n - na); *rest = lb; }
   if (!env.ok()) { free_formatted(env, f); return env.status; }
   fill_u32(env, (uint32_t *)f->val, ndiag * L, 0u);
-  fill_u32(env, bitmap, nwords, 0u);
-  US_LAUNCH(env, "diag_offsets", 8.0 * nbins, diag_offsets_kernel, ceil_div<int64_t>(nbins, 256), 256, flag,
-            (const int32_t *)pos, nbins, (int32_t)coo.nrows, f->level[0].idx);
+  fill_u32(env, (uint32_t *)slotmap, nvec * 4, 0u);
+  fill_u32(env, (uint32_t *)cursors, 2, 0u);
+  US_LAUNCH(env, "diag_offsets", 8.0 * nbins, diag_offsets_kernel, ceil_div<int64_t>(nbins, 256), 256,
+            (const int32_t *)gmap, nbins, (int32_t)coo.nrows, f->level[0].idx);
   if (n > 0)
-    US_LAUNCH(env, "dia_scatter", 16.0 * n, dia_scatter_kernel, ceil_div<int64_t>(n, 256), 256, coo.row, coo.col,
-              coo.val, n, (uint32_t)coo.nrows, flag, (const int32_t *)pos, L, plan.swapped ? 1 : 0, f->val, bitmap,
-              flags);
+    US_LAUNCH(env, "dia_split_scatter", 12.0 * n + 5.0 * na + 12.0 * (rest ? n - na : 0), (split_kernel<true>),
+              ceil_div<int64_t>(n, SP_TILE), SP_T, coo.row, coo.col, coo.val, n, (int)G_DIAG, (uint32_t)coo.nrows,
+              (const int32_t *)gmap, L, plan.swapped ? 1 : 0, f->val, slotmap, CooLists(), lb, cursors);
+  US_LAUNCH(env, "count_marks", 1.0 * ndiag * L, count_marks_kernel, nvec < 4096 * 256 ? ceil_div<int64_t>(nvec, 256) : 4096,
+            256, (const uint4 *)slotmap, nvec, &flags->scalar[3]);
   if (!read_flags(env, flags, &h)) { free_formatted(env, f); return env.status; }
   if (flag_status(h) != US_OK) { free_formatted(env, f); return flag_status(h); }
+  if (h.scalar[3] != na) { free_formatted(env, f); return US_ERR_DUPLICATE; }
   *out = f;
   return US_OK;
 }
@@ -405,7 +533,7 @@ static GroupCounts group_flags(Env &env, const us_coo &coo, int gkind, int pkind
   if (!env.ok()) return g;
   fill_u32(env, g.count, g.nbins, 0);
   if (coo.nnz > 0)
-    US_LAUNCH(env, "group_hist", 8.0 * coo.nnz, group_hist_kernel, ceil_div<int64_t>(coo.nnz, 256), 256, coo.row,
+    US_LAUNCH(env, "group_hist", 8.0 * coo.nnz, group_hist_kernel, ceil_div<int64_t>(coo.nnz, GH_TILE), GH_T, coo.row,
               coo.col, coo.nnz, gkind, (uint32_t)coo.nrows, (uint32_t)coo.ncols, g.count, flags);
   US_LAUNCH(env, "group_flag", 8.0 * g.nbins, group_flag_kernel, ceil_div<int64_t>(g.nbins, 256), 256,
             (const uint32_t *)g.count, g.nbins, gkind, pkind, num, den, thr, coo.nrows, coo.ncols, g.flag,
@@ -417,7 +545,7 @@ static us_status convert_dia(Env &env, const us_coo &coo, const Plan &plan, cons
                              Flags *flags, us_formatted **out) {
   GroupCounts g = group_flags(env, coo, G_DIAG, -1, 0, 1, 0, flags);
   if (!env.ok()) return env.status;
-  return dia_from_flags(env, coo, plan, desc, flags, g.flag, out);
+  return dia_from_flags(env, coo, plan, desc, flags, g.flag, out, nullptr, nullptr);
 }
 
 // ------------------------------------------------------------------ BCSR
@@ -577,36 +705,6 @@ us_status convert_impl(Env &env, const us_coo &coo, const us_format_desc &desc, 
 }
 
 // ------------------------------------------------------------------ decompose
-// entries whose group is flagged go to list A, the others to list B (order inside a list is
-// irrelevant: each part is put into canonical order by its conversion)
-__global__ __launch_bounds__(256) void partition_kernel(const int32_t *row, const int32_t *col, const float *val,
-                                                       int64_t n, int gkind, uint32_t nrows, const int32_t *flag,
-                                                       int32_t *ar, int32_t *ac, float *av, int32_t *br,
-                                                       int32_t *bc, float *bv, int32_t *cursors) {
-  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  bool valid = i < n;
-  uint32_t r = valid ? (uint32_t)row[i] : 0u, c = valid ? (uint32_t)col[i] : 0u;
-  float v = valid ? val[i] : 0.f;
-  bool to_a = valid && flag[group_bin(gkind, r, c, nrows)] != 0;
-  bool to_b = valid && !to_a;
-  const int lane = lane_id();
-  uint64_t ma = __ballot(to_a), mb = __ballot(to_b);
-  int32_t base_a = 0, base_b = 0;
-  if (lane == 0) {
-    if (ma && ar) base_a = atomicAdd(&cursors[0], (int32_t)__popcll(ma));
-    if (mb) base_b = atomicAdd(&cursors[1], (int32_t)__popcll(mb));
-  }
-  base_a = __shfl(base_a, 0); base_b = __shfl(base_b, 0);
-  if (to_a && ar) {
-    int32_t p = base_a + (int32_t)__popcll(ma & lanes_below());
-    ar[p] = (int32_t)r; ac[p] = (int32_t)c; av[p] = v;
-  }
-  if (to_b) {
-    int32_t p = base_b + (int32_t)__popcll(mb & lanes_below());
-    br[p] = (int32_t)r; bc[p] = (int32_t)c; bv[p] = v;
-  }
-}
-
 __global__ __launch_bounds__(256) void row_len_kernel(const int32_t *ptr, int64_t n, uint32_t *len) {
   int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (g < n) len[g] = (uint32_t)(ptr[g + 1] - ptr[g]);
@@ -640,43 +738,39 @@ static bool row_major_family(const Plan &p) {
   return !p.swapped && (p.pattern == P_COO || p.pattern == P_CSR || p.pattern == P_DCSR || p.pattern == P_ELL);
 }
 
-struct CooLists { int32_t *r = nullptr, *c = nullptr; float *v = nullptr; };
-static CooLists alloc_lists(Env &env, int64_t n) {
-  CooLists l;
-  l.r = env.owned<int32_t>(n); l.c = env.owned<int32_t>(n); l.v = env.owned<float>(n);
-  return l;
-}
-static void free_lists(Env &env, CooLists &l) {
-  env.free_raw(l.r); env.free_raw(l.c); env.free_raw(l.v);
-  l = CooLists();
-}
-
 static us_status decompose_sum(Env &env, const us_coo &coo, const Plan &pa, const us_format_desc &da, const Plan &pb,
                                const us_format_desc &db, const us_predicate &pred, int gkind, us_formatted **oa,
                                us_formatted **ob) {
   Flags *flags = new_flags(env);
   if (!env.ok()) return env.status;
   GroupCounts g = group_flags(env, coo, gkind, pred.kind, pred.num, pred.den, pred.abs, flags);
-  Flags h{};
-  if (!read_flags(env, flags, &h)) return env.status;
-  if (flag_status(h) != US_OK) return flag_status(h);
-  const int64_t n = coo.nnz, na = h.scalar[1], nb = n - na;
-  const bool dia_direct = gkind == G_DIAG && pa.pattern == P_DIA;  // part A goes straight into the slab
-  CooLists la, lb = alloc_lists(env, nb);
-  if (!dia_direct) la = alloc_lists(env, na);
-  int32_t *cursors = env.temp<int32_t>(2);
-  us_status st = env.status;
-  if (st == US_OK) {
-    fill_u32(env, (uint32_t *)cursors, 2, 0u);
-    if (n > 0)
-      US_LAUNCH(env, "partition", 12.0 * n + 12.0 * (dia_direct ? nb : n), partition_kernel,
-                ceil_div<int64_t>(n, 256), 256, coo.row, coo.col, coo.val, n, gkind, (uint32_t)coo.nrows,
-                (const int32_t *)g.flag, la.r, la.c, la.v, lb.r, lb.c, lb.v, cursors);
+  if (!env.ok()) return env.status;
+  const int64_t n = coo.nnz;
+  CooLists la, lb;
+  int64_t na = 0, nb = 0;
+  us_status st;
+  if (gkind == G_DIAG && pa.pattern == P_DIA) {
+    // part A goes straight into the slab while part B is collected, in one pass over the input
+    st = dia_from_flags(env, coo, pa, da, flags, g.flag, oa, &lb, &nb);
+  } else {
+    Flags h{};
+    if (!read_flags(env, flags, &h)) return env.status;
+    if (flag_status(h) != US_OK) return flag_status(h);
+    na = h.scalar[1]; nb = n - na;
+    la = alloc_lists(env, na); lb = alloc_lists(env, nb);
+    int32_t *gmap = env.temp<int32_t>(g.nbins), *cursors = env.temp<int32_t>(2);
     st = env.status;
-  }
-  if (st == US_OK) {
-    if (dia_direct) st = dia_from_flags(env, coo, pa, da, flags, g.flag, oa);
-    else {
+    if (st == US_OK) {
+      fill_u32(env, (uint32_t *)cursors, 2, 0u);
+      US_LAUNCH(env, "group_map", 12.0 * g.nbins, group_map_kernel, ceil_div<int64_t>(g.nbins, 256), 256,
+                (const int32_t *)g.flag, (const int32_t *)g.flag, g.nbins, gmap);
+      if (n > 0)
+        US_LAUNCH(env, "split", 24.0 * n, (split_kernel<false>), ceil_div<int64_t>(n, SP_TILE), SP_T, coo.row, coo.col,
+                  coo.val, n, gkind, (uint32_t)coo.nrows, (const int32_t *)gmap, (int64_t)0, 0, (float *)nullptr,
+                  (uint8_t *)nullptr, la, lb, cursors);
+      st = env.status;
+    }
+    if (st == US_OK) {
       us_coo ca{coo.nrows, coo.ncols, na, la.r, la.c, la.v};
       st = convert_with_plan(env, ca, pa, da, oa);
     }
@@ -690,8 +784,6 @@ static us_status decompose_sum(Env &env, const us_coo &coo, const Plan &pa, cons
   free_lists(env, lb);
   return st;
 }
-
-void sort_u32(Env &env, const uint32_t *key, int64_t n, int bits, uint32_t *out);
 
 static us_status decompose_rank(Env &env, const us_coo &coo, const Plan &pa, const us_format_desc &da, const Plan &pb,
                                 const us_format_desc &db, const us_predicate &pred, us_formatted **oa,
@@ -718,7 +810,7 @@ static us_status decompose_rank(Env &env, const us_coo &coo, const Plan &pa, con
     US_LAUNCH(env, "row_len", 8.0 * nrows, row_len_kernel, ceil_div<int64_t>(nrows, 256), 256, (const int32_t *)ptr,
               nrows, len);
     const int64_t maxlen = n < coo.ncols ? n : coo.ncols;
-    sort_u32(env, len, nrows, bits_for((uint64_t)maxlen), slen);
+    sort_u32(env, len, nrows, bits_for((uint64_t)maxlen), slen, flags);
     int64_t k = (pred.num * nrows + pred.den - 1) / pred.den;
     if (k < 1) k = 1;
     if (k > nrows) k = nrows;

@@ -31,14 +31,28 @@ __global__ __launch_bounds__(256) void bcsr44_spmm_mfma_kernel(const int32_t *pt
   float4v acc = {0.f, 0.f, 0.f, 0.f};
   const int b0 = ptr[br], b1 = ptr[br + 1];
   const int arow = lane & 3;
-  for (int b = b0; b < b1; ++b) {
-    const int64_t xr = (int64_t)idx[b] * 4;
-    const float4v a = *reinterpret_cast<const float4v *>(val + (int64_t)b * 16 + arow * 4);
-    float xv[4];
+  constexpr int U = 4;  // blocks in flight: 16 X-row loads per wavefront before the first MFMA
+  for (int bb = b0; bb < b1; bb += 64) {
+    const int cnt = min(64, b1 - bb);
+    const int32_t my_bc = lane < cnt ? idx[bb + lane] : 0;   // block columns of the next 64 blocks, one per lane
+    for (int j0 = 0; j0 < cnt; j0 += U) {
+      float4v a[U];
+      float xv[U][4];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) xv[k] = (col_ok && xr + k < ncols) ? X[(xr + k) * ldx + c] : 0.f;
+      for (int u = 0; u < U; ++u) {
+        const int j = j0 + u;
+        const bool ok = j < cnt;
+        const int64_t xr = (int64_t)__shfl(my_bc, ok ? j : 0) * 4;
+        a[u] = ok ? *reinterpret_cast<const float4v *>(val + (int64_t)(bb + j) * 16 + arow * 4)
+                  : float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int k = 0; k < 4; ++k) acc = __builtin_amdgcn_mfma_f32_4x4x1f32(a[k], xv[k], acc, 0, 0, 0);
+        for (int k = 0; k < 4; ++k) xv[u][k] = (ok && col_ok && xr + k < ncols) ? X[(xr + k) * ldx + c] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc = __builtin_amdgcn_mfma_f32_4x4x1f32(a[u][k], xv[u][k], acc, 0, 0, 0);
+    }
   }
   if (col_ok) {
 #pragma unroll
@@ -77,19 +91,40 @@ __global__ __launch_bounds__(256) void bcsr_spmm_kernel(const int32_t *ptr, cons
 }
 
 // ------------------------------------------------------------------ row-grouped layouts, one wavefront per (row, 64 columns)
+// A lane owns VEC consecutive columns (VEC = 2 covers N = 128 with one wavefront per row).
+template <int VEC> struct VecT;
+template <> struct VecT<1> { typedef float type; };
+template <> struct VecT<2> { typedef float type __attribute__((ext_vector_type(2))); };
+template <> struct VecT<4> { typedef float type __attribute__((ext_vector_type(4))); };
+
+// ELL: the slots of a row are independent gathers; 8 are issued before the first FMA.
+template <int VEC>
 __global__ __launch_bounds__(256) void ell_spmm_kernel(const int32_t *ecol, const float *ev, int64_t K, int64_t nrows,
                                                       const float *X, int64_t N, int64_t ldx, float *Y, int64_t ldy,
                                                       int accumulate) {
+  typedef typename VecT<VEC>::type V;
   const int64_t i = (int64_t)blockIdx.x * 4 + wave_id();
   if (i >= nrows) return;
-  const int64_t c = (int64_t)blockIdx.y * 64 + lane_id();
+  const int64_t c = ((int64_t)blockIdx.y * 64 + lane_id()) * VEC;
   if (c >= N) return;
-  float s = accumulate ? Y[i * ldy + c] : 0.f;
-  for (int64_t k = 0; k < K; ++k) {
-    int32_t col = ecol[k * nrows + i];
-    if (col >= 0) s += ev[k * nrows + i] * X[(int64_t)col * ldx + c];
+  V s = accumulate ? *reinterpret_cast<const V *>(Y + i * ldy + c) : V(0.f);
+  constexpr int U = 8;
+  for (int64_t k0 = 0; k0 < K; k0 += U) {
+    int32_t col[U];
+    float v[U];
+    V xv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool ok = k0 + u < K;
+      col[u] = ok ? ecol[(k0 + u) * nrows + i] : -1;
+      v[u] = ok ? ev[(k0 + u) * nrows + i] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) xv[u] = *reinterpret_cast<const V *>(X + (int64_t)(col[u] < 0 ? 0 : col[u]) * ldx + c);
+#pragma unroll
+    for (int u = 0; u < U; ++u) s += col[u] >= 0 ? v[u] * xv[u] : V(0.f);
   }
-  Y[i * ldy + c] = s;
+  *reinterpret_cast<V *>(Y + i * ldy + c) = s;
 }
 
 __global__ __launch_bounds__(256) void csr_spmm_kernel(const int32_t *ptr, const int32_t *idx, const float *val,
@@ -126,54 +161,72 @@ __global__ __launch_bounds__(256) void dia_spmm_kernel(const int32_t *off, const
 // go to a carry buffer and are summed in chunk order by the fix-up kernel (reproducible).
 constexpr int CS_CHUNK = 512;
 
+template <int VEC>
 __global__ __launch_bounds__(256) void coo_spmm_kernel(const int32_t *row, const int32_t *col, const float *val,
                                                       int64_t nnz, const float *X, int64_t N, int64_t ldx, float *Y,
                                                       int64_t ldy, int32_t *carry_row, float *carry) {
+  typedef typename VecT<VEC>::type V;
   const int lane = lane_id();
   const int64_t chunk = (int64_t)blockIdx.x * 4 + wave_id();
   const int64_t e0 = chunk * CS_CHUNK;
   if (e0 >= nnz) return;
   const int64_t e1 = min(e0 + CS_CHUNK, nnz);
-  const int64_t c = (int64_t)blockIdx.y * 64 + lane;
+  const int64_t c = ((int64_t)blockIdx.y * 64 + lane) * VEC;
   const bool col_ok = c < N;
   const int32_t row_before = e0 > 0 ? row[e0 - 1] : -1;
   const int32_t row_after = e1 < nnz ? row[e1] : -1;
   const int32_t first_row = row[e0], last_row = row[e1 - 1];
-  float *carry_head = carry + ((chunk * 2 + 0) * gridDim.y + blockIdx.y) * 64;
-  float *carry_tail = carry + ((chunk * 2 + 1) * gridDim.y + blockIdx.y) * 64;
+  V *carry_head = reinterpret_cast<V *>(carry + ((chunk * 2 + 0) * gridDim.y + blockIdx.y) * (64 * VEC)) + lane;
+  V *carry_tail = reinterpret_cast<V *>(carry + ((chunk * 2 + 1) * gridDim.y + blockIdx.y) * (64 * VEC)) + lane;
   const bool head_cut = first_row == row_before, tail_cut = last_row == row_after;
-  float acc = 0.f;
+  V acc = V(0.f);
   int32_t cur = first_row;
   bool in_head = true;  // still inside the first row piece of the chunk
+  constexpr int U = 8;
   for (int64_t base = e0; base < e1; base += 64) {
     const int64_t e = base + lane;
     int32_t r = e < e1 ? row[e] : -1, cc = e < e1 ? col[e] : 0;
     float v = e < e1 ? val[e] : 0.f;
     const int cnt = (int)min((int64_t)64, e1 - base);
-    for (int t = 0; t < cnt; ++t) {
-      int32_t rt = __shfl(r, t), ct = __shfl(cc, t);
-      float vt = __shfl(v, t);
-      if (rt != cur) {  // flush the finished piece of row `cur`
-        if (col_ok) {
-          if (in_head && head_cut) carry_head[lane] = acc;
-          else Y[(int64_t)cur * ldy + c] += acc;
-        }
-        in_head = false;
-        acc = 0.f;
-        cur = rt;
+    for (int t0 = 0; t0 < cnt; t0 += U) {
+      int32_t rt[U];
+      float vt[U];
+      V xv[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {   // 8 gathers of X rows in flight
+        const int t = t0 + u < cnt ? t0 + u : cnt - 1;
+        rt[u] = __shfl(r, t);
+        vt[u] = __shfl(v, t);
+        const int32_t ct = __shfl(cc, t);
+        xv[u] = col_ok ? *reinterpret_cast<const V *>(X + (int64_t)ct * ldx + c) : V(0.f);
       }
-      if (col_ok) acc += vt * X[(int64_t)ct * ldx + c];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (t0 + u < cnt) {
+          if (rt[u] != cur) {  // flush the finished piece of row `cur`
+            if (col_ok) {
+              if (in_head && head_cut) *carry_head = acc;
+              else { V *yp = reinterpret_cast<V *>(Y + (int64_t)cur * ldy + c); *yp += acc; }
+            }
+            in_head = false;
+            acc = V(0.f);
+            cur = rt[u];
+          }
+          acc += vt[u] * xv[u];
+        }
+      }
     }
   }
   // last piece
   const bool single = in_head;  // the whole chunk lies inside one row
   if (col_ok) {
+    V *yp = reinterpret_cast<V *>(Y + (int64_t)cur * ldy + c);
     if (single) {
-      if (head_cut || tail_cut) { carry_head[lane] = acc; carry_tail[lane] = 0.f; }
-      else Y[(int64_t)cur * ldy + c] += acc;
+      if (head_cut || tail_cut) { *carry_head = acc; *carry_tail = V(0.f); }
+      else *yp += acc;
     } else {
-      if (tail_cut) carry_tail[lane] = acc;
-      else Y[(int64_t)cur * ldy + c] += acc;
+      if (tail_cut) *carry_tail = acc;
+      else *yp += acc;
     }
   }
   if (lane == 0 && blockIdx.y == 0) {
@@ -185,21 +238,22 @@ __global__ __launch_bounds__(256) void coo_spmm_kernel(const int32_t *row, const
 }
 
 __global__ __launch_bounds__(256) void coo_spmm_fixup_kernel(const int32_t *carry_row, const float *carry,
-                                                            int64_t nentries, int64_t ncb, int64_t N, float *Y,
-                                                            int64_t ldy) {
+                                                            int64_t nentries, int64_t ncb, int cbw, int64_t N,
+                                                            float *Y, int64_t ldy) {
   const int lane = lane_id();
   const int64_t e = (int64_t)blockIdx.x * 4 + wave_id();
   if (e >= nentries) return;
   const int32_t r = carry_row[e];
   if (r < 0) return;
-  // first entry of the run of row r (entries marked -1 in between belong to no run of r:
-  // a run never skips an entry, see the kernel above)
+  // only the first entry of the run of row r works (a run never skips an entry, see above)
   if (e > 0 && carry_row[e - 1] == r) return;
-  const int64_t c = (int64_t)blockIdx.y * 64 + lane;
-  if (c >= N) return;
-  float s = 0.f;
-  for (int64_t j = e; j < nentries && carry_row[j] == r; ++j) s += carry[(j * ncb + blockIdx.y) * 64 + lane];
-  Y[(int64_t)r * ldy + c] += s;
+  for (int q = lane; q < cbw; q += 64) {
+    const int64_t c = (int64_t)blockIdx.y * cbw + q;
+    if (c >= N) continue;
+    float s = 0.f;
+    for (int64_t j = e; j < nentries && carry_row[j] == r; ++j) s += carry[(j * ncb + blockIdx.y) * cbw + q];
+    Y[(int64_t)r * ldy + c] += s;
+  }
 }
 
 // scatter form for CSC / DCSC: one wavefront per (stored column, 64 columns of X)
@@ -234,6 +288,10 @@ us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, 
                     bool accumulate) {
   const int64_t ncb = ceil_div<int64_t>(N, 64);
   const int acc = accumulate ? 1 : 0;
+  // columns per lane for the gather kernels: vector loads need aligned rows
+  const bool al16 = ((uintptr_t)X % 16 == 0) && ((uintptr_t)Y % 16 == 0);
+  const int vec = (al16 && N % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && N >= 256) ? 4
+                  : (al16 && N % 2 == 0 && ldx % 2 == 0 && ldy % 2 == 0 && N >= 128) ? 2 : 1;
   const double xy = 4.0 * N * (A.ncols + A.nrows);
   switch (A.pattern) {
     case P_BCSR: {
@@ -258,9 +316,11 @@ us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, 
     case P_ELL:
       if (env.ok()) {
         LaunchScope ls(env, "spmm_ell", 8.0 * A.nval + xy);
-        hipLaunchKernelGGL(ell_spmm_kernel, dim3((unsigned)ceil_div<int64_t>(A.nrows, 4), (unsigned)ncb), dim3(256), 0,
-                           env.stream, (const int32_t *)A.level[2].idx, (const float *)A.val, A.nmajor, A.nrows, X, N,
-                           ldx, Y, ldy, acc);
+        const dim3 grid((unsigned)ceil_div<int64_t>(A.nrows, 4), (unsigned)ceil_div<int64_t>(N, 64 * vec));
+        const int32_t *ec = A.level[2].idx;
+        if (vec == 4) hipLaunchKernelGGL(ell_spmm_kernel<4>, grid, dim3(256), 0, env.stream, ec, (const float *)A.val, A.nmajor, A.nrows, X, N, ldx, Y, ldy, acc);
+        else if (vec == 2) hipLaunchKernelGGL(ell_spmm_kernel<2>, grid, dim3(256), 0, env.stream, ec, (const float *)A.val, A.nmajor, A.nrows, X, N, ldx, Y, ldy, acc);
+        else hipLaunchKernelGGL(ell_spmm_kernel<1>, grid, dim3(256), 0, env.stream, ec, (const float *)A.val, A.nmajor, A.nrows, X, N, ldx, Y, ldy, acc);
         env.check(hipGetLastError());
       }
       return env.status;
@@ -315,22 +375,26 @@ us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, 
       const int64_t nchunks = ceil_div<int64_t>(A.nnz, CS_CHUNK);
       const size_t rows_bytes = (size_t)nchunks * 2 * sizeof(int32_t);
       const size_t rows_pad = (rows_bytes + 255) / 256 * 256;
-      char *ws = (char *)ensure_workspace(env, A, rows_pad + (size_t)nchunks * 2 * ncb * 64 * sizeof(float));
+      const int cbw = 64 * vec;
+      const int64_t ncbv = ceil_div<int64_t>(N, cbw);
+      char *ws = (char *)ensure_workspace(env, A, rows_pad + (size_t)nchunks * 2 * ncbv * cbw * sizeof(float));
       if (!env.ok()) return env.status;
       int32_t *carry_row = (int32_t *)ws;
       float *carry = (float *)(ws + rows_pad);
       {
         LaunchScope ls(env, "spmm_coo", 12.0 * A.nnz + xy);
-        hipLaunchKernelGGL(coo_spmm_kernel, dim3((unsigned)ceil_div<int64_t>(nchunks, 4), (unsigned)ncb), dim3(256), 0,
-                           env.stream, (const int32_t *)A.level[0].idx, (const int32_t *)A.level[1].idx,
-                           (const float *)A.val, A.nnz, X, N, ldx, Y, ldy, carry_row, carry);
+        const dim3 grid((unsigned)ceil_div<int64_t>(nchunks, 4), (unsigned)ncbv);
+        const int32_t *ar = A.level[0].idx, *ac = A.level[1].idx;
+        if (vec == 4) hipLaunchKernelGGL(coo_spmm_kernel<4>, grid, dim3(256), 0, env.stream, ar, ac, (const float *)A.val, A.nnz, X, N, ldx, Y, ldy, carry_row, carry);
+        else if (vec == 2) hipLaunchKernelGGL(coo_spmm_kernel<2>, grid, dim3(256), 0, env.stream, ar, ac, (const float *)A.val, A.nnz, X, N, ldx, Y, ldy, carry_row, carry);
+        else hipLaunchKernelGGL(coo_spmm_kernel<1>, grid, dim3(256), 0, env.stream, ar, ac, (const float *)A.val, A.nnz, X, N, ldx, Y, ldy, carry_row, carry);
         env.check(hipGetLastError());
       }
       if (env.ok()) {
         LaunchScope ls(env, "spmm_coo_fixup", 8.0 * nchunks);
-        hipLaunchKernelGGL(coo_spmm_fixup_kernel, dim3((unsigned)ceil_div<int64_t>(nchunks * 2, 4), (unsigned)ncb),
-                           dim3(256), 0, env.stream, (const int32_t *)carry_row, (const float *)carry, nchunks * 2, ncb,
-                           N, Y, ldy);
+        hipLaunchKernelGGL(coo_spmm_fixup_kernel, dim3((unsigned)ceil_div<int64_t>(nchunks * 2, 4), (unsigned)ncbv),
+                           dim3(256), 0, env.stream, (const int32_t *)carry_row, (const float *)carry, nchunks * 2, ncbv,
+                           cbw, N, Y, ldy);
         env.check(hipGetLastError());
       }
       return env.status;

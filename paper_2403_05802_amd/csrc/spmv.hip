@@ -25,28 +25,31 @@ __device__ __forceinline__ int64_t merge_path_rows(const int32_t *row_end, int64
 
 struct SegPair { int32_t key; float val; };
 
+// split[t] = row ends consumed before merge step t * MP_TILE (t = 0..ntiles)
+__global__ __launch_bounds__(256) void merge_path_split_kernel(const int32_t *ptr, int64_t nrows, int64_t nnz,
+                                                              int64_t ntiles, int32_t *split) {
+  int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t > ntiles) return;
+  int64_t d = t * MP_TILE;
+  if (d > nrows + nnz) d = nrows + nnz;
+  split[t] = (int32_t)merge_path_rows(ptr + 1, nrows, nnz, d);
+}
+
 template <bool INDIRECT_ROWS>
 __global__ __launch_bounds__(MP_T) void csr_spmv_kernel(const int32_t *ptr, const int32_t *idx, const float *val,
-                                                       const int32_t *row_ids, int64_t nrows, int64_t nnz,
-                                                       const float *x, float *y, int accumulate,
+                                                       const int32_t *row_ids, const int32_t *split, int64_t nrows,
+                                                       int64_t nnz, const float *x, float *y, int accumulate,
                                                        int32_t *carry_row, float *carry_val) {
   __shared__ float s_prod[MP_TILE];
   __shared__ int32_t s_end[MP_TILE + 1];
-  __shared__ int64_t s_range[4];
   __shared__ int32_t s_wkey[MP_T / 64];
   __shared__ float s_wval[MP_T / 64];
   const int32_t *row_end = ptr + 1;
   const int64_t total = nrows + nnz;
   const int64_t diag0 = (int64_t)blockIdx.x * MP_TILE;
   const int64_t diag1 = min(diag0 + MP_TILE, total);
-  if (threadIdx.x < 2) {
-    int64_t d = threadIdx.x == 0 ? diag0 : diag1;
-    int64_t r = merge_path_rows(row_end, nrows, nnz, d);
-    s_range[threadIdx.x * 2] = r;
-    s_range[threadIdx.x * 2 + 1] = d - r;
-  }
-  __syncthreads();
-  const int64_t r0 = s_range[0], z0 = s_range[1], r1 = s_range[2], z1 = s_range[3];
+  const int64_t r0 = split[blockIdx.x], r1 = split[blockIdx.x + 1];
+  const int64_t z0 = diag0 - r0, z1 = diag1 - r1;
   const int nr = (int)(r1 - r0), nz = (int)(z1 - z0);
   for (int i = threadIdx.x; i < nz; i += MP_T) s_prod[i] = val[z0 + i] * x[idx[z0 + i]];
   for (int i = threadIdx.x; i < nr; i += MP_T) s_end[i] = (int32_t)(row_end[r0 + i] - z0);
@@ -137,6 +140,7 @@ static void spmv_compressed(Env &env, const us_formatted &A, const int32_t *ptr,
   const int64_t total = nrows_stored + nnz;
   if (total == 0) return;
   const int64_t nb = ceil_div<int64_t>(total, MP_TILE);
+  if (!A.mp_split || A.mp_tiles != nb) { env.fail(US_ERR_FORMAT_MISMATCH); return; }
   const size_t half = ((size_t)nb * 4 + 255) / 256 * 256;
   char *ws = (char *)ensure_workspace(env, A, 2 * half);
   if (!env.ok()) return;
@@ -144,12 +148,14 @@ static void spmv_compressed(Env &env, const us_formatted &A, const int32_t *ptr,
   float *carry_val = (float *)(ws + half);
   const double bytes = 8.0 * nnz + 4.0 * (nrows_stored + 1) + 4.0 * nnz /*x gather*/ + 4.0 * nrows_stored;
   if (row_ids) {
-    US_LAUNCH(env, "spmv_csr", bytes, (csr_spmv_kernel<true>), nb, MP_T, ptr, idx, val, row_ids, nrows_stored, nnz,
+    US_LAUNCH(env, "spmv_csr", bytes, (csr_spmv_kernel<true>), nb, MP_T, ptr, idx, val, row_ids,
+              (const int32_t *)A.mp_split, nrows_stored, nnz,
               x, y, accumulate ? 1 : 0, carry_row, carry_val);
     US_LAUNCH(env, "spmv_csr_fixup", 8.0 * nb, (csr_spmv_fixup_kernel<true>), ceil_div<int64_t>(nb, 256), 256,
               (const int32_t *)carry_row, (const float *)carry_val, nb, nrows_stored, row_ids, y);
   } else {
-    US_LAUNCH(env, "spmv_csr", bytes, (csr_spmv_kernel<false>), nb, MP_T, ptr, idx, val, row_ids, nrows_stored, nnz,
+    US_LAUNCH(env, "spmv_csr", bytes, (csr_spmv_kernel<false>), nb, MP_T, ptr, idx, val, row_ids,
+              (const int32_t *)A.mp_split, nrows_stored, nnz,
               x, y, accumulate ? 1 : 0, carry_row, carry_val);
     US_LAUNCH(env, "spmv_csr_fixup", 8.0 * nb, (csr_spmv_fixup_kernel<false>), ceil_div<int64_t>(nb, 256), 256,
               (const int32_t *)carry_row, (const float *)carry_val, nb, nrows_stored, row_ids, y);
@@ -220,6 +226,18 @@ __global__ __launch_bounds__(256) void bcsr_spmv_kernel(const int32_t *ptr, cons
     int64_t row = br * bh + r;
     if (lane == 0 && row < nrows) y[row] = (accumulate ? y[row] : 0.f) + s;
   }
+}
+
+void spmv_prepare(Env &env, us_formatted *f) {
+  if (f->swapped || (f->pattern != P_CSR && f->pattern != P_DCSR)) return;
+  const int64_t total = f->nmajor + f->nnz;
+  if (total == 0) return;
+  const int64_t nb = ceil_div<int64_t>(total, MP_TILE);
+  f->mp_split = env.owned<int32_t>(nb + 1);
+  f->mp_tiles = nb;
+  if (!env.ok()) return;
+  US_LAUNCH(env, "spmv_split", 4.0 * (nb + 1), merge_path_split_kernel, ceil_div<int64_t>(nb + 1, 256), 256,
+            (const int32_t *)f->level[1].ptr, f->nmajor, f->nnz, nb, f->mp_split);
 }
 
 us_status spmv_impl(Env &env, const us_formatted &A, const float *x, float *y, bool accumulate) {

@@ -67,7 +67,7 @@ def test_spmv_spmm_all_formats(ctx, name, desc):
     y = dev(y0)
     B.us_spmv(ctx, g, dev(x), y, accumulate=True)
     assert rel_err(host(y), yref + y0, scale + np.abs(y0)) <= TOL, name
-    for N in (1, 5, 64, 130):
+    for N in (1, 5, 64, 130, 260):
         X = rng.uniform(-1, 1, (nc, N)).astype(np.float32)
         Yref = O.spmm_coo(nr, nc, r, c, v, X)
         S = O.spmm_coo(nr, nc, r, c, np.abs(v), np.abs(X))
