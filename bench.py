@@ -25,6 +25,10 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix peak, published
+# HBM bytes per launch (fetched + written) of the dominant kernel on the headline workload, from the
+# two rocprofv3 --pmc runs summarised in profiles/config2_hbm_traffic_pmc.txt (mean over the five
+# scatter passes of a conversion; FETCH_SIZE x2.00, WRITE_SIZE x1.00 after calibration with a plain copy)
+PMC_TRAFFIC_BYTES = {"radix_scatter": 456.0e6}
 
 
 def parse():
@@ -34,6 +38,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--only-headline", action="store_true", help="skip the four other workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc", action="store_true",
+                    help="counter-collection workload: 3 plain copies of 256 MiB (calibration), then 3 headline steps")
     return ap.parse_args()
 
 
@@ -103,7 +109,19 @@ def main():
         B.us_spmv(ctx, b, x, y)
         a.free(); b.free()
 
-    ms_plain = timed(torch, step, max(3, K // 4), Wm)          # without event recording
+    if args.pmc:
+        a = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev).fill_(1.0)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            step()
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_workload": "3 copies of 268435456 B, then 3 headline steps", "nnz": nnz}))
+        return
+
+    # the timed steps: W warm-up, then exactly K, with a HIP event pair around every kernel launch
     ctx.enable_profile(); ctx.profile_reset()
     for _ in range(Wm):
         step()
@@ -115,12 +133,19 @@ def main():
     ms_step = (time.perf_counter() - t0) / K * 1e3
     rep = ctx.profile_report()
     ctx.disable_profile()
+    ms_plain = timed(torch, step, K, 1)          # the same K steps without event recording
     table = kernel_table(rep)
     dom = table[0]
     roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["gbps"], "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(dom["gbps"] / HBM_PEAK_GBS, 4),
                 "avg_launch_us": dom["avg_us"], "alg_bytes_per_launch": dom["alg_bytes_per_launch"],
-                "traffic": None}
+                "traffic": PMC_TRAFFIC_BYTES.get(dom["kernel"])}
+    # practical ceiling: a plain device-to-device copy of 256 MiB timed in the same run
+    ca = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev).fill_(1.0)
+    cb = torch.empty_like(ca)
+    ms_copy = timed(torch, lambda: cb.copy_(ca), 20, 3)
+    copy_gbps = 2 * ca.numel() * 4 / ms_copy / 1e6
+    del ca, cb
 
     # separate timings of the pieces (each its own timed loop)
     fa = B.us_convert(ctx, m.nrows, m.ncols, r, c, v, CSR)
@@ -142,6 +167,8 @@ def main():
                      "useful_frac_of_hbm": round(spmv_bytes / ms_spmv / 1e6 / HBM_PEAK_GBS, 4)},
         "spmv_dcsr": {"ms": round(ms_spmv_d, 4), "gflop_s": round(2.0 * nnz / ms_spmv_d / 1e6, 1)},
         "ms_per_step_without_event_recording": round(ms_plain, 4),
+        "mnnz_s_without_event_recording": round(nnz / ms_plain / 1e3, 1),
+        "device_copy_gbps": round(copy_gbps, 1),
         "kernels": table,
     }
     fa.free(); fb.free()

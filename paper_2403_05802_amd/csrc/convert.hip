@@ -579,35 +579,49 @@ __global__ __launch_bounds__(BE_T) void bcsr_emit_kernel(const uint64_t *key, co
                                                         int32_t *blk_col, float *bval) {
   __shared__ uint32_t s_wave[BE_T / 64 + 1];
   const int inner_bits = ks.ih_bits + ks.iw_bits;
-  int64_t base = (int64_t)blockIdx.x * BE_TILE + (int64_t)threadIdx.x * BE_IPT;
+  const int lane = lane_id();
+  // a wavefront owns 64*BE_IPT consecutive entries, lanes striped (coalesced loads); block ids
+  // come from ballots of the head flags, so no per-thread serial run is needed
+  const int64_t wbase = (int64_t)blockIdx.x * BE_TILE + (int64_t)wave_id() * (64 * BE_IPT);
   uint64_t k[BE_IPT];
-  uint32_t head[BE_IPT], heads = 0;
-  uint64_t prev = (base > 0 && base <= n) ? key[base - 1] : ~0ull;
+  uint64_t hb[BE_IPT];   // ballot of head flags of item j
+  uint32_t wave_total = 0;
+  uint64_t last_prev = (wbase > 0 && wbase <= n) ? key[wbase - 1] : ~0ull;  // key before the wave's slice
 #pragma unroll
   for (int j = 0; j < BE_IPT; ++j) {
-    int64_t i = base + j;
+    const int64_t i = wbase + j * 64 + lane;
     k[j] = i < n ? key[i] : ~0ull;
-    head[j] = (i < n) && ((i == 0) | ((k[j] >> inner_bits) != (prev >> inner_bits)));
-    heads += head[j];
-    prev = k[j];
+  }
+#pragma unroll
+  for (int j = 0; j < BE_IPT; ++j) {
+    const int64_t i = wbase + j * 64 + lane;
+    uint64_t prev = __shfl_up(k[j], 1);
+    if (lane == 0) prev = last_prev;
+    const bool head = (i < n) && ((i == 0) | ((k[j] >> inner_bits) != (prev >> inner_bits)));
+    hb[j] = __ballot(head);
+    wave_total += (uint32_t)__popcll(hb[j]);
+    last_prev = __shfl(k[j], 63);
   }
   uint32_t total;
-  uint32_t id = block_exclusive_sum<BE_T>(heads, s_wave, &total) + partial[blockIdx.x];  // blocks before
+  uint32_t wave_base = block_exclusive_sum<BE_T>(lane == 0 ? wave_total : 0u, s_wave, &total);
+  uint32_t run = __shfl(wave_base, 0) + partial[blockIdx.x];  // blocks before this wave's slice
   const uint32_t bsz = ks.bh * ks.bw;
 #pragma unroll
   for (int j = 0; j < BE_IPT; ++j) {
-    int64_t i = base + j;
-    if (i >= n) break;
-    id += head[j];
-    uint32_t blk = id - 1;
-    uint32_t bi = (uint32_t)(k[j] & ((1ull << ks.iw_bits) - 1));
-    uint32_t ai = (uint32_t)((k[j] >> ks.iw_bits) & ((1ull << ks.ih_bits) - 1));
-    uint64_t bk = k[j] >> inner_bits;
-    if (head[j]) {
-      blk_col[blk] = (int32_t)(bk & ((1ull << ks.b_bits) - 1));
-      blk_row[blk] = (int32_t)(bk >> ks.b_bits);
+    const int64_t i = wbase + j * 64 + lane;
+    if (i < n) {
+      const bool head = (hb[j] >> lane) & 1ull;
+      const uint32_t blk = run + (uint32_t)__popcll(hb[j] & (lanes_below() | (1ull << lane))) - 1;
+      const uint32_t bi = (uint32_t)(k[j] & ((1ull << ks.iw_bits) - 1));
+      const uint32_t ai = (uint32_t)((k[j] >> ks.iw_bits) & ((1ull << ks.ih_bits) - 1));
+      const uint64_t bk = k[j] >> inner_bits;
+      if (head) {
+        blk_col[blk] = (int32_t)(bk & ((1ull << ks.b_bits) - 1));
+        blk_row[blk] = (int32_t)(bk >> ks.b_bits);
+      }
+      bval[(size_t)blk * bsz + ai * ks.bw + bi] = val[i];
     }
-    bval[(size_t)blk * bsz + ai * ks.bw + bi] = val[i];
+    run += (uint32_t)__popcll(hb[j]);
   }
 }
 

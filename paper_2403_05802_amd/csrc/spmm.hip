@@ -116,9 +116,10 @@ __global__ __launch_bounds__(256) void ell_spmm_kernel(const int32_t *ecol, cons
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const bool ok = k0 + u < K;
-      col[u] = ok ? ecol[(k0 + u) * nrows + i] : -1;
-      v[u] = ok ? ev[(k0 + u) * nrows + i] : 0.f;
+      col[u] = ok ? __builtin_nontemporal_load(ecol + (k0 + u) * nrows + i) : -1;
+      v[u] = ok ? __builtin_nontemporal_load(ev + (k0 + u) * nrows + i) : 0.f;
     }
+    if (col[0] < 0) break;  // slots fill from the front: the row has ended (uniform: one row per wavefront)
 #pragma unroll
     for (int u = 0; u < U; ++u) xv[u] = *reinterpret_cast<const V *>(X + (int64_t)(col[u] < 0 ? 0 : col[u]) * ldx + c);
 #pragma unroll
@@ -185,8 +186,8 @@ __global__ __launch_bounds__(256) void coo_spmm_kernel(const int32_t *row, const
   constexpr int U = 8;
   for (int64_t base = e0; base < e1; base += 64) {
     const int64_t e = base + lane;
-    int32_t r = e < e1 ? row[e] : -1, cc = e < e1 ? col[e] : 0;
-    float v = e < e1 ? val[e] : 0.f;
+    int32_t r = e < e1 ? __builtin_nontemporal_load(row + e) : -1, cc = e < e1 ? __builtin_nontemporal_load(col + e) : 0;
+    float v = e < e1 ? __builtin_nontemporal_load(val + e) : 0.f;
     const int cnt = (int)min((int64_t)64, e1 - base);
     for (int t0 = 0; t0 < cnt; t0 += U) {
       int32_t rt[U];

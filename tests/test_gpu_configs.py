@@ -36,7 +36,7 @@ def check_spmv(ctx, parts, m, x):
 def check_spmm_rows(ctx, parts, m, X, rows):
     """Y = sum of parts * X on the GPU; the sampled rows are recomputed in fp64 one by one."""
     from paper_2403_05802_amd import binding as B
-    from helpers import TOL, dev, host
+    from helpers import FLOOR, TOL, dev, host
     Y = torch.full((m.nrows, X.shape[1]), -5.0, device="cuda")
     Xd = dev(X)
     for k, g in enumerate(parts):
@@ -52,7 +52,7 @@ def check_spmm_rows(ctx, parts, m, X, rows):
         v = m.val[e].astype(np.float64)
         ref = v @ X64[m.col[e]]
         scale = np.abs(v) @ np.abs(X64[m.col[e]])
-        den = np.maximum(np.abs(ref), scale * 2.0 ** -10)
+        den = np.maximum(np.abs(ref), scale * FLOOR)
         den[den == 0] = 1.0
         worst = max(worst, float(np.max(np.abs(Yh[t] - ref) / den)))
     assert worst <= TOL, worst
