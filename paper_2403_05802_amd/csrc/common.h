@@ -153,10 +153,6 @@ void sort_coo(Env &env, const int32_t *row, const int32_t *col, const float *val
               const KeySpec &ks, const SortOut &out, Flags *flags_dev);
 // ascending sort of 32-bit keys
 void sort_u32(Env &env, const uint32_t *key, int64_t n, int bits, uint32_t *out, Flags *flags_dev);
-// sort pre-built 64-bit keys
-void sort_keys(Env &env, const uint64_t *key, const float *val, int64_t nnz, const KeySpec &ks,
-               const SortOut &out, Flags *flags_dev);
-
 // convert.hip
 us_status convert_impl(Env &env, const us_coo &coo, const us_format_desc &desc, us_formatted **out);
 us_status decompose_impl(Env &env, const us_coo &coo, const us_format_desc &da, const us_format_desc &db,
