@@ -27,7 +27,7 @@ US_A_SIZE, US_A_PTR, US_A_IDX, US_A_VAL = range(4)
 
 EXPORTS = ["us_convert", "us_decompose", "us_spmv", "us_spmm", "us_formatted_array", "us_formatted_info",
            "us_free", "us_status_str", "us_desc_preset", "us_profile_create", "us_profile_destroy",
-           "us_profile_reset", "us_profile_collect", "us_profile_entry"]
+           "us_profile_reset", "us_profile_collect", "us_profile_entry", "us_profile_set_min_bytes"]
 
 
 class UnisparseError(RuntimeError):
@@ -99,6 +99,8 @@ def lib() -> C.CDLL:
         L.us_profile_destroy.argtypes = [C.c_void_p]
         L.us_profile_reset.argtypes = [C.c_void_p]
         L.us_profile_collect.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
+        L.us_profile_set_min_bytes.argtypes = [C.c_void_p, C.c_double]
+        L.us_profile_set_min_bytes.restype = C.c_int32
         L.us_profile_entry.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_int64),
                                        C.POINTER(C.c_double), C.POINTER(C.c_double)]
         for fn in ("us_desc_preset", "us_convert", "us_decompose", "us_spmv", "us_spmm", "us_formatted_array",
@@ -160,6 +162,9 @@ class Context:
             _check(lib().us_profile_create(C.byref(p)), "us_profile_create")
             self._profile = p
         self.c.profile = self._profile
+
+    def profile_min_bytes(self, min_bytes: float):
+        _check(lib().us_profile_set_min_bytes(self._profile, float(min_bytes)), "us_profile_set_min_bytes")
 
     def disable_profile(self):
         self.c.profile = None

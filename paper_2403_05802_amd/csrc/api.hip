@@ -155,6 +155,11 @@ us_status us_profile_reset(us_profile *p) {
   for (auto &e : p->p.entries) { e.launches = 0; e.ms = 0.0; e.bytes = 0.0; }
   return st;
 }
+us_status us_profile_set_min_bytes(us_profile *p, double min_bytes) {
+  if (!p) return US_ERR_NULL;
+  p->p.min_bytes = min_bytes;
+  return US_OK;
+}
 us_status us_profile_entry(const us_profile *p, int32_t i, const char **name, int64_t *launches, double *total_ms,
                            double *alg_bytes) {
   if (!p) return US_ERR_NULL;

@@ -29,6 +29,7 @@ struct Profile {
   std::vector<Pending> pending;
   std::vector<hipEvent_t> pool;
   std::vector<Entry> entries;
+  double min_bytes = 0.0;
   int intern(const char *name);
   hipEvent_t get_event();
 };

@@ -38,7 +38,7 @@ hipEvent_t Profile::get_event() {
 }
 
 LaunchScope::LaunchScope(Env &e, const char *name, double alg_bytes) : env(e), bytes(alg_bytes) {
-  if (!env.prof) return;
+  if (!env.prof || alg_bytes < env.prof->min_bytes) return;
   idx = env.prof->intern(name);
   a = env.prof->get_event();
   b = env.prof->get_event();

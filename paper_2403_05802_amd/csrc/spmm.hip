@@ -97,35 +97,53 @@ template <> struct VecT<1> { typedef float type; };
 template <> struct VecT<2> { typedef float type __attribute__((ext_vector_type(2))); };
 template <> struct VecT<4> { typedef float type __attribute__((ext_vector_type(4))); };
 
-// ELL: the slots of a row are independent gathers; 8 are issued before the first FMA.
+// ELL: a wavefront owns 8 consecutive rows.  One coalesced load brings the column indices of
+// 8 slots x 8 rows (lane = slot*8 + row), which are then broadcast one by one while every
+// lane gathers its columns of X: up to 64 independent 256/512-byte gathers per wavefront are
+// in flight, instead of one row's worth.  Pad slots gather row 0 (cached) and are not added.
 template <int VEC>
 __global__ __launch_bounds__(256) void ell_spmm_kernel(const int32_t *ecol, const float *ev, int64_t K, int64_t nrows,
                                                       const float *X, int64_t N, int64_t ldx, float *Y, int64_t ldy,
                                                       int accumulate) {
   typedef typename VecT<VEC>::type V;
-  const int64_t i = (int64_t)blockIdx.x * 4 + wave_id();
-  if (i >= nrows) return;
-  const int64_t c = ((int64_t)blockIdx.y * 64 + lane_id()) * VEC;
-  if (c >= N) return;
-  V s = accumulate ? *reinterpret_cast<const V *>(Y + i * ldy + c) : V(0.f);
-  constexpr int U = 8;
-  for (int64_t k0 = 0; k0 < K; k0 += U) {
-    int32_t col[U];
-    float v[U];
-    V xv[U];
+  const int lane = lane_id();
+  const int64_t i0 = ((int64_t)blockIdx.x * 4 + wave_id()) * 8;
+  if (i0 >= nrows) return;
+  const int64_t c = ((int64_t)blockIdx.y * 64 + lane) * VEC;
+  const bool col_ok = c < N;
+  V acc[8];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const bool ok = k0 + u < K;
-      col[u] = ok ? __builtin_nontemporal_load(ecol + (k0 + u) * nrows + i) : -1;
-      v[u] = ok ? __builtin_nontemporal_load(ev + (k0 + u) * nrows + i) : 0.f;
+  for (int r = 0; r < 8; ++r)
+    acc[r] = (accumulate && col_ok && i0 + r < nrows) ? *reinterpret_cast<const V *>(Y + (i0 + r) * ldy + c) : V(0.f);
+  const int my_slot = lane >> 3, my_row = lane & 7;
+  for (int64_t k0 = 0; k0 < K; k0 += 8) {
+    const int64_t kk = k0 + my_slot, i = i0 + my_row;
+    const bool ok = kk < K && i < nrows;
+    const int32_t mycol = ok ? __builtin_nontemporal_load(ecol + kk * nrows + i) : -1;
+    const float myval = ok ? __builtin_nontemporal_load(ev + kk * nrows + i) : 0.f;
+    if (__ballot(mycol >= 0) == 0) break;  // slots fill from the front: all 8 rows have ended
+#pragma unroll
+    for (int s8 = 0; s8 < 8; ++s8) {
+      int32_t cs[8];
+      float vs[8];
+      V xv[8];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        cs[r] = __builtin_amdgcn_readlane(mycol, s8 * 8 + r);
+        vs[r] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, myval), s8 * 8 + r));
+      }
+#pragma unroll
+      for (int r = 0; r < 8; ++r)
+        xv[r] = col_ok ? *reinterpret_cast<const V *>(X + (int64_t)(cs[r] < 0 ? 0 : cs[r]) * ldx + c) : V(0.f);
+#pragma unroll
+      for (int r = 0; r < 8; ++r) acc[r] += cs[r] >= 0 ? vs[r] * xv[r] : V(0.f);
     }
-    if (col[0] < 0) break;  // slots fill from the front: the row has ended (uniform: one row per wavefront)
-#pragma unroll
-    for (int u = 0; u < U; ++u) xv[u] = *reinterpret_cast<const V *>(X + (int64_t)(col[u] < 0 ? 0 : col[u]) * ldx + c);
-#pragma unroll
-    for (int u = 0; u < U; ++u) s += col[u] >= 0 ? v[u] * xv[u] : V(0.f);
   }
-  *reinterpret_cast<V *>(Y + i * ldy + c) = s;
+  if (col_ok) {
+#pragma unroll
+    for (int r = 0; r < 8; ++r)
+      if (i0 + r < nrows) *reinterpret_cast<V *>(Y + (i0 + r) * ldy + c) = acc[r];
+  }
 }
 
 __global__ __launch_bounds__(256) void csr_spmm_kernel(const int32_t *ptr, const int32_t *idx, const float *val,
@@ -317,7 +335,7 @@ us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, 
     case P_ELL:
       if (env.ok()) {
         LaunchScope ls(env, "spmm_ell", 8.0 * A.nval + xy);
-        const dim3 grid((unsigned)ceil_div<int64_t>(A.nrows, 4), (unsigned)ceil_div<int64_t>(N, 64 * vec));
+        const dim3 grid((unsigned)ceil_div<int64_t>(A.nrows, 32), (unsigned)ceil_div<int64_t>(N, 64 * vec));
         const int32_t *ec = A.level[2].idx;
         if (vec == 4) hipLaunchKernelGGL(ell_spmm_kernel<4>, grid, dim3(256), 0, env.stream, ec, (const float *)A.val, A.nmajor, A.nrows, X, N, ldx, Y, ldy, acc);
         else if (vec == 2) hipLaunchKernelGGL(ell_spmm_kernel<2>, grid, dim3(256), 0, env.stream, ec, (const float *)A.val, A.nmajor, A.nrows, X, N, ldx, Y, ldy, acc);

@@ -51,8 +51,26 @@ __global__ __launch_bounds__(MP_T) void csr_spmv_kernel(const int32_t *ptr, cons
   const int64_t r0 = split[blockIdx.x], r1 = split[blockIdx.x + 1];
   const int64_t z0 = diag0 - r0, z1 = diag1 - r1;
   const int nr = (int)(r1 - r0), nz = (int)(z1 - z0);
-  for (int i = threadIdx.x; i < nz; i += MP_T) s_prod[i] = val[z0 + i] * x[idx[z0 + i]];
-  for (int i = threadIdx.x; i < nr; i += MP_T) s_end[i] = (int32_t)(row_end[r0 + i] - z0);
+  {  // all index/value loads first, then all gathers of x: two round trips instead of sixteen
+    int32_t ci[MP_IPT];
+    float vv[MP_IPT], xv[MP_IPT];
+    int32_t re[MP_IPT];
+#pragma unroll
+    for (int k = 0; k < MP_IPT; ++k) {
+      const int i = k * MP_T + threadIdx.x;
+      ci[k] = i < nz ? idx[z0 + i] : 0;
+      vv[k] = i < nz ? val[z0 + i] : 0.f;
+      re[k] = i < nr ? row_end[r0 + i] : 0;
+    }
+#pragma unroll
+    for (int k = 0; k < MP_IPT; ++k) xv[k] = (k * MP_T + (int)threadIdx.x) < nz ? x[ci[k]] : 0.f;
+#pragma unroll
+    for (int k = 0; k < MP_IPT; ++k) {
+      const int i = k * MP_T + threadIdx.x;
+      if (i < nz) s_prod[i] = vv[k] * xv[k];
+      if (i < nr) s_end[i] = (int32_t)(re[k] - z0);
+    }
+  }
   __syncthreads();
 
   // this thread's slice of the tile's merge sequence
@@ -274,11 +292,13 @@ us_status spmv_impl(Env &env, const us_formatted &A, const float *x, float *y, b
                 (const float *)A.val, A.nmajor, (int)A.bh, (int)A.bw, A.nrows, A.ncols, x, y, accumulate ? 1 : 0);
       return env.status;
     case P_COO:
+      // row-major COO: the entry-balanced SpMM kernel with one column (fixed summation order);
+      // column-major COO scatters with float atomics
+      if (!A.swapped) return spmm_impl(env, A, x, 1, 1, y, 1, accumulate);
       if (!accumulate) fill_u32(env, (uint32_t *)y, A.nrows, 0u);
       if (A.nnz > 0)
-        US_LAUNCH(env, "spmv_coo", 16.0 * A.nnz, coo_spmv_atomic_kernel, ceil_div<int64_t>(A.nnz, 256), 256,
-                  (const int32_t *)(A.swapped ? A.level[1].idx : A.level[0].idx),
-                  (const int32_t *)(A.swapped ? A.level[0].idx : A.level[1].idx), (const float *)A.val, A.nnz, x, y);
+        US_LAUNCH(env, "spmv_coo_atomic", 16.0 * A.nnz, coo_spmv_atomic_kernel, ceil_div<int64_t>(A.nnz, 256), 256,
+                  (const int32_t *)A.level[1].idx, (const int32_t *)A.level[0].idx, (const float *)A.val, A.nnz, x, y);
       return env.status;
     default: break;
   }

@@ -1,0 +1,133 @@
+"""HIP library vs oracle: degenerate shapes of the method, determinism, empty parts."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import unisparse_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    from paper_2403_05802_amd import binding as B
+    return B.Context("cuda:0")
+
+
+def roundtrip(ctx, nr, nc, r, c, v, descs):
+    from paper_2403_05802_amd import binding as B
+    from helpers import assert_same_layout, dev, us_desc_of
+    for d in descs:
+        o = O.convert(nr, nc, r, c, v, d)
+        g = B.us_convert(ctx, nr, nc, dev(r), dev(c), dev(v), us_desc_of(d))
+        assert_same_layout(g, o, str(d.levels))
+        g.free()
+
+
+def test_all_entries_in_one_row_and_one_column(ctx):
+    """A row (column) longer than several sort tiles and SpMV tiles."""
+    rng = np.random.default_rng(1)
+    n = 70_000
+    cols = rng.permutation(n)[:50_000].astype(np.int32)
+    rows = np.full(cols.size, 12345, np.int32)
+    v = rng.uniform(0.5, 1, cols.size).astype(np.float32)
+    roundtrip(ctx, n, n, rows, cols, v, [O.CSR(), O.DCSR(), O.COO(), O.CSC(), O.BCSR(4)])
+    roundtrip(ctx, n, n, cols, rows, v, [O.CSR(), O.DCSR(), O.CSC(), O.DCSC()])
+    from paper_2403_05802_amd import binding as B
+    from helpers import TOL, dev, host, rel_err, us_desc_of
+    x = rng.uniform(-1, 1, n).astype(np.float32)
+    for d in (O.CSR(), O.DCSR(), O.COO()):
+        g = B.us_convert(ctx, n, n, dev(rows), dev(cols), dev(v), us_desc_of(d))
+        y = torch.empty(n, device="cuda")
+        B.us_spmv(ctx, g, dev(x), y)
+        assert rel_err(host(y), O.spmv_coo(n, n, rows, cols, v, x), O.abs_row_sums(n, rows, cols, v, x)) <= TOL
+        X = rng.uniform(-1, 1, (n, 128)).astype(np.float32)
+        Y = torch.empty(n, 128, device="cuda")
+        B.us_spmm(ctx, g, dev(X), Y)
+        ref = v.astype(np.float64) @ X[cols].astype(np.float64)
+        got = host(Y[12345])
+        assert np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 2.0 ** -4 * (np.abs(v) @ np.abs(X[cols])))) <= TOL
+        assert float(Y.abs().sum()) == pytest.approx(float(np.abs(got).sum()), rel=1e-5)   # other rows are zero
+        g.free()
+
+
+def test_single_full_diagonal_and_far_corners(ctx):
+    n = 5000
+    i = np.arange(n, dtype=np.int32)
+    v = np.linspace(0.1, 1, n).astype(np.float32)
+    roundtrip(ctx, n, n, i, i, v, [O.DIA(), O.DIA_VARIANT(), O.CSR(), O.ELL(), O.BCSR(8)])
+    # two entries in opposite corners: offsets -(n-1) and +(n-1), almost all rows empty
+    r = np.array([0, n - 1], np.int32); c = np.array([n - 1, 0], np.int32); w = np.array([2, 3], np.float32)
+    roundtrip(ctx, n, n, r, c, w, [O.DIA(), O.DIA_VARIANT(), O.CSR(), O.DCSR(), O.ELL(), O.BCSR(2)])
+    # non-square
+    roundtrip(ctx, 40, 3000, np.array([0, 39, 7], np.int32), np.array([2999, 0, 7], np.int32),
+              np.array([1, 2, 3], np.float32), [O.DIA(), O.DIA_VARIANT(), O.CSR(), O.CSC(), O.BCSR(4, 2)])
+
+
+def test_duplicates_on_the_sort_free_dia_path(ctx):
+    from paper_2403_05802_amd import binding as B
+    from helpers import dev, us_desc_of, us_pred_of
+    n = 3000
+    i = np.arange(n, dtype=np.int32)
+    r = np.concatenate([i, i[100:101]]); c = np.concatenate([i, i[100:101]])
+    v = np.ones(r.size, np.float32)                       # identical duplicate: same slot, same value
+    with pytest.raises(B.UnisparseError) as ei:
+        B.us_convert(ctx, n, n, dev(r), dev(c), dev(v), us_desc_of(O.DIA()))
+    assert ei.value.code == "US_ERR_DUPLICATE"
+    pred = O.Predicate((O.diag(),), O.SUM_GE_FRAC_OF_CAPACITY, num=9, den=10)
+    with pytest.raises(B.UnisparseError) as ei:
+        B.us_decompose(ctx, n, n, dev(r), dev(c), dev(v), us_desc_of(O.DIA()), us_desc_of(O.CSR()), us_pred_of(pred))
+    assert ei.value.code == "US_ERR_DUPLICATE"
+
+
+def test_decompose_with_an_empty_part(ctx):
+    from paper_2403_05802_amd import binding as B
+    from helpers import assert_same_layout, dev, us_desc_of, us_pred_of
+    rng = np.random.default_rng(3)
+    n = 400
+    lin = rng.choice(n * n, 3000, replace=False)
+    r, c = (lin // n).astype(np.int32), (lin % n).astype(np.int32)
+    v = rng.uniform(0.1, 1, r.size).astype(np.float32)
+    cases = [
+        (O.DIA(), O.CSR(), O.Predicate((O.diag(),), O.SUM_GE_ABS, abs=10 ** 6)),     # nothing goes to A
+        (O.CSR(), O.COO(), O.Predicate((O.d0(),), O.SUM_GE_ABS, abs=0)),             # everything goes to A
+        (O.ELL(), O.COO(), O.Predicate((O.d0(),), O.RANK_LT_ABS, abs=0)),            # K = 0
+        (O.ELL(), O.CSR(), O.Predicate((O.d0(),), O.RANK_LT_PERCENTILE, num=1, den=1)),  # K = longest row
+        (O.CSC(), O.DCSR(), O.Predicate((O.d1(),), O.SUM_GE_ABS, abs=9)),            # column groups
+    ]
+    for da, db, pred in cases:
+        oa, ob, _ = O.decompose(n, n, r, c, v, da, db, pred)
+        ga, gb = B.us_decompose(ctx, n, n, dev(r), dev(c), dev(v), us_desc_of(da), us_desc_of(db), us_pred_of(pred))
+        assert_same_layout(ga, oa, f"A {pred.kind}")
+        assert_same_layout(gb, ob, f"B {pred.kind}")
+
+
+def test_results_are_reproducible_bit_for_bit(ctx):
+    """Two runs of every path give identical bytes: the row-major layouts never add floats
+    with atomics (only the column-major scatter forms do), integer atomics only count."""
+    from paper_2403_05802_amd import binding as B
+    from paper_2403_05802_amd import workloads as W
+    from helpers import coo_to_dev, dev, us_desc_of, us_pred_of
+    m = W.cfg5_powerlaw_local(n=40_000, target_nnz=800_000, max_len=6000)
+    d = coo_to_dev(m)
+    x = dev(W.dense_operand(5, m.ncols)); X = dev(W.dense_operand(5, (m.ncols, 128)))
+    pred = us_pred_of(O.Predicate((O.d0(),), O.RANK_LT_PERCENTILE, num=9, den=10))
+
+    def run():
+        out = []
+        for desc in (O.CSR(), O.DCSR(), O.BCSR(4), O.ELL(), O.COO()):
+            g = B.us_convert(ctx, m.nrows, m.ncols, *d, us_desc_of(desc))
+            y = torch.empty(m.nrows, device="cuda"); Y = torch.empty(m.nrows, 128, device="cuda")
+            B.us_spmv(ctx, g, x, y); B.us_spmm(ctx, g, X, Y)
+            out += [g.val().clone(), y, Y] + [t.clone() for L in range(g.desc.nlevels)
+                                              for t in (g.ptr(L), g.idx(L)) if t is not None]
+        ga, gb = B.us_decompose(ctx, m.nrows, m.ncols, *d, us_desc_of(O.ELL()), us_desc_of(O.COO()), pred)
+        Y = torch.empty(m.nrows, 128, device="cuda")
+        B.us_spmm(ctx, ga, X, Y); B.us_spmm(ctx, gb, X, Y, accumulate=True)
+        out += [ga.val().clone(), gb.val().clone(), Y]
+        return out
+
+    a, b = run(), run()
+    assert len(a) == len(b)
+    for s, t in zip(a, b):
+        assert s.dtype == t.dtype and torch.equal(s.view(torch.int32), t.view(torch.int32))
