@@ -117,6 +117,14 @@ typedef struct us_formatted us_formatted; /* opaque; owns arrays obtained throug
  * Errors: NULL, SHAPE, INDEX_RANGE, DUPLICATE, UNSUPPORTED_DESC, OVERFLOW, ALLOC, HIP. */
 us_status us_convert(const us_ctx *ctx, const us_coo *coo, const us_format_desc *target, us_formatted **out);
 
+/* Conversion between any two supported formats through the COO hub (Section 5.2: reversibility
+ * and reachability; the cases of Table 5 such as CSR->CSC or DCSC->BCSR): the source is expanded
+ * back to COO on the device (Split of ptr levels, inverse index map, bounds guard; slots of dense
+ * levels holding +-0.0 and ELL pads are padding and are dropped), then converted as by us_convert.
+ * The source is left untouched. */
+us_status us_convert_formatted(const us_ctx *ctx, const us_formatted *src, const us_format_desc *target,
+                               us_formatted **out);
+
 /* decompose + convert of a hybrid (Figure 3c lines "decompose" and "convert"): entries that
  * satisfy `pred` form part A (stored as desc_a), the rest part B (desc_b).  Both parts keep
  * the shape of the whole matrix, so A*x = out_a*x + out_b*x. */

@@ -25,7 +25,7 @@ US_F_COO, US_F_CSR, US_F_DCSR, US_F_CSC, US_F_DCSC, US_F_DIA, US_F_DIA_VARIANT, 
 US_P_SUM_GE_ABS, US_P_SUM_GE_FRAC_OF_CAPACITY, US_P_RANK_LT_ABS, US_P_RANK_LT_PERCENTILE = range(4)
 US_A_SIZE, US_A_PTR, US_A_IDX, US_A_VAL = range(4)
 
-EXPORTS = ["us_convert", "us_decompose", "us_spmv", "us_spmm", "us_formatted_array", "us_formatted_info",
+EXPORTS = ["us_convert", "us_convert_formatted", "us_decompose", "us_spmv", "us_spmm", "us_formatted_array", "us_formatted_info",
            "us_free", "us_status_str", "us_desc_preset", "us_profile_create", "us_profile_destroy",
            "us_profile_reset", "us_profile_collect", "us_profile_entry", "us_profile_set_min_bytes"]
 
@@ -82,6 +82,9 @@ def lib() -> C.CDLL:
         L.us_desc_preset.argtypes = [C.c_int32, C.c_int64, C.c_int64, C.POINTER(us_format_desc)]
         L.us_convert.argtypes = [C.POINTER(us_ctx), C.POINTER(us_coo), C.POINTER(us_format_desc),
                                  C.POINTER(C.c_void_p)]
+        L.us_convert_formatted.argtypes = [C.POINTER(us_ctx), C.c_void_p, C.POINTER(us_format_desc),
+                                           C.POINTER(C.c_void_p)]
+        L.us_convert_formatted.restype = C.c_int32
         L.us_decompose.argtypes = [C.POINTER(us_ctx), C.POINTER(us_coo), C.POINTER(us_format_desc),
                                    C.POINTER(us_format_desc), C.POINTER(us_predicate),
                                    C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]
@@ -283,6 +286,12 @@ def us_convert(ctx: Context, nrows: int, ncols: int, row, col, val, desc: us_for
     coo = _coo_struct(nrows, ncols, row, col, val)
     out = C.c_void_p()
     _check(lib().us_convert(C.byref(ctx.c), C.byref(coo), C.byref(desc), C.byref(out)), "us_convert")
+    return Formatted(ctx, out.value)
+
+
+def us_convert_formatted(ctx: Context, src: Formatted, desc: us_format_desc) -> Formatted:
+    out = C.c_void_p()
+    _check(lib().us_convert_formatted(C.byref(ctx.c), src.handle, C.byref(desc), C.byref(out)), "us_convert_formatted")
     return Formatted(ctx, out.value)
 
 

@@ -66,6 +66,14 @@ us_status us_convert(const us_ctx *ctx, const us_coo *coo, const us_format_desc 
   return convert_impl(env, *coo, *target, out);
 }
 
+us_status us_convert_formatted(const us_ctx *ctx, const us_formatted *src, const us_format_desc *target,
+                               us_formatted **out) {
+  if (out) *out = nullptr;
+  if (!ctx || !src || !target || !out) return US_ERR_NULL;
+  Env env(ctx);
+  return convert_formatted_impl(env, *src, *target, out);
+}
+
 us_status us_decompose(const us_ctx *ctx, const us_coo *coo, const us_format_desc *desc_a,
                        const us_format_desc *desc_b, const us_predicate *pred, us_formatted **out_a,
                        us_formatted **out_b) {

@@ -159,6 +159,7 @@ us_status convert_impl(Env &env, const us_coo &coo, const us_format_desc &desc, 
 us_status decompose_impl(Env &env, const us_coo &coo, const us_format_desc &da, const us_format_desc &db,
                          const us_predicate &pred, us_formatted **oa, us_formatted **ob);
 void free_formatted(Env &env, us_formatted *f);
+us_status convert_formatted_impl(Env &env, const us_formatted &src, const us_format_desc &desc, us_formatted **out);
 
 // device scratch attached to a formatted tensor, at least `bytes` large (contents undefined)
 void *ensure_workspace(Env &env, const us_formatted &A, size_t bytes);

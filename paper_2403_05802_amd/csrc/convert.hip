@@ -718,6 +718,123 @@ us_status convert_impl(Env &env, const us_coo &coo, const us_format_desc &desc, 
   return s;
 }
 
+// ------------------------------------------------------------------ formatted -> COO (the hub of Section 5.2)
+// Every format whose encoding uses only direct index maps and mutation primitives converts
+// back to COO (reversibility, Section 5.2): Split re-expands a ptr level into one parent index
+// per child, Trim drops the padding of dense inner levels, TileUnion re-joins (d/b, d%b), and
+// the inverse index map restores (d0, d1).  ELL is read back as well (its column level stores
+// d1).  Slots of dense levels that hold +-0.0 are padding and are dropped.
+// Step 1 flags the slots that carry an entry, a scan gives their positions, step 2 writes.
+struct SrcView {
+  int pattern, swapped;
+  int64_t nrows, ncols, nslots, nmajor, bh, bw;
+  const int32_t *ptr, *idx, *idx0;  // ptr/idx of the compressed level; idx0: stored rows (DCSR) / offsets (DIA)
+  const float *val;
+};
+
+// upper_bound(ptr, e) - 1: the parent whose segment [ptr[p], ptr[p+1]) holds child e
+__device__ __forceinline__ int64_t parent_of(const int32_t *ptr, int64_t nparents, int64_t e) {
+  int64_t lo = 0, hi = nparents;
+  while (lo < hi) {
+    int64_t mid = (lo + hi) >> 1;
+    if ((int64_t)ptr[mid + 1] <= e) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+__device__ __forceinline__ bool slot_entry(const SrcView &v, int64_t s, int32_t *r, int32_t *c, float *x) {
+  int64_t a, b;  // major, minor logical indices before undoing a swap
+  float val = v.val[s];
+  switch (v.pattern) {
+    case P_COO: a = v.idx0[s]; b = v.idx[s]; break;
+    case P_CSR: a = parent_of(v.ptr, v.nmajor, s); b = v.idx[s]; break;
+    case P_DCSR: a = v.idx0[parent_of(v.ptr, v.nmajor, s)]; b = v.idx[s]; break;
+    case P_DIA: {
+      const int64_t L = v.swapped ? v.ncols : v.nrows, k = s / L, i = s - k * L, off = v.idx0[k];
+      const int64_t row = v.swapped ? i - off : i, col = v.swapped ? i : i + off;
+      if (val == 0.f || row < 0 || row >= v.nrows || col < 0 || col >= v.ncols) return false;
+      *r = (int32_t)row; *c = (int32_t)col; *x = val;
+      return true;
+    }
+    case P_BCSR: {
+      const int64_t bsz = v.bh * v.bw, blk = s / bsz, in = s - blk * bsz, ri = in / v.bw, ci = in - ri * v.bw;
+      const int64_t row = parent_of(v.ptr, v.nmajor, blk) * v.bh + ri, col = (int64_t)v.idx[blk] * v.bw + ci;
+      if (val == 0.f || row >= v.nrows || col >= v.ncols) return false;
+      *r = (int32_t)row; *c = (int32_t)col; *x = val;
+      return true;
+    }
+    case P_ELL: {
+      const int64_t k = s / v.nrows, i = s - k * v.nrows;
+      if (v.idx[s] < 0 || val == 0.f) return false;
+      *r = (int32_t)i; *c = v.idx[s]; *x = val;
+      return true;
+    }
+    default: return false;
+  }
+  *r = (int32_t)(v.swapped ? b : a); *c = (int32_t)(v.swapped ? a : b); *x = val;
+  return true;
+}
+
+__global__ __launch_bounds__(256) void expand_flag_kernel(SrcView v, int32_t *flag) {
+  int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (s >= v.nslots) return;
+  int32_t r, c; float x;
+  flag[s] = slot_entry(v, s, &r, &c, &x) ? 1 : 0;
+}
+__global__ __launch_bounds__(256) void expand_write_kernel(SrcView v, const int32_t *flag, const int32_t *pos,
+                                                          int32_t *row, int32_t *col, float *val) {
+  int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (s >= v.nslots || !flag[s]) return;
+  int32_t r, c; float x;
+  slot_entry(v, s, &r, &c, &x);
+  row[pos[s]] = r; col[pos[s]] = c; val[pos[s]] = x;
+}
+
+us_status convert_formatted_impl(Env &env, const us_formatted &src, const us_format_desc &desc, us_formatted **out) {
+  *out = nullptr;
+  Plan plan;
+  if (!match_desc(desc, &plan)) return US_ERR_UNSUPPORTED_DESC;
+  if (plan.pattern == P_ELL && plan.swapped) return US_ERR_UNSUPPORTED_DESC;
+  SrcView v{};
+  v.pattern = src.pattern; v.swapped = src.swapped ? 1 : 0;
+  v.nrows = src.nrows; v.ncols = src.ncols; v.nslots = src.nval; v.nmajor = src.nmajor;
+  v.bh = src.bh; v.bw = src.bw; v.val = src.val;
+  switch (src.pattern) {
+    case P_COO: v.idx0 = src.level[0].idx; v.idx = src.level[1].idx; break;
+    case P_CSR: v.ptr = src.level[1].ptr; v.idx = src.level[1].idx; break;
+    case P_DCSR: v.idx0 = src.level[0].idx; v.ptr = src.level[1].ptr; v.idx = src.level[1].idx; break;
+    case P_DIA: v.idx0 = src.level[0].idx; break;
+    case P_BCSR: v.ptr = src.level[1].ptr; v.idx = src.level[1].idx; break;
+    case P_ELL: v.idx = src.level[2].idx; break;
+    default: return US_ERR_FORMAT_MISMATCH;
+  }
+  const int64_t ns = v.nslots;
+  Flags *flags = new_flags(env);
+  int32_t *flag = env.temp<int32_t>(ns), *pos = env.temp<int32_t>(ns);
+  if (!env.ok()) return env.status;
+  if (ns > 0)
+    US_LAUNCH(env, "expand_flag", 8.0 * ns, expand_flag_kernel, ceil_div<int64_t>(ns, 256), 256, v, flag);
+  exclusive_scan_i32(env, flag, pos, ns, &flags->scalar[0]);
+  Flags h{};
+  if (!read_flags(env, flags, &h)) return env.status;
+  const int64_t n = ns > 0 ? h.scalar[0] : 0;
+  CooLists l = alloc_lists(env, n);
+  us_status st = env.status;
+  if (st == US_OK && ns > 0)
+    US_LAUNCH(env, "expand_write", 12.0 * ns + 12.0 * n, expand_write_kernel, ceil_div<int64_t>(ns, 256), 256, v,
+              (const int32_t *)flag, (const int32_t *)pos, l.r, l.c, l.v);
+  if (st == US_OK) st = env.status;
+  if (st == US_OK) {
+    us_coo coo{src.nrows, src.ncols, n, l.r, l.c, l.v};
+    st = convert_with_plan(env, coo, plan, desc, out);
+  }
+  env.sync();
+  free_lists(env, l);
+  if (st == US_OK && !env.ok()) st = env.status;
+  if (st != US_OK && *out) { free_formatted(env, *out); *out = nullptr; }
+  return st;
+}
+
 // ------------------------------------------------------------------ decompose
 __global__ __launch_bounds__(256) void row_len_kernel(const int32_t *ptr, int64_t n, uint32_t *len) {
   int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;

@@ -198,26 +198,34 @@ __global__ __launch_bounds__(RS_T) void radix_scatter_kernel(PassArgs a) {
   }
   __syncthreads();
 
-  // stable rank of every item among the items of its wave with the same digit
+  // stable rank of every item among the items of its wave with the same digit.
+  // peers = lanes holding the same digit = AND over the digit's bits of (bit ? ballot : ~ballot);
+  // per bit that is one compare (the ballot), one sign-mask and one 3-input logic op per half.
+  const uint32_t lane_lo = lane < 32 ? (1u << lane) - 1u : 0xFFFFFFFFu;   // lanes below this one
+  const uint32_t lane_hi = lane < 32 ? 0u : (1u << (lane - 32)) - 1u;
 #pragma unroll
   for (int j = 0; j < RS_IPT; ++j) {
     uint32_t t = w * (64 * RS_IPT) + j * 64 + lane;
     bool valid = t < in_tile;
     uint32_t d = (uint32_t)(key[j] >> a.shift) & a.mask;
-    uint64_t peers = __ballot(valid);
+    uint64_t vb = __ballot(valid);
+    uint32_t plo = (uint32_t)vb, phi = (uint32_t)(vb >> 32);
 #pragma unroll
     for (int b = 0; b < RS_MAXBITS; ++b) {
-      uint64_t bal = __ballot((d >> b) & 1u);
-      peers &= ((d >> b) & 1u) ? bal : ~bal;
+      const uint64_t bal = __ballot((d >> b) & 1u);
+      const uint32_t keep = (uint32_t)((int32_t)(~d << (31 - b)) >> 31);   // all ones when bit b of d is 0
+      plo &= (uint32_t)bal ^ keep;
+      phi &= (uint32_t)(bal >> 32) ^ keep;
     }
-    uint32_t before = __popcll(peers & lanes_below());
-    int leader = __ffsll((unsigned long long)peers) - 1;
+    uint32_t before = __popc(plo & lane_lo) + __popc(phi & lane_hi);
+    uint32_t count = __popc(plo) + __popc(phi);
+    int leader = plo ? __ffs(plo) - 1 : (phi ? __ffs(phi) + 31 : 0);
     uint32_t old = 0;
     if (valid && lane == leader) {
       old = s_cnt[w][d];
-      s_cnt[w][d] = old + (uint32_t)__popcll(peers);
+      s_cnt[w][d] = old + count;
     }
-    old = __shfl(old, leader < 0 ? 0 : leader);
+    old = __shfl(old, leader);
     pos[j] = old + before;
     __builtin_amdgcn_wave_barrier();
   }
