@@ -732,16 +732,6 @@ struct SrcView {
   const float *val;
 };
 
-// upper_bound(ptr, e) - 1: the parent whose segment [ptr[p], ptr[p+1]) holds child e
-__device__ __forceinline__ int64_t parent_of(const int32_t *ptr, int64_t nparents, int64_t e) {
-  int64_t lo = 0, hi = nparents;
-  while (lo < hi) {
-    int64_t mid = (lo + hi) >> 1;
-    if ((int64_t)ptr[mid + 1] <= e) lo = mid + 1; else hi = mid;
-  }
-  return lo;
-}
-
 __device__ __forceinline__ bool slot_entry(const SrcView &v, int64_t s, int32_t *r, int32_t *c, float *x) {
   int64_t a, b;  // major, minor logical indices before undoing a swap
   float val = v.val[s];

@@ -49,4 +49,14 @@ __device__ __forceinline__ uint32_t block_exclusive_sum(uint32_t v, uint32_t *s_
   return res;
 }
 
+// upper_bound(ptr, e) - 1: the parent whose segment [ptr[p], ptr[p+1]) holds child e
+__device__ __forceinline__ int64_t parent_of(const int32_t *ptr, int64_t nparents, int64_t e) {
+  int64_t lo = 0, hi = nparents;
+  while (lo < hi) {
+    int64_t mid = (lo + hi) >> 1;
+    if ((int64_t)ptr[mid + 1] <= e) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
 }  // namespace us

@@ -174,14 +174,28 @@ __global__ __launch_bounds__(256) void dia_spmm_kernel(const int32_t *off, const
   Y[i * ldy + c] = s;
 }
 
-// ------------------------------------------------------------------ COO sorted by row: equal shares of non-zeros per wavefront
+// ------------------------------------------------------------------ entries grouped by row (COO sorted by row, CSR, DCSR): equal shares of non-zeros per wavefront
+// The row of entry e is read from the COO row array, or found in ptr (plus the stored-row list
+// for DCSR), so a 20,000-entry row costs the same as 20,000 one-entry rows.
+struct RowSrc {
+  const int32_t *row;   // COO: row of every entry, else null
+  const int32_t *ptr;   // CSR / DCSR: children of parent p are [ptr[p], ptr[p+1])
+  const int32_t *ids;   // DCSR: row index of parent p, else null
+  int64_t nparents;
+  __device__ __forceinline__ int32_t of(int64_t e) const {
+    if (row) return __builtin_nontemporal_load(row + e);
+    int64_t p = parent_of(ptr, nparents, e);
+    return ids ? ids[p] : (int32_t)p;
+  }
+};
+
 // A wavefront walks CS_CHUNK consecutive entries; for each it adds val * X[col, :] into a
 // register accumulator and flushes when the row changes.  Row pieces cut by a chunk boundary
 // go to a carry buffer and are summed in chunk order by the fix-up kernel (reproducible).
 constexpr int CS_CHUNK = 512;
 
 template <int VEC>
-__global__ __launch_bounds__(256) void coo_spmm_kernel(const int32_t *row, const int32_t *col, const float *val,
+__global__ __launch_bounds__(256) void coo_spmm_kernel(RowSrc row, const int32_t *col, const float *val,
                                                       int64_t nnz, const float *X, int64_t N, int64_t ldx, float *Y,
                                                       int64_t ldy, int32_t *carry_row, float *carry) {
   typedef typename VecT<VEC>::type V;
@@ -192,9 +206,9 @@ __global__ __launch_bounds__(256) void coo_spmm_kernel(const int32_t *row, const
   const int64_t e1 = min(e0 + CS_CHUNK, nnz);
   const int64_t c = ((int64_t)blockIdx.y * 64 + lane) * VEC;
   const bool col_ok = c < N;
-  const int32_t row_before = e0 > 0 ? row[e0 - 1] : -1;
-  const int32_t row_after = e1 < nnz ? row[e1] : -1;
-  const int32_t first_row = row[e0], last_row = row[e1 - 1];
+  const int32_t row_before = e0 > 0 ? row.of(e0 - 1) : -1;
+  const int32_t row_after = e1 < nnz ? row.of(e1) : -1;
+  const int32_t first_row = row.of(e0), last_row = row.of(e1 - 1);
   V *carry_head = reinterpret_cast<V *>(carry + ((chunk * 2 + 0) * gridDim.y + blockIdx.y) * (64 * VEC)) + lane;
   V *carry_tail = reinterpret_cast<V *>(carry + ((chunk * 2 + 1) * gridDim.y + blockIdx.y) * (64 * VEC)) + lane;
   const bool head_cut = first_row == row_before, tail_cut = last_row == row_after;
@@ -204,7 +218,7 @@ __global__ __launch_bounds__(256) void coo_spmm_kernel(const int32_t *row, const
   constexpr int U = 8;
   for (int64_t base = e0; base < e1; base += 64) {
     const int64_t e = base + lane;
-    int32_t r = e < e1 ? __builtin_nontemporal_load(row + e) : -1, cc = e < e1 ? __builtin_nontemporal_load(col + e) : 0;
+    int32_t r = e < e1 ? row.of(e) : -1, cc = e < e1 ? __builtin_nontemporal_load(col + e) : 0;
     float v = e < e1 ? __builtin_nontemporal_load(val + e) : 0.f;
     const int cnt = (int)min((int64_t)64, e1 - base);
     for (int t0 = 0; t0 < cnt; t0 += U) {
@@ -303,6 +317,37 @@ static void zero_rows(Env &env, float *Y, int64_t nrows, int64_t N, int64_t ldy)
   for (int64_t i = 0; i < nrows && env.ok(); ++i) fill_u32(env, (uint32_t *)(Y + i * ldy), N, 0u);
 }
 
+static void entry_balanced_spmm(Env &env, const us_formatted &A, const RowSrc &rs, const int32_t *col,
+                                const char *name, int vec, const float *X, int64_t N, int64_t ldx, float *Y,
+                                int64_t ldy) {
+  // Y must already hold the values to add to (zeros for a plain product)
+  const double xy = 4.0 * N * (A.ncols + A.nrows);
+  const int64_t nchunks = ceil_div<int64_t>(A.nnz, CS_CHUNK);
+  const size_t rows_bytes = (size_t)nchunks * 2 * sizeof(int32_t);
+  const size_t rows_pad = (rows_bytes + 255) / 256 * 256;
+  const int cbw = 64 * vec;
+  const int64_t ncbv = ceil_div<int64_t>(N, cbw);
+  char *ws = (char *)ensure_workspace(env, A, rows_pad + (size_t)nchunks * 2 * ncbv * cbw * sizeof(float));
+  if (!env.ok()) return;
+  int32_t *carry_row = (int32_t *)ws;
+  float *carry = (float *)(ws + rows_pad);
+  {
+    LaunchScope ls(env, name, 12.0 * A.nnz + xy);
+    const dim3 grid((unsigned)ceil_div<int64_t>(nchunks, 4), (unsigned)ncbv);
+    if (vec == 4) hipLaunchKernelGGL(coo_spmm_kernel<4>, grid, dim3(256), 0, env.stream, rs, col, (const float *)A.val, A.nnz, X, N, ldx, Y, ldy, carry_row, carry);
+    else if (vec == 2) hipLaunchKernelGGL(coo_spmm_kernel<2>, grid, dim3(256), 0, env.stream, rs, col, (const float *)A.val, A.nnz, X, N, ldx, Y, ldy, carry_row, carry);
+    else hipLaunchKernelGGL(coo_spmm_kernel<1>, grid, dim3(256), 0, env.stream, rs, col, (const float *)A.val, A.nnz, X, N, ldx, Y, ldy, carry_row, carry);
+    env.check(hipGetLastError());
+  }
+  if (env.ok()) {
+    LaunchScope ls(env, "spmm_rows_fixup", 8.0 * nchunks);
+    hipLaunchKernelGGL(coo_spmm_fixup_kernel, dim3((unsigned)ceil_div<int64_t>(nchunks * 2, 4), (unsigned)ncbv),
+                       dim3(256), 0, env.stream, (const int32_t *)carry_row, (const float *)carry, nchunks * 2, ncbv,
+                       cbw, N, Y, ldy);
+    env.check(hipGetLastError());
+  }
+}
+
 us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, int64_t ldx, float *Y, int64_t ldy,
                     bool accumulate) {
   const int64_t ncb = ceil_div<int64_t>(N, 64);
@@ -358,14 +403,10 @@ us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, 
         }
         return env.status;
       }
-      if (d && !accumulate) zero_rows(env, Y, A.nrows, N, ldy);
-      if (env.ok() && A.nmajor > 0) {
-        LaunchScope ls(env, "spmm_csr", 8.0 * A.nnz + xy);
-        hipLaunchKernelGGL(csr_spmm_kernel, dim3((unsigned)ceil_div<int64_t>(A.nmajor, 4), (unsigned)ncb), dim3(256), 0,
-                           env.stream, (const int32_t *)A.level[1].ptr, (const int32_t *)A.level[1].idx,
-                           (const float *)A.val, (const int32_t *)(d ? A.level[0].idx : nullptr), A.nmajor, X, N, ldx,
-                           Y, ldy, d ? 1 : acc);
-        env.check(hipGetLastError());
+      if (!accumulate) zero_rows(env, Y, A.nrows, N, ldy);
+      if (A.nnz > 0) {
+        RowSrc rs{nullptr, A.level[1].ptr, d ? A.level[0].idx : nullptr, A.nmajor};
+        entry_balanced_spmm(env, A, rs, A.level[1].idx, "spmm_csr", vec, X, N, ldx, Y, ldy);
       }
       return env.status;
     }
@@ -391,31 +432,8 @@ us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, 
         }
         return env.status;
       }
-      const int64_t nchunks = ceil_div<int64_t>(A.nnz, CS_CHUNK);
-      const size_t rows_bytes = (size_t)nchunks * 2 * sizeof(int32_t);
-      const size_t rows_pad = (rows_bytes + 255) / 256 * 256;
-      const int cbw = 64 * vec;
-      const int64_t ncbv = ceil_div<int64_t>(N, cbw);
-      char *ws = (char *)ensure_workspace(env, A, rows_pad + (size_t)nchunks * 2 * ncbv * cbw * sizeof(float));
-      if (!env.ok()) return env.status;
-      int32_t *carry_row = (int32_t *)ws;
-      float *carry = (float *)(ws + rows_pad);
-      {
-        LaunchScope ls(env, "spmm_coo", 12.0 * A.nnz + xy);
-        const dim3 grid((unsigned)ceil_div<int64_t>(nchunks, 4), (unsigned)ncbv);
-        const int32_t *ar = A.level[0].idx, *ac = A.level[1].idx;
-        if (vec == 4) hipLaunchKernelGGL(coo_spmm_kernel<4>, grid, dim3(256), 0, env.stream, ar, ac, (const float *)A.val, A.nnz, X, N, ldx, Y, ldy, carry_row, carry);
-        else if (vec == 2) hipLaunchKernelGGL(coo_spmm_kernel<2>, grid, dim3(256), 0, env.stream, ar, ac, (const float *)A.val, A.nnz, X, N, ldx, Y, ldy, carry_row, carry);
-        else hipLaunchKernelGGL(coo_spmm_kernel<1>, grid, dim3(256), 0, env.stream, ar, ac, (const float *)A.val, A.nnz, X, N, ldx, Y, ldy, carry_row, carry);
-        env.check(hipGetLastError());
-      }
-      if (env.ok()) {
-        LaunchScope ls(env, "spmm_coo_fixup", 8.0 * nchunks);
-        hipLaunchKernelGGL(coo_spmm_fixup_kernel, dim3((unsigned)ceil_div<int64_t>(nchunks * 2, 4), (unsigned)ncbv),
-                           dim3(256), 0, env.stream, (const int32_t *)carry_row, (const float *)carry, nchunks * 2, ncbv,
-                           cbw, N, Y, ldy);
-        env.check(hipGetLastError());
-      }
+      RowSrc rs{A.level[0].idx, nullptr, nullptr, 0};
+      entry_balanced_spmm(env, A, rs, A.level[1].idx, "spmm_coo", vec, X, N, ldx, Y, ldy);
       return env.status;
     }
     default: break;
