@@ -280,7 +280,43 @@ def other_workloads(B, W, torch, ctx, up, K, Wm):
     run("config5_ell_coo_spmm128", m,
         lambda r, c, v: list(B.us_decompose(ctx, m.nrows, m.ncols, r, c, v, ELL, COO, pr)), prod5,
         2.0 * m.nnz * 128, lambda p: 12.0 * m.nnz + 8.0 * p[0].val().numel() + 12.0 * p[1].nnz)
+    res["label_propagation"] = label_propagation(B, W, torch, ctx, up)
     return res
+
+
+def label_propagation(B, W, torch, ctx, up, iters=20, N=1000):
+    """The paper's label-propagation case study (Section 7.2.5): `iters` products Y <- A_hat Y with a
+    row-normalised power-law graph and N = 1000 labels, over CSR and over the ELL+COO hybrid,
+    with the conversion (pre-processing) time beside the kernel time."""
+    import numpy as np
+    dev = torch.device("cuda:0")
+    m = W.cfg5_powerlaw_local(n=1 << 18, target_nnz=5_200_000, max_len=20000, index=6)
+    deg = np.bincount(m.row, minlength=m.nrows)
+    val = (1.0 / deg[m.row]).astype(np.float32)
+    r, c, v = up(m.row), up(m.col), up(val)
+    Y0 = up(W.dense_operand(6, (m.ncols, N)))
+    bufs = [Y0.clone(), torch.empty_like(Y0)]
+    CSR, COO, ELL = B.us_desc_preset(B.US_F_CSR), B.us_desc_preset(B.US_F_COO), B.us_desc_preset(B.US_F_ELL)
+    pr = B.make_predicate([B.expr(B.US_E_AFFINE, 1, 0)], B.US_P_RANK_LT_PERCENTILE, 9, 10)
+
+    def loop(parts):
+        for t in range(iters):
+            src, dst = bufs[t & 1], bufs[(t + 1) & 1]
+            for k, p in enumerate(parts):
+                B.us_spmm(ctx, p, src, dst, accumulate=k > 0)
+
+    out = {"nrows": m.nrows, "nnz": m.nnz, "N": N, "iterations": iters}
+    for name, conv in (("csr", lambda: [B.us_convert(ctx, m.nrows, m.ncols, r, c, v, CSR)]),
+                       ("ell_coo", lambda: list(B.us_decompose(ctx, m.nrows, m.ncols, r, c, v, ELL, COO, pr)))):
+        ms_conv = timed(torch, lambda: [p.free() for p in conv()], 5, 2)
+        parts = conv()
+        ms_loop = timed(torch, lambda: loop(parts), 3, 1)
+        out[name] = {"preprocess_ms": round(ms_conv, 3), "kernels_ms": round(ms_loop, 3),
+                     "total_ms": round(ms_conv + ms_loop, 3),
+                     "gflop_s": round(2.0 * m.nnz * N * iters / ms_loop / 1e6, 1)}
+        for p in parts:
+            p.free()
+    return out
 
 
 if __name__ == "__main__":

@@ -213,3 +213,28 @@ def test_cfg5_full(ctx):
     rng = np.random.default_rng(2)
     rows = np.unique(np.concatenate([rng.choice(m.nrows, 2000, replace=False), np.argsort(lens)[-20:]]))
     check_spmm_rows(ctx, [ga, gb], m, X, rows)
+
+
+def test_label_propagation_small(ctx):
+    """A few iterations Y <- A_hat Y (row-normalised graph, Section 7.2.5) over CSR and over the
+    ELL+COO hybrid against the fp64 iteration from the COO list."""
+    from paper_2403_05802_amd import binding as B
+    from helpers import coo_to_dev, dev, host, us_desc_of, us_pred_of
+    m = W.cfg5_powerlaw_local(n=3000, target_nnz=40_000, max_len=800, index=6)
+    deg = np.bincount(m.row, minlength=m.nrows)
+    m.val = (1.0 / deg[m.row]).astype(np.float32)
+    N, iters = 40, 5
+    Y0 = W.dense_operand(6, (m.ncols, N))
+    ref = Y0.astype(np.float64)
+    for _ in range(iters):
+        ref = O.spmm_coo(m.nrows, m.ncols, m.row, m.col, m.val, ref)
+    d = coo_to_dev(m)
+    csr = [B.us_convert(ctx, m.nrows, m.ncols, *d, us_desc_of(O.CSR()))]
+    hyb = list(B.us_decompose(ctx, m.nrows, m.ncols, *d, us_desc_of(O.ELL()), us_desc_of(O.COO()), us_pred_of(P90_PRED)))
+    for parts in (csr, hyb):
+        bufs = [dev(Y0), torch.empty(m.nrows, N, device="cuda")]
+        for t in range(iters):
+            for k, p in enumerate(parts):
+                B.us_spmm(ctx, p, bufs[t & 1], bufs[(t + 1) & 1], accumulate=k > 0)
+        got = host(bufs[iters & 1])
+        assert np.max(np.abs(got - ref)) <= 1e-4 * np.max(np.abs(ref))

@@ -131,3 +131,24 @@ def test_results_are_reproducible_bit_for_bit(ctx):
     assert len(a) == len(b)
     for s, t in zip(a, b):
         assert s.dtype == t.dtype and torch.equal(s.view(torch.int32), t.view(torch.int32))
+
+
+def test_dia_large_slab(ctx):
+    """A slab larger than the L2s (5 diagonals of a 2^20 matrix): same arrays as the oracle, and
+    the duplicate check of the sort-free path still fires."""
+    from paper_2403_05802_amd import binding as B
+    from paper_2403_05802_amd import workloads as W
+    from helpers import assert_same_layout, coo_to_dev, dev, us_desc_of, us_pred_of
+    m = W.cfg3_banded(n=1 << 20, offsets=(-300, -1, 0, 1, 70000), extra_frac=0.002, index=7)
+    pred = O.Predicate((O.diag(),), O.SUM_GE_FRAC_OF_CAPACITY, num=9, den=10)
+    oa, ob, _ = O.decompose(m.nrows, m.ncols, m.row, m.col, m.val, O.DIA(), O.DCSR(), pred)
+    ga, gb = B.us_decompose(ctx, m.nrows, m.ncols, *coo_to_dev(m), us_desc_of(O.DIA()), us_desc_of(O.DCSR()),
+                            us_pred_of(pred))
+    assert_same_layout(ga, oa, "large DIA part")
+    assert_same_layout(gb, ob, "DCSR remainder")
+    r = np.concatenate([m.row, m.row[:1]]); c = np.concatenate([m.col, m.col[:1]]); v = np.concatenate([m.val, m.val[:1]])
+    on_diag = np.isin(m.col[:1].astype(np.int64) - m.row[:1], (-300, -1, 0, 1, 70000))[0]
+    with pytest.raises(B.UnisparseError) as ei:
+        B.us_decompose(ctx, m.nrows, m.ncols, dev(r), dev(c), dev(v), us_desc_of(O.DIA()), us_desc_of(O.DCSR()),
+                       us_pred_of(pred))
+    assert ei.value.code == "US_ERR_DUPLICATE", on_diag
