@@ -209,7 +209,8 @@ def main():
         "metric": "conversion Mnnz/s + SpMV GFLOP/s; achieved HBM GB/s as % of MI355X peak",
         "value": round(nnz / ms_step / 1e3, 1), "unit": "Mnnz/s",
         "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(ms_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32 indices / u64 keys / f32 values",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u64",
+        "dtype_note": "sort keys u64 (40-bit packed (row,col)), indices int32, values and products f32 (f32 accumulate)",
         "data": "synthetic",
         "config": {"workload": "config 2: 1,048,576^2 fp32, Zipf(1.8) row lengths 1..20000, uniform columns, "
                                f"{nnz} nnz, unsorted COO in HBM; step = COO->CSR + COO->DCSR + SpMV over each"},

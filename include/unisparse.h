@@ -78,7 +78,8 @@ typedef struct us_expr {
  *   DCSR (d0,d1) merge(0) trim(0,1)     CSC / DCSC: the same with map (d1,d0)
  *   DIA  (d1-d0,d0) merge(0) trim(0,0)  DIA variant (d1-d0,d1)
  *   BCSR (d0/bh,d1/bw,d0%bh,d1%bw) merge(0,1) trim(1,1), 1 <= bh,bw <= 16
- *   ELL  (indirect(d1),d0,d1) merge(0) trim(0,0)                                            */
+ *   ELL  (indirect(d1),d0,d1) merge(0) trim(0,0)
+ *   BDIA (d0/b,d1-d0,d0%b) merge(0) trim(1,1), 1 <= b <= 16 (the blocked DIA of Figure 3c)  */
 typedef struct us_format_desc {
   int32_t nlevels;
   us_expr level[4];
@@ -87,9 +88,9 @@ typedef struct us_format_desc {
   int64_t ell_width;      /* ELL only: 0 = longest row, >0 = fixed number of slots */
 } us_format_desc;
 
-enum { US_F_COO = 0, US_F_CSR, US_F_DCSR, US_F_CSC, US_F_DCSC, US_F_DIA, US_F_DIA_VARIANT, US_F_BCSR, US_F_ELL };
-/* Fill *out with the encoding of Figure 7 for `format`; b0,b1 = block height,width (BCSR) or
- * b0 = fixed width (ELL, 0 = longest row).  host pointers. */
+enum { US_F_COO = 0, US_F_CSR, US_F_DCSR, US_F_CSC, US_F_DCSC, US_F_DIA, US_F_DIA_VARIANT, US_F_BCSR, US_F_ELL, US_F_BDIA };
+/* Fill *out with the encoding of Figure 7 (Figure 3c for BDIA) for `format`; b0,b1 = block
+ * height,width (BCSR), b0 = block height (BDIA) or b0 = fixed width (ELL, 0 = longest row).  host pointers. */
 us_status us_desc_preset(int32_t format, int64_t b0, int64_t b1, us_format_desc *out);
 
 /* Decomposition predicate: the `sum` query of Section 4.1.2 (groupBy map, stored entry -> 1)
@@ -101,7 +102,8 @@ us_status us_desc_preset(int32_t format, int64_t b0, int64_t b1, us_format_desc 
  *   US_P_RANK_LT_ABS             rank of the entry in its row (ascending column) < abs
  *   US_P_RANK_LT_PERCENTILE      rank < K, K = nearest-rank num/den percentile of the row
  *                                lengths over all rows (empty rows included)
- * group maps supported: (d1-d0), (d0), (d1) for the sum predicates; (d0) for the rank ones. */
+ * group maps supported: (d1-d0), (d0), (d1) for the sum predicates; (d0) for the rank ones;
+ * (d0/b, d1-d0) with US_P_SUM_GE_ABS (the #sum query of Figure 3c; part A must then be BDIA with the same b). */
 enum { US_P_SUM_GE_ABS = 0, US_P_SUM_GE_FRAC_OF_CAPACITY = 1, US_P_RANK_LT_ABS = 2, US_P_RANK_LT_PERCENTILE = 3 };
 typedef struct us_predicate {
   us_expr group[2];

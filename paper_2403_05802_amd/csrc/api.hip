@@ -47,6 +47,12 @@ us_status us_desc_preset(int32_t format, int64_t b0, int64_t b1, us_format_desc 
       d.level[2] = mk(US_E_MOD, 1, 0, (int)b0); d.level[3] = mk(US_E_MOD, 0, 1, (int)b1);
       d.trim_s = 1; d.trim_e = 1; d.merge_mask = 3;
       break;
+    case US_F_BDIA:
+      if (b0 < 1 || b0 > 16) return US_ERR_UNSUPPORTED_DESC;
+      d.nlevels = 3;
+      d.level[0] = mk(US_E_DIV, 1, 0, (int)b0); d.level[1] = dg; d.level[2] = mk(US_E_MOD, 1, 0, (int)b0);
+      d.trim_s = 1; d.trim_e = 1; d.merge_mask = 1;
+      break;
     case US_F_ELL:
       if (b0 < 0) return US_ERR_UNSUPPORTED_DESC;
       d.nlevels = 3;

@@ -86,7 +86,7 @@ struct LaunchScope {  // brackets one kernel launch with events when profiling i
   } while (0)
 
 // ------------------------------------------------------------------ formatted tensor
-enum Pattern { P_COO = 0, P_CSR, P_DCSR, P_DIA, P_BCSR, P_ELL };
+enum Pattern { P_COO = 0, P_CSR, P_DCSR, P_DIA, P_BCSR, P_ELL, P_BDIA };
 
 struct LevelStore {
   int64_t size = -1;      // extent of a dense level, -1 if none
@@ -105,8 +105,8 @@ struct us_formatted {
   us::LevelStore level[4];
   float *val = nullptr; int64_t nval = 0;
   // derived sizes
-  int64_t nmajor = 0;   // CSR: rows (cols if swapped); DCSR: stored rows; DIA: ndiag; BCSR: block rows; ELL: K
-  int64_t bh = 1, bw = 1, nblk = 0;
+  int64_t nmajor = 0;   // CSR: rows (cols if swapped); DCSR: stored rows; DIA: ndiag; BCSR/BDIA: block rows; ELL: K
+  int64_t bh = 1, bw = 1, nblk = 0;   // BDIA: bh = block height, bw = 1, nblk = (block row, diagonal) nodes
   // CSR / DCSR: where every SpMV tile starts on the merge path of row ends and non-zeros
   // (rows consumed before step t * tile), computed once at conversion
   int32_t *mp_split = nullptr; int64_t mp_tiles = 0;
@@ -135,7 +135,8 @@ void lower_bound_ptr(Env &env, const int32_t *sorted_major, int64_t n, int64_t n
 
 // how the 64/32-bit sort key is built from a COO entry
 struct KeySpec {
-  int mode;        // 0: (a,b) with a = row (or col if swap), b = the other; 1: block (a/bh, b/bw, a%bh, b%bw)
+  int mode;        // 0: (a,b) with a = row (or col if swap), b = the other; 1: block (a/bh, b/bw, a%bh, b%bw);
+                   // 2: blocked diagonal (a/bh, b-a+a_extent-1, a%bh)
   int swap;        // 1: a = col, b = row
   int b_bits;      // bits of b (mode 0) / of b/bw (mode 1)
   int ih_bits, iw_bits;

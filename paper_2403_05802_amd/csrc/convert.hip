@@ -63,6 +63,12 @@ static bool match_desc(const us_format_desc &d, Plan *p) {
       p->pattern = P_ELL; p->ell_width = d.ell_width;
       return true;
     }
+    int64_t f0, f2;
+    if (tile(d.level[0], US_E_DIV, 0, &f0) && aff(d.level[1], -1, 1) && tile(d.level[2], US_E_MOD, 0, &f2) &&
+        f0 == f2 && S == 1 && E == 1 && m == 1) {
+      p->pattern = P_BDIA; p->bh = f0; p->bw = 1;
+      return true;
+    }
   }
   return false;
 }
@@ -578,8 +584,8 @@ __global__ __launch_bounds__(BE_T) void bcsr_count_kernel(const uint64_t *key, i
 }
 
 __global__ __launch_bounds__(BE_T) void bcsr_emit_kernel(const uint64_t *key, const float *val, int64_t n,
-                                                        KeySpec ks, const uint32_t *partial, int32_t *blk_row,
-                                                        int32_t *blk_col, float *bval) {
+                                                        KeySpec ks, int32_t col_bias, const uint32_t *partial,
+                                                        int32_t *blk_row, int32_t *blk_col, float *bval) {
   __shared__ uint32_t s_wave[BE_T / 64 + 1];
   const int inner_bits = ks.ih_bits + ks.iw_bits;
   const int lane = lane_id();
@@ -619,7 +625,7 @@ __global__ __launch_bounds__(BE_T) void bcsr_emit_kernel(const uint64_t *key, co
       const uint32_t ai = (uint32_t)((k[j] >> ks.iw_bits) & ((1ull << ks.ih_bits) - 1));
       const uint64_t bk = k[j] >> inner_bits;
       if (head) {
-        blk_col[blk] = (int32_t)(bk & ((1ull << ks.b_bits) - 1));
+        blk_col[blk] = (int32_t)(bk & ((1ull << ks.b_bits) - 1)) - col_bias;
         blk_row[blk] = (int32_t)(bk >> ks.b_bits);
       }
       bval[(size_t)blk * bsz + ai * ks.bw + bi] = val[i];
@@ -628,53 +634,75 @@ __global__ __launch_bounds__(BE_T) void bcsr_emit_kernel(const uint64_t *key, co
   }
 }
 
-static us_status convert_bcsr(Env &env, const us_coo &coo, const Plan &plan, const us_format_desc &desc,
-                              Flags *flags, us_formatted **out) {
-  const int64_t n = coo.nnz;
-  const int64_t nbr = ceil_div<int64_t>(coo.nrows, plan.bh), nbc = ceil_div<int64_t>(coo.ncols, plan.bw);
+// Key layout of the two blocked families: BCSR (d0/bh, d1/bw, d0%bh, d1%bw) and BDIA
+// (d0/bh, d1-d0 biased by nrows-1, d0%bh).
+static KeySpec blocked_keyspec(const Plan &plan, int64_t nrows, int64_t ncols) {
+  const int64_t nbr = ceil_div<int64_t>(nrows, plan.bh);
   KeySpec ks{};
-  ks.mode = 1; ks.swap = 0; ks.bh = (uint32_t)plan.bh; ks.bw = (uint32_t)plan.bw;
-  ks.a_extent = (uint32_t)coo.nrows; ks.b_extent = (uint32_t)coo.ncols;
-  ks.b_bits = bits_for(nbc - 1);
-  ks.ih_bits = bits_for(plan.bh - 1); ks.iw_bits = bits_for(plan.bw - 1);
+  ks.swap = 0; ks.bh = (uint32_t)plan.bh; ks.bw = (uint32_t)plan.bw;
+  ks.a_extent = (uint32_t)nrows; ks.b_extent = (uint32_t)ncols;
+  ks.ih_bits = bits_for(plan.bh - 1);
+  if (plan.pattern == P_BDIA) {
+    ks.mode = 2; ks.b_bits = bits_for(nrows + ncols - 2); ks.iw_bits = 0;
+  } else {
+    ks.mode = 1; ks.b_bits = bits_for(ceil_div<int64_t>(ncols, plan.bw) - 1); ks.iw_bits = bits_for(plan.bw - 1);
+  }
   ks.total_bits = bits_for(nbr - 1) + ks.b_bits + ks.ih_bits + ks.iw_bits;
-  uint64_t *skey = env.temp<uint64_t>(n);
-  float *sval = env.temp<float>(n);
+  return ks;
+}
+
+// Sorted keys -> ptr/idx of the merged node level and the zero-filled dense inner levels.
+static us_status emit_blocked(Env &env, const Plan &plan, const us_format_desc &desc, int64_t nrows, int64_t ncols,
+                              const KeySpec &ks, const uint64_t *skey, const float *sval, int64_t n, Flags *flags,
+                              us_formatted **out) {
+  const int64_t nbr = ceil_div<int64_t>(nrows, plan.bh);
   const int64_t nb = ceil_div<int64_t>(n > 0 ? n : 1, BE_TILE);
   uint32_t *partial = env.temp<uint32_t>(nb);
   if (!env.ok()) return env.status;
-  SortOut so{};
-  so.key64 = skey; so.val = sval;
-  sort_coo(env, coo.row, coo.col, coo.val, n, ks, so, flags);
-  US_LAUNCH(env, "bcsr_count", 8.0 * n, bcsr_count_kernel, nb, BE_T, (const uint64_t *)skey, n,
-            ks.ih_bits + ks.iw_bits, partial, flags);
+  US_LAUNCH(env, "bcsr_count", 8.0 * n, bcsr_count_kernel, nb, BE_T, skey, n, ks.ih_bits + ks.iw_bits, partial, flags);
   scan_partials_launch(env, partial, nb, &flags->scalar[0]);
   Flags h{};
   if (!read_flags(env, flags, &h)) return env.status;
   if (flag_status(h) != US_OK) return flag_status(h);
   const int64_t nblk = h.scalar[0], bsz = plan.bh * plan.bw;
   if (nblk * bsz >= (1ll << 31)) return US_ERR_OVERFLOW;
+  const bool bdia = plan.pattern == P_BDIA;
   us_formatted *f = new us_formatted();
-  f->desc = desc; f->pattern = P_BCSR;
-  f->nrows = coo.nrows; f->ncols = coo.ncols; f->nnz = n;
-  f->nlevels = 4;
+  f->desc = desc; f->pattern = plan.pattern;
+  f->nrows = nrows; f->ncols = ncols; f->nnz = n;
+  f->nlevels = bdia ? 3 : 4;
   f->level[0].size = nbr;
   f->level[1].ptr = env.owned<int32_t>(nbr + 1); f->level[1].nptr = nbr + 1;
   f->level[1].idx = env.owned<int32_t>(nblk); f->level[1].nidx = nblk;
-  f->level[2].size = plan.bh; f->level[3].size = plan.bw;
+  f->level[2].size = plan.bh;
+  if (!bdia) f->level[3].size = plan.bw;
   f->val = env.owned<float>(nblk * bsz); f->nval = nblk * bsz;
   f->nmajor = nbr; f->bh = plan.bh; f->bw = plan.bw; f->nblk = nblk;
   int32_t *blk_row = env.temp<int32_t>(nblk);
   if (!env.ok()) { free_formatted(env, f); return env.status; }
   fill_u32(env, (uint32_t *)f->val, nblk * bsz, 0u);
   if (n > 0)
-    US_LAUNCH(env, "bcsr_emit", 12.0 * n + 4.0 * n, bcsr_emit_kernel, nb, BE_T, (const uint64_t *)skey,
-              (const float *)sval, n, ks, (const uint32_t *)partial, blk_row, f->level[1].idx, f->val);
+    US_LAUNCH(env, "bcsr_emit", 12.0 * n + 4.0 * n, bcsr_emit_kernel, nb, BE_T, skey, sval, n, ks,
+              (int32_t)(bdia ? nrows - 1 : 0), (const uint32_t *)partial, blk_row, f->level[1].idx, f->val);
   lower_bound_ptr(env, blk_row, nblk, nbr, f->level[1].ptr);
   env.sync();
   if (!env.ok()) { free_formatted(env, f); return env.status; }
   *out = f;
   return US_OK;
+}
+
+static us_status convert_blocked(Env &env, const us_coo &coo, const Plan &plan, const us_format_desc &desc,
+                                 Flags *flags, us_formatted **out) {
+  const int64_t n = coo.nnz;
+  const KeySpec ks = blocked_keyspec(plan, coo.nrows, coo.ncols);
+  if (ks.total_bits > 64) return US_ERR_OVERFLOW;
+  uint64_t *skey = env.temp<uint64_t>(n);
+  float *sval = env.temp<float>(n);
+  if (!env.ok()) return env.status;
+  SortOut so{};
+  so.key64 = skey; so.val = sval;
+  sort_coo(env, coo.row, coo.col, coo.val, n, ks, so, flags);
+  return emit_blocked(env, plan, desc, coo.nrows, coo.ncols, ks, skey, sval, n, flags, out);
 }
 
 // ------------------------------------------------------------------ convert
@@ -696,7 +724,7 @@ static us_status convert_with_plan(Env &env, const us_coo &coo, const Plan &plan
   Flags *flags = new_flags(env);
   if (!env.ok()) return env.status;
   if (plan.pattern == P_DIA) return convert_dia(env, coo, plan, desc, flags, out);
-  if (plan.pattern == P_BCSR) return convert_bcsr(env, coo, plan, desc, flags, out);
+  if (plan.pattern == P_BCSR || plan.pattern == P_BDIA) return convert_blocked(env, coo, plan, desc, flags, out);
   // COO / CSR / DCSR / ELL: sort by (major, minor), then build
   const int64_t n = coo.nnz;
   int32_t *major = env.owned<int32_t>(n), *minor = env.owned<int32_t>(n);
@@ -756,6 +784,13 @@ __device__ __forceinline__ bool slot_entry(const SrcView &v, int64_t s, int32_t 
       *r = (int32_t)row; *c = (int32_t)col; *x = val;
       return true;
     }
+    case P_BDIA: {   // inverse map of Figure 9: d0 = e0*b + e2, d1 = e1 + d0
+      const int64_t node = s / v.bh, ri = s - node * v.bh;
+      const int64_t row = parent_of(v.ptr, v.nmajor, node) * v.bh + ri, col = row + v.idx[node];
+      if (val == 0.f || row >= v.nrows || col < 0 || col >= v.ncols) return false;
+      *r = (int32_t)row; *c = (int32_t)col; *x = val;
+      return true;
+    }
     case P_ELL: {
       const int64_t k = s / v.nrows, i = s - k * v.nrows;
       if (v.idx[s] < 0 || val == 0.f) return false;
@@ -797,7 +832,8 @@ us_status convert_formatted_impl(Env &env, const us_formatted &src, const us_for
     case P_CSR: v.ptr = src.level[1].ptr; v.idx = src.level[1].idx; break;
     case P_DCSR: v.idx0 = src.level[0].idx; v.ptr = src.level[1].ptr; v.idx = src.level[1].idx; break;
     case P_DIA: v.idx0 = src.level[0].idx; break;
-    case P_BCSR: v.ptr = src.level[1].ptr; v.idx = src.level[1].idx; break;
+    case P_BCSR:
+    case P_BDIA: v.ptr = src.level[1].ptr; v.idx = src.level[1].idx; break;
     case P_ELL: v.idx = src.level[2].idx; break;
     default: return US_ERR_FORMAT_MISMATCH;
   }
@@ -976,6 +1012,113 @@ static us_status decompose_rank(Env &env, const us_coo &coo, const Plan &pa, con
   return st;
 }
 
+// ------------------------------------------------------------------ decompose by (block row, diagonal) -- Figure 3c
+// The #sum query of the BDIA/CSR hybrid groups by (d0/b, d1-d0).  Such groups are exactly the
+// nodes of the BDIA tree, so the entries are sorted by the BDIA tuple first: a group is then a run
+// of the sorted list, its count is the run length, and the entries that stay (part A) are already
+// in BDIA order -- no second sort for them.
+__global__ __launch_bounds__(256) void node_head_kernel(const uint64_t *key, int64_t n, int ih_bits, int32_t *head,
+                                                       Flags *flags) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const uint64_t cur = key[i], prev = i > 0 ? key[i - 1] : ~0ull;
+  if (i > 0 && cur == prev) flags->duplicate = 1;
+  head[i] = (i == 0) | ((cur >> ih_bits) != (prev >> ih_bits));
+}
+
+// start[g] = first entry of run g; the slot after the last run gets n
+__global__ __launch_bounds__(256) void node_start_kernel(const int32_t *head, const int32_t *pos, int64_t n,
+                                                        int32_t *start) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  if (head[i]) start[pos[i]] = (int32_t)i;
+  if (i == n - 1) start[pos[i] + head[i]] = (int32_t)n;
+}
+
+__global__ __launch_bounds__(256) void node_keep_kernel(const int32_t *head, const int32_t *pos, const int32_t *start,
+                                                       int64_t n, int64_t thld, int32_t *keep) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const int32_t g = pos[i] + head[i] - 1;
+  keep[i] = (int64_t)(start[g + 1] - start[g]) >= thld ? 1 : 0;
+}
+
+__global__ __launch_bounds__(256) void node_split_kernel(const uint64_t *key, const float *val, const int32_t *keep,
+                                                        const int32_t *pos_a, int64_t n, KeySpec ks, uint64_t *key_a,
+                                                        float *val_a, CooLists la, CooLists lb) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const uint64_t k = key[i];
+  const bool a = keep[i] != 0;
+  const int64_t at = a ? pos_a[i] : i - pos_a[i];
+  if (a && key_a) { key_a[at] = k; val_a[at] = val[i]; return; }
+  const uint64_t bk = k >> ks.ih_bits;
+  const int32_t row = (int32_t)((bk >> ks.b_bits) * ks.bh + (k & ((1ull << ks.ih_bits) - 1)));
+  const int32_t col = row + (int32_t)(bk & ((1ull << ks.b_bits) - 1)) - (int32_t)(ks.a_extent - 1);
+  const CooLists &l = a ? la : lb;
+  l.r[at] = row; l.c[at] = col; l.v[at] = val[i];
+}
+
+static us_status decompose_blockdiag(Env &env, const us_coo &coo, const Plan &pa, const us_format_desc &da,
+                                     const Plan &pb, const us_format_desc &db, int64_t b, int64_t thld,
+                                     us_formatted **oa, us_formatted **ob) {
+  Flags *flags = new_flags(env);
+  const int64_t n = coo.nnz;
+  Plan pg; pg.pattern = P_BDIA; pg.bh = b; pg.bw = 1;
+  const KeySpec ks = blocked_keyspec(pg, coo.nrows, coo.ncols);
+  const bool direct = pa.pattern == P_BDIA && pa.bh == b;   // part A keeps the sorted order
+  uint64_t *skey = env.temp<uint64_t>(n);
+  float *sval = env.temp<float>(n);
+  int32_t *head = env.temp<int32_t>(n), *pos = env.temp<int32_t>(n), *start = env.temp<int32_t>(n + 1);
+  int32_t *keep = env.temp<int32_t>(n), *pos_a = env.temp<int32_t>(n);
+  if (!env.ok()) return env.status;
+  int64_t na = 0;
+  if (n > 0) {
+    SortOut so{};
+    so.key64 = skey; so.val = sval;
+    sort_coo(env, coo.row, coo.col, coo.val, n, ks, so, flags);
+    const int64_t g = ceil_div<int64_t>(n, 256);
+    US_LAUNCH(env, "node_head", 12.0 * n, node_head_kernel, g, 256, (const uint64_t *)skey, n, ks.ih_bits, head, flags);
+    exclusive_scan_i32(env, head, pos, n, &flags->scalar[0]);
+    US_LAUNCH(env, "node_start", 12.0 * n, node_start_kernel, g, 256, (const int32_t *)head, (const int32_t *)pos, n,
+              start);
+    US_LAUNCH(env, "node_keep", 16.0 * n, node_keep_kernel, g, 256, (const int32_t *)head, (const int32_t *)pos,
+              (const int32_t *)start, n, thld, keep);
+    exclusive_scan_i32(env, keep, pos_a, n, &flags->scalar[1]);
+    Flags h{};
+    if (!read_flags(env, flags, &h)) return env.status;
+    if (flag_status(h) != US_OK) return flag_status(h);
+    na = h.scalar[1];
+  }
+  const int64_t nb = n - na;
+  uint64_t *key_a = direct ? env.temp<uint64_t>(na) : nullptr;
+  float *val_a = direct ? env.temp<float>(na) : nullptr;
+  CooLists la = direct ? CooLists() : alloc_lists(env, na), lb = alloc_lists(env, nb);
+  us_status st = env.status;
+  if (st == US_OK && n > 0) {
+    US_LAUNCH(env, "node_split", 20.0 * n + 12.0 * n, node_split_kernel, ceil_div<int64_t>(n, 256), 256,
+              (const uint64_t *)skey, (const float *)sval, (const int32_t *)keep, (const int32_t *)pos_a, n, ks, key_a,
+              val_a, la, lb);
+    st = env.status;
+  }
+  if (st == US_OK) {
+    if (direct) {
+      st = emit_blocked(env, pa, da, coo.nrows, coo.ncols, ks, key_a, val_a, na, flags, oa);
+    } else {
+      us_coo ca{coo.nrows, coo.ncols, na, la.r, la.c, la.v};
+      st = convert_with_plan(env, ca, pa, da, oa);
+    }
+  }
+  if (st == US_OK) {
+    us_coo cb{coo.nrows, coo.ncols, nb, lb.r, lb.c, lb.v};
+    st = convert_with_plan(env, cb, pb, db, ob);
+  }
+  env.sync();
+  free_lists(env, la);
+  free_lists(env, lb);
+  return st;
+}
+
 us_status decompose_impl(Env &env, const us_coo &coo, const us_format_desc &da, const us_format_desc &db,
                          const us_predicate &pred, us_formatted **oa, us_formatted **ob) {
   *oa = *ob = nullptr;
@@ -984,6 +1127,18 @@ us_status decompose_impl(Env &env, const us_coo &coo, const us_format_desc &da, 
   Plan pa, pb;
   if (!match_desc(da, &pa) || !match_desc(db, &pb)) return US_ERR_UNSUPPORTED_DESC;
   if ((pa.pattern == P_ELL && pa.swapped) || (pb.pattern == P_ELL && pb.swapped)) return US_ERR_UNSUPPORTED_DESC;
+  if (pred.ngroup == 2) {
+    int64_t b;
+    if (!tile(pred.group[0], US_E_DIV, 0, &b) || !aff(pred.group[1], -1, 1) || pred.kind != US_P_SUM_GE_ABS)
+      return US_ERR_UNSUPPORTED_DESC;
+    s = decompose_blockdiag(env, coo, pa, da, pb, db, b, pred.abs, oa, ob);
+    if (s == US_OK && !env.ok()) s = env.status;
+    if (s != US_OK) {
+      if (*oa) { free_formatted(env, *oa); *oa = nullptr; }
+      if (*ob) { free_formatted(env, *ob); *ob = nullptr; }
+    }
+    return s;
+  }
   if (pred.ngroup != 1) return US_ERR_UNSUPPORTED_DESC;
   const us_expr &ge = pred.group[0];
   int gkind = aff(ge, -1, 1) ? G_DIAG : aff(ge, 1, 0) ? G_ROW : aff(ge, 0, 1) ? G_COL : -1;

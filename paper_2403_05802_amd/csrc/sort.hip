@@ -32,6 +32,10 @@ typedef uint64_t Key;  // keys live in registers and LDS as 64-bit words whateve
 __device__ __forceinline__ Key build_key(const KeySpec &ks, uint32_t r, uint32_t c) {
   uint32_t a = ks.swap ? c : r, b = ks.swap ? r : c;
   if (ks.mode == 0) return ((Key)a << ks.b_bits) | (Key)b;
+  if (ks.mode == 2) {   // Skew(0,1,-1) then TileSplit(0,bh): (a/bh, b-a, a%bh), the diagonal biased to be >= 0
+    uint32_t ab = a / ks.bh, ai = a - ab * ks.bh, dg = b - a + (ks.a_extent - 1);
+    return ((((Key)ab << ks.b_bits) | (Key)dg) << ks.ih_bits) | (Key)ai;
+  }
   uint32_t ab = a / ks.bh, ai = a - ab * ks.bh, bb = b / ks.bw, bi = b - bb * ks.bw;
   return (((((Key)ab << ks.b_bits) | (Key)bb) << ks.ih_bits | (Key)ai) << ks.iw_bits) | (Key)bi;
 }
@@ -96,9 +100,12 @@ __global__ __launch_bounds__(RS_T) void radix_hist_kernel(PassArgs a) {
     // the previous pass left this pass's digits as bytes: 8 per thread in one 8-byte load
     const uint32_t i = base + threadIdx.x * RS_IPT;
     if (i + RS_IPT <= a.n) {
-      uint2 v = *reinterpret_cast<const uint2 *>(a.digit_in + i);
+      static_assert(RS_IPT == 4 || RS_IPT == 8, "digit bytes are read 4 or 8 at a time");
+      uint32_t v[RS_IPT / 4];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) { digit[k] = (v.x >> (8 * k)) & 0xFFu; digit[4 + k] = (v.y >> (8 * k)) & 0xFFu; }
+      for (int q = 0; q < RS_IPT / 4; ++q) v[q] = reinterpret_cast<const uint32_t *>(a.digit_in + i)[q];
+#pragma unroll
+      for (int k = 0; k < RS_IPT; ++k) digit[k] = (v[k / 4] >> (8 * (k % 4))) & 0xFFu;
     } else {
 #pragma unroll
       for (int k = 0; k < RS_IPT; ++k) digit[k] = i + k < a.n ? a.digit_in[i + k] : 0xFFFFFFFFu;

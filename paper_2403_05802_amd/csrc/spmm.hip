@@ -174,6 +174,24 @@ __global__ __launch_bounds__(256) void dia_spmm_kernel(const int32_t *off, const
   Y[i * ldy + c] = s;
 }
 
+// BDIA: a wavefront per row, lanes over 64 columns of X / Y, walking the nodes of the row's block row
+__global__ __launch_bounds__(256) void bdia_spmm_kernel(const int32_t *ptr, const int32_t *off, const float *val,
+                                                       int bh, int64_t nrows, int64_t ncols, const float *X, int64_t N,
+                                                       int64_t ldx, float *Y, int64_t ldy, int accumulate) {
+  const int64_t i = (int64_t)blockIdx.x * 4 + wave_id();
+  if (i >= nrows) return;
+  const int64_t c = (int64_t)blockIdx.y * 64 + lane_id();
+  if (c >= N) return;
+  const int64_t br = i / bh;
+  const int ri = (int)(i - br * bh);
+  float s = accumulate ? Y[i * ldy + c] : 0.f;
+  for (int64_t n = ptr[br]; n < ptr[br + 1]; ++n) {
+    const int64_t j = i + off[n];
+    if (j >= 0 && j < ncols) s += val[n * bh + ri] * X[j * ldx + c];
+  }
+  Y[i * ldy + c] = s;
+}
+
 // ------------------------------------------------------------------ entries grouped by row (COO sorted by row, CSR, DCSR): equal shares of non-zeros per wavefront
 // The row of entry e is read from the COO row array, or found in ptr (plus the stored-row list
 // for DCSR), so a 20,000-entry row costs the same as 20,000 one-entry rows.
@@ -416,6 +434,15 @@ us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, 
         hipLaunchKernelGGL(dia_spmm_kernel, dim3((unsigned)ceil_div<int64_t>(A.nrows, 4), (unsigned)ncb), dim3(256), 0,
                            env.stream, (const int32_t *)A.level[0].idx, (const float *)A.val, A.nmajor, A.nrows, A.ncols,
                            A.swapped ? 1 : 0, X, N, ldx, Y, ldy, acc);
+        env.check(hipGetLastError());
+      }
+      return env.status;
+    case P_BDIA:
+      if (env.ok()) {
+        LaunchScope ls(env, "spmm_bdia", 4.0 * A.nval + 4.0 * A.nblk + xy);
+        hipLaunchKernelGGL(bdia_spmm_kernel, dim3((unsigned)ceil_div<int64_t>(A.nrows, 4), (unsigned)ncb), dim3(256), 0,
+                           env.stream, (const int32_t *)A.level[1].ptr, (const int32_t *)A.level[1].idx,
+                           (const float *)A.val, (int)A.bh, A.nrows, A.ncols, X, N, ldx, Y, ldy, acc);
         env.check(hipGetLastError());
       }
       return env.status;

@@ -246,6 +246,24 @@ __global__ __launch_bounds__(256) void bcsr_spmv_kernel(const int32_t *ptr, cons
   }
 }
 
+// BDIA (Figure 3c, Figure 9): node n of block row br holds the bh entries (br*bh + ri, br*bh + ri + off_n);
+// one thread per row walks the nodes of its block row, so x is read along the diagonal (unit stride
+// across threads) and val in runs of bh.
+__global__ __launch_bounds__(256) void bdia_spmv_kernel(const int32_t *ptr, const int32_t *off, const float *val,
+                                                       int bh, int64_t nrows, int64_t ncols, const float *x, float *y,
+                                                       int accumulate) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= nrows) return;
+  const int64_t br = i / bh;
+  const int ri = (int)(i - br * bh);
+  float s = accumulate ? y[i] : 0.f;
+  for (int64_t n = ptr[br]; n < ptr[br + 1]; ++n) {
+    const int64_t j = i + off[n];
+    if (j >= 0 && j < ncols) s += val[n * bh + ri] * x[j];
+  }
+  y[i] = s;
+}
+
 void spmv_prepare(Env &env, us_formatted *f) {
   if (f->swapped || (f->pattern != P_CSR && f->pattern != P_DCSR)) return;
   const int64_t total = f->nmajor + f->nnz;
@@ -290,6 +308,11 @@ us_status spmv_impl(Env &env, const us_formatted &A, const float *x, float *y, b
       US_LAUNCH(env, "spmv_bcsr", 4.0 * A.nval + 4.0 * A.nblk + 8.0 * A.nrows, bcsr_spmv_kernel,
                 ceil_div<int64_t>(A.nmajor, 4), 256, (const int32_t *)A.level[1].ptr, (const int32_t *)A.level[1].idx,
                 (const float *)A.val, A.nmajor, (int)A.bh, (int)A.bw, A.nrows, A.ncols, x, y, accumulate ? 1 : 0);
+      return env.status;
+    case P_BDIA:
+      US_LAUNCH(env, "spmv_bdia", 4.0 * A.nval + 4.0 * A.nblk + 8.0 * A.nrows + 4.0 * A.ncols, bdia_spmv_kernel,
+                ceil_div<int64_t>(A.nrows, 256), 256, (const int32_t *)A.level[1].ptr, (const int32_t *)A.level[1].idx,
+                (const float *)A.val, (int)A.bh, A.nrows, A.ncols, x, y, accumulate ? 1 : 0);
       return env.status;
     case P_COO:
       // row-major COO: the entry-balanced SpMM kernel with one column (fixed summation order);

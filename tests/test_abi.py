@@ -12,9 +12,16 @@ def declared_symbols():
     return sorted(set(re.findall(r"\b(us_[a-z_0-9]+)\s*\(", text)))
 
 
-def test_library_exports_header_symbols():
+def _ensure_built():
     from paper_2403_05802_amd import binding as B
-    assert os.path.exists(B.LIB_PATH), "build the library first: python -m paper_2403_05802_amd.build"
+    if not os.path.exists(B.LIB_PATH):   # fresh checkout: the .so is not tracked
+        from paper_2403_05802_amd import build
+        build.build(verbose=False)
+    return B
+
+
+def test_library_exports_header_symbols():
+    B = _ensure_built()
     lib = ctypes.CDLL(B.LIB_PATH)
     names = declared_symbols()
     assert set(B.EXPORTS) <= set(names)
@@ -24,7 +31,7 @@ def test_library_exports_header_symbols():
 
 
 def test_status_strings_and_presets_need_no_gpu():
-    from paper_2403_05802_amd import binding as B
+    B = _ensure_built()
     L = B.lib()
     for code, name in B.STATUS_NAMES.items():
         assert L.us_status_str(code).decode() == name
@@ -33,9 +40,61 @@ def test_status_strings_and_presets_need_no_gpu():
     assert [d.level[i].kind for i in range(4)] == [B.US_E_DIV, B.US_E_DIV, B.US_E_MOD, B.US_E_MOD]
     e = B.us_desc_preset(B.US_F_ELL, 0, 0)
     assert e.nlevels == 3 and e.level[0].kind == B.US_E_INDIRECT_ENUM
+    b = B.us_desc_preset(B.US_F_BDIA, 3, 0)        # Figure 3c: (d0/3, d1-d0, d0%3), merge(0), trim(1,1)
+    assert b.nlevels == 3 and b.merge_mask == 1 and (b.trim_s, b.trim_e) == (1, 1)
+    assert [(b.level[i].kind, b.level[i].c0, b.level[i].c1, b.level[i].factor) for i in range(3)] == \
+        [(B.US_E_DIV, 1, 0, 3), (B.US_E_AFFINE, -1, 1, b.level[1].factor), (B.US_E_MOD, 1, 0, 3)]
     import pytest
     with pytest.raises(B.UnisparseError):
         B.us_desc_preset(B.US_F_BCSR, 0, 4)
+    with pytest.raises(B.UnisparseError):
+        B.us_desc_preset(B.US_F_BDIA, 17, 0)
     # null arguments are rejected before anything touches the device
     assert L.us_convert(None, None, None, None) == -1
     assert L.us_spmv(None, None, None, None, 0) == -1
+
+
+def test_host_side_checks_return_before_any_device_work():
+    """Argument validation and descriptor matching are host logic: they answer without a GPU."""
+    import ctypes as C
+    B = _ensure_built()
+    L = B.lib()
+    ctx = B.us_ctx()                      # NULL allocator, NULL stream: never used on these paths
+    out = C.c_void_p()
+    csr = B.us_desc_preset(B.US_F_CSR)
+
+    def convert(nrows, ncols, nnz, desc, row=None):
+        coo = B.us_coo(nrows, ncols, nnz, row, row, row)
+        return L.us_convert(C.byref(ctx), C.byref(coo), C.byref(desc), C.byref(out))
+
+    assert convert(0, 5, 0, csr) == -2                       # US_ERR_SHAPE
+    assert convert(5, -1, 0, csr) == -2
+    assert convert(5, 5, -3, csr) == -2
+    assert convert(1 << 31, 5, 0, csr) == -7                 # US_ERR_OVERFLOW
+    assert convert(5, 5, 1 << 31, csr) == -7
+    assert convert(5, 5, 3, csr, None) == -1                 # US_ERR_NULL: entries without arrays
+    E = B.expr
+    unsupported = [
+        B.make_desc([E(B.US_E_AFFINE, 1, 1), E(B.US_E_AFFINE, 0, 1)], (1, 1), (0,)),          # d0+d1 level
+        B.make_desc([E(B.US_E_AFFINE, 1, 0), E(B.US_E_AFFINE, 0, 1)], (1, 1), ()),             # trim(1,1) without merge
+        B.make_desc([E(B.US_E_AFFINE, -1, 1), E(B.US_E_AFFINE, 1, 0)], (0, 1), (0,)),          # DIA map, DCSR mutation
+        B.make_desc([E(B.US_E_DIV, 1, 0, 0, 4), E(B.US_E_DIV, 0, 1, 0, 4), E(B.US_E_MOD, 1, 0, 0, 4),
+                     E(B.US_E_MOD, 0, 1, 0, 2)], (1, 1), (0, 1)),                               # div/mod factors disagree
+        B.make_desc([E(B.US_E_DIV, 1, 0, 0, 32), E(B.US_E_DIV, 0, 1, 0, 32), E(B.US_E_MOD, 1, 0, 0, 32),
+                     E(B.US_E_MOD, 0, 1, 0, 32)], (1, 1), (0, 1)),                              # block too large
+        B.make_desc([E(B.US_E_DIV, 1, 0, 0, 2), E(B.US_E_DIV, 0, 1, 0, 2), E(B.US_E_MOD, 1, 0, 0, 2),
+                     E(B.US_E_MOD, 0, 1, 0, 2)], (2, 3), (1,)),                                 # CSB: not on the GPU path
+        B.make_desc([E(B.US_E_AFFINE, 1, 0)], (0, 0), (0,)),                                    # one level
+    ]
+    for d in unsupported:
+        assert convert(5, 5, 0, d) == -4                     # US_ERR_UNSUPPORTED_DESC
+    pred = B.make_predicate([E(B.US_E_AFFINE, 1, 1)], B.US_P_SUM_GE_ABS, abs_=1)   # unsupported group map
+    coo = B.us_coo(5, 5, 0, None, None, None)
+    oa, ob = C.c_void_p(), C.c_void_p()
+    assert L.us_decompose(C.byref(ctx), C.byref(coo), C.byref(csr), C.byref(csr), C.byref(pred),
+                          C.byref(oa), C.byref(ob)) == -4
+    pred = B.make_predicate([E(B.US_E_AFFINE, -1, 1)], B.US_P_RANK_LT_ABS, abs_=1)  # rank predicates group by row
+    assert L.us_decompose(C.byref(ctx), C.byref(coo), C.byref(csr), C.byref(csr), C.byref(pred),
+                          C.byref(oa), C.byref(ob)) == -4
+    assert L.us_spmm(C.byref(ctx), None, None, 4, 4, None, 4, 0) == -1
+    assert L.us_formatted_array(None, 0, 0, None, None) == -1

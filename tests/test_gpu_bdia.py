@@ -1,0 +1,123 @@
+"""The BDIA/CSR hybrid of Figure 3c: decompose by the #sum query over (d0/b, d1-d0), part A
+stored as blocked DIA (Figure 9 addressing val[node*b + d0%b]), part B as CSR; HIP vs oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import unisparse_oracle as O
+from paper_2403_05802_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    from paper_2403_05802_amd import binding as B
+    return B.Context("cuda:0")
+
+
+def block_pred(b, thld):
+    return O.Predicate((O.div(0, b), O.diag()), O.SUM_GE_ABS, abs=thld)
+
+
+def broken_bands(n, ncols, seed, keep=0.85, extra=0.02):
+    """A few diagonals with holes plus scattered entries, shuffled."""
+    rng = np.random.default_rng(seed)
+    have = {}
+    for off in (-n // 3, -2, 0, 1, 5, ncols // 2):
+        i = np.arange(max(0, -off), min(n, ncols - off))
+        i = i[rng.random(i.size) < keep]
+        for a in i.tolist():
+            have[(a, a + off)] = 1
+    for e in rng.choice(n * ncols, int(extra * n) + 1, replace=False).tolist():
+        have[(e // ncols, e % ncols)] = 1
+    rc = np.array(list(have.keys()), dtype=np.int32)
+    rc = rc[rng.permutation(rc.shape[0])]
+    v = rng.uniform(0.1, 1, rc.shape[0]).astype(np.float32)
+    return rc[:, 0].copy(), rc[:, 1].copy(), v
+
+
+@pytest.mark.parametrize("shape", [(1000, 1000), (3001, 1777), (50, 4000)], ids=lambda s: f"{s[0]}x{s[1]}")
+@pytest.mark.parametrize("b,thld", [(3, 3), (3, 2), (4, 4), (16, 12), (1, 1)])
+def test_bdia_csr_hybrid(ctx, shape, b, thld):
+    from paper_2403_05802_amd import binding as B
+    from helpers import TOL, assert_same_layout, dev, host, rel_err, us_desc_of, us_pred_of
+    nr, nc = shape
+    r, c, v = broken_bands(nr, nc, seed=b * 100 + thld)
+    pred = block_pred(b, thld)
+    oa, ob, mask = O.decompose(nr, nc, r, c, v, O.BDIA(b), O.CSR(), pred)
+    assert mask.sum() > 0 and (b == 1 or mask.sum() < mask.size)
+    ga, gb = B.us_decompose(ctx, nr, nc, dev(r), dev(c), dev(v), us_desc_of(O.BDIA(b)), us_desc_of(O.CSR()),
+                            us_pred_of(pred))
+    assert_same_layout(ga, oa, "A BDIA")
+    assert_same_layout(gb, ob, "B CSR")
+    rng = np.random.default_rng(1)
+    x = rng.uniform(-1, 1, nc).astype(np.float32)
+    y = torch.full((nr,), 3.0, device="cuda")
+    B.us_spmv(ctx, ga, dev(x), y)
+    B.us_spmv(ctx, gb, dev(x), y, accumulate=True)
+    assert rel_err(host(y), O.spmv_coo(nr, nc, r, c, v, x), O.abs_row_sums(nr, r, c, v, x)) <= TOL
+    X = rng.uniform(-1, 1, (nc, 70)).astype(np.float32)
+    Y = torch.full((nr, 70), 3.0, device="cuda")
+    B.us_spmm(ctx, ga, dev(X), Y)
+    B.us_spmm(ctx, gb, dev(X), Y, accumulate=True)
+    S = O.spmm_coo(nr, nc, r, c, np.abs(v), np.abs(X))
+    assert rel_err(host(Y), O.spmm_coo(nr, nc, r, c, v, X), S) <= TOL
+    ga.free(); gb.free()
+
+
+def test_block_diagonal_groups_with_other_part_formats(ctx):
+    """The grouping is independent of how the parts are stored afterwards."""
+    from paper_2403_05802_amd import binding as B
+    from helpers import assert_same_layout, dev, us_desc_of, us_pred_of
+    nr, nc = 700, 900
+    r, c, v = broken_bands(nr, nc, seed=9)
+    for da, db, b, thld in [(O.BDIA(4), O.COO(), 2, 2), (O.DIA(), O.DCSR(), 8, 7), (O.CSR(), O.BDIA(3), 3, 3),
+                            (O.BDIA(3), O.CSR(), 3, 10 ** 9), (O.BDIA(3), O.CSR(), 3, 0)]:
+        pred = block_pred(b, thld)
+        oa, ob, _ = O.decompose(nr, nc, r, c, v, da, db, pred)
+        ga, gb = B.us_decompose(ctx, nr, nc, dev(r), dev(c), dev(v), us_desc_of(da), us_desc_of(db), us_pred_of(pred))
+        assert_same_layout(ga, oa, f"A b={b} thld={thld}")
+        assert_same_layout(gb, ob, f"B b={b} thld={thld}")
+        ga.free(); gb.free()
+
+
+def test_bdia_hybrid_errors_and_empty(ctx):
+    from paper_2403_05802_amd import binding as B
+    from helpers import assert_same_layout, dev, us_desc_of, us_pred_of
+    pred = block_pred(3, 3)
+    e = np.zeros(0, np.int32); ev = np.zeros(0, np.float32)
+    oa, ob, _ = O.decompose(7, 9, e, e, ev, O.BDIA(3), O.CSR(), pred)
+    ga, gb = B.us_decompose(ctx, 7, 9, dev(e), dev(e), dev(ev), us_desc_of(O.BDIA(3)), us_desc_of(O.CSR()), us_pred_of(pred))
+    assert_same_layout(ga, oa, "empty A"); assert_same_layout(gb, ob, "empty B")
+    r = np.array([0, 1, 1], np.int32); c = np.array([0, 2, 2], np.int32); v = np.ones(3, np.float32)
+    with pytest.raises(B.UnisparseError) as ei:
+        B.us_decompose(ctx, 3, 3, dev(r), dev(c), dev(v), us_desc_of(O.BDIA(3)), us_desc_of(O.CSR()), us_pred_of(pred))
+    assert ei.value.code == "US_ERR_DUPLICATE"
+    with pytest.raises(B.UnisparseError) as ei:
+        B.us_decompose(ctx, 3, 2, dev(r[:2]), dev(c[:2]), dev(v[:2]), us_desc_of(O.BDIA(3)), us_desc_of(O.CSR()),
+                       us_pred_of(pred))
+    assert ei.value.code == "US_ERR_INDEX_RANGE"
+    bad = O.Predicate((O.div(0, 3), O.diag()), O.SUM_GE_FRAC_OF_CAPACITY, num=1, den=2)
+    with pytest.raises(B.UnisparseError) as ei:
+        B.us_decompose(ctx, 3, 3, dev(r[:2]), dev(c[:2]), dev(v[:2]), us_desc_of(O.BDIA(3)), us_desc_of(O.CSR()),
+                       us_pred_of(bad))
+    assert ei.value.code == "US_ERR_UNSUPPORTED_DESC"
+
+
+def test_bdia_hybrid_on_scaled_banded_workload(ctx):
+    """Config-3-like matrix (7 diagonals + 1 % scattered) at 2^17 rows with the Figure 3c program."""
+    from paper_2403_05802_amd import binding as B
+    from helpers import TOL, assert_same_layout, coo_to_dev, dev, host, rel_err, us_desc_of, us_pred_of
+    m = W.cfg3_banded(n=1 << 17)
+    pred = block_pred(4, 4)
+    oa, ob, mask = O.decompose(m.nrows, m.ncols, m.row, m.col, m.val, O.BDIA(4), O.CSR(), pred)
+    ga, gb = B.us_decompose(ctx, m.nrows, m.ncols, *coo_to_dev(m), us_desc_of(O.BDIA(4)), us_desc_of(O.CSR()),
+                            us_pred_of(pred))
+    assert_same_layout(ga, oa, "A"); assert_same_layout(gb, ob, "B")
+    x = W.dense_operand(3, m.ncols)
+    y = torch.empty(m.nrows, device="cuda")
+    B.us_spmv(ctx, ga, dev(x), y); B.us_spmv(ctx, gb, dev(x), y, accumulate=True)
+    yref = O.spmv(oa, x) + O.spmv(ob, x)
+    np.testing.assert_allclose(yref, O.spmv_coo(m.nrows, m.ncols, m.row, m.col, m.val, x), atol=1e-9)
+    assert rel_err(host(y), yref, O.abs_row_sums(m.nrows, m.row, m.col, m.val, x)) <= TOL

@@ -9,7 +9,8 @@ from paper_2403_05802_amd import workloads as W
 pytestmark = pytest.mark.gpu
 
 FORMATS = [("COO", O.COO()), ("CSR", O.CSR()), ("DCSR", O.DCSR()), ("CSC", O.CSC()), ("DCSC", O.DCSC()),
-           ("DIA", O.DIA()), ("DIAv", O.DIA_VARIANT()), ("BCSR4", O.BCSR(4)), ("BCSR2x3", O.BCSR(2, 3)), ("ELL", O.ELL())]
+           ("DIA", O.DIA()), ("DIAv", O.DIA_VARIANT()), ("BCSR4", O.BCSR(4)), ("BCSR2x3", O.BCSR(2, 3)), ("ELL", O.ELL()),
+           ("BDIA3", O.BDIA(3))]
 
 
 @pytest.fixture(scope="module")
