@@ -28,7 +28,8 @@ US_A_SIZE, US_A_PTR, US_A_IDX, US_A_VAL = range(4)
 
 EXPORTS = ["us_convert", "us_convert_formatted", "us_decompose", "us_spmv", "us_spmm", "us_formatted_array", "us_formatted_info",
            "us_free", "us_status_str", "us_desc_preset", "us_profile_create", "us_profile_destroy",
-           "us_profile_reset", "us_profile_collect", "us_profile_entry", "us_profile_set_min_bytes"]
+           "us_profile_reset", "us_profile_collect", "us_profile_entry", "us_profile_set_min_bytes",
+           "us_set_sort_lds_finish"]
 
 
 class UnisparseError(RuntimeError):
@@ -105,6 +106,8 @@ def lib() -> C.CDLL:
         L.us_profile_collect.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
         L.us_profile_set_min_bytes.argtypes = [C.c_void_p, C.c_double]
         L.us_profile_set_min_bytes.restype = C.c_int32
+        L.us_set_sort_lds_finish.argtypes = [C.c_int32]
+        L.us_set_sort_lds_finish.restype = C.c_int32
         L.us_profile_entry.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_int64),
                                        C.POINTER(C.c_double), C.POINTER(C.c_double)]
         for fn in ("us_desc_preset", "us_convert", "us_decompose", "us_spmv", "us_spmm", "us_formatted_array",
@@ -234,6 +237,10 @@ def make_predicate(group, kind: int, num: int = 0, den: int = 1, abs_: int = 0) 
         p.group[i] = e
     p.kind, p.num, p.den, p.abs = kind, num, den, abs_
     return p
+
+
+def us_set_sort_lds_finish(enabled: bool) -> None:
+    _check(lib().us_set_sort_lds_finish(1 if enabled else 0), "us_set_sort_lds_finish")
 
 
 # ----------------------------------------------------------------------------- formatted tensor

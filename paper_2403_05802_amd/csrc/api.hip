@@ -68,16 +68,20 @@ us_status us_desc_preset(int32_t format, int64_t b0, int64_t b1, us_format_desc 
 us_status us_convert(const us_ctx *ctx, const us_coo *coo, const us_format_desc *target, us_formatted **out) {
   if (out) *out = nullptr;
   if (!ctx || !coo || !target || !out) return US_ERR_NULL;
-  Env env(ctx);
-  return convert_impl(env, *coo, *target, out);
+  us_status s;
+  { Env env(ctx); s = convert_impl(env, *coo, *target, out); }
+  if (s == US_SORT_RETRY) { Env env(ctx); env.lds_finish = false; s = convert_impl(env, *coo, *target, out); }
+  return s;
 }
 
 us_status us_convert_formatted(const us_ctx *ctx, const us_formatted *src, const us_format_desc *target,
                                us_formatted **out) {
   if (out) *out = nullptr;
   if (!ctx || !src || !target || !out) return US_ERR_NULL;
-  Env env(ctx);
-  return convert_formatted_impl(env, *src, *target, out);
+  us_status s;
+  { Env env(ctx); s = convert_formatted_impl(env, *src, *target, out); }
+  if (s == US_SORT_RETRY) { Env env(ctx); env.lds_finish = false; s = convert_formatted_impl(env, *src, *target, out); }
+  return s;
 }
 
 us_status us_decompose(const us_ctx *ctx, const us_coo *coo, const us_format_desc *desc_a,
@@ -86,8 +90,18 @@ us_status us_decompose(const us_ctx *ctx, const us_coo *coo, const us_format_des
   if (out_a) *out_a = nullptr;
   if (out_b) *out_b = nullptr;
   if (!ctx || !coo || !desc_a || !desc_b || !pred || !out_a || !out_b) return US_ERR_NULL;
-  Env env(ctx);
-  return decompose_impl(env, *coo, *desc_a, *desc_b, *pred, out_a, out_b);
+  us_status s;
+  { Env env(ctx); s = decompose_impl(env, *coo, *desc_a, *desc_b, *pred, out_a, out_b); }
+  if (s == US_SORT_RETRY) {
+    Env env(ctx); env.lds_finish = false;
+    s = decompose_impl(env, *coo, *desc_a, *desc_b, *pred, out_a, out_b);
+  }
+  return s;
+}
+
+us_status us_set_sort_lds_finish(int32_t enabled) {
+  us::g_lds_finish = enabled != 0;
+  return US_OK;
 }
 
 us_status us_spmv(const us_ctx *ctx, const us_formatted *A, const float *x, float *y, int32_t accumulate) {

@@ -35,15 +35,18 @@ struct Profile {
 };
 
 // ------------------------------------------------------------------ per-call environment
+extern bool g_lds_finish;   // process-wide default of Env::lds_finish (us_set_sort_lds_finish)
 struct Env {
   const us_ctx *ctx;
   hipStream_t stream;
   Profile *prof;
   us_status status = US_OK;
   std::vector<void *> temps;  // temporaries, released by release_temps() after the stream is idle
+  bool lds_finish;            // sort: finish buckets inside LDS (cleared for the retry after Flags::sort_retry)
 
   explicit Env(const us_ctx *c)
-      : ctx(c), stream(c ? (hipStream_t)c->hip_stream : nullptr), prof(c ? (Profile *)c->profile : nullptr) {}
+      : ctx(c), stream(c ? (hipStream_t)c->hip_stream : nullptr), prof(c ? (Profile *)c->profile : nullptr),
+        lds_finish(g_lds_finish) {}
   ~Env() { release_temps(); }
 
   void *alloc_raw(size_t bytes);
@@ -117,12 +120,16 @@ struct us_formatted {
 
 namespace us {
 
+// internal status: the sort met a bucket too large for its in-LDS finish (Flags::sort_retry); the
+// entry point runs the call again with Env::lds_finish cleared.  Never returned to the caller.
+constexpr us_status US_SORT_RETRY = -100;
+
 // device-side status flags written by kernels, read back once per call
 struct Flags {
   int32_t index_range;  // != 0: some coordinate out of range
   int32_t duplicate;    // != 0: two equal keys
   int32_t ell_overflow; // != 0: an entry's rank >= fixed ELL width
-  int32_t sort_abort;   // != 0: a look-back wait in the sort gave up (reported as US_ERR_HIP)
+  int32_t sort_retry;   // != 0: a bucket was too large for the in-LDS finish; the host sorts again without it
   int32_t scalar[4];    // data-dependent sizes (nnr, ndiag, nblk, K, nnz_a ...)
 };
 
@@ -146,12 +153,13 @@ struct KeySpec {
 };
 
 // Sort COO entries by key.  Output either unpacked (major, minor, val) or (key, val).
+// Returns true when the sort itself has looked for equal keys (Flags::duplicate).
 struct SortOut {
   int32_t *major = nullptr, *minor = nullptr;  // unpacked output (mode 0 only)
   uint64_t *key64 = nullptr; uint32_t *key32 = nullptr;  // packed output
   float *val = nullptr;
 };
-void sort_coo(Env &env, const int32_t *row, const int32_t *col, const float *val, int64_t nnz,
+bool sort_coo(Env &env, const int32_t *row, const int32_t *col, const float *val, int64_t nnz,
               const KeySpec &ks, const SortOut &out, Flags *flags_dev);
 // ascending sort of 32-bit keys
 void sort_u32(Env &env, const uint32_t *key, int64_t n, int bits, uint32_t *out, Flags *flags_dev);

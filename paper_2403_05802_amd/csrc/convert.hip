@@ -133,7 +133,7 @@ static bool read_flags(Env &env, Flags *dev, Flags *host) {
 }
 
 static us_status flag_status(const Flags &h) {
-  if (h.sort_abort) return US_ERR_HIP;
+  if (h.sort_retry) return US_SORT_RETRY;
   if (h.index_range) return US_ERR_INDEX_RANGE;
   if (h.duplicate) return US_ERR_DUPLICATE;
   if (h.ell_overflow) return US_ERR_SHAPE;
@@ -181,7 +181,7 @@ static KeySpec rowcol_keyspec(const us_coo &coo, bool swapped) {
 // that move into the result (or are released when the format re-lays them out: ELL).
 static us_status build_from_sorted(Env &env, const Plan &plan, const us_format_desc &desc, int64_t nrows,
                                    int64_t ncols, int64_t nnz, int32_t *major, int32_t *minor, float *val,
-                                   Flags *flags, us_formatted **out) {
+                                   Flags *flags, bool check_dups, us_formatted **out) {
   // Takes ownership of major, minor and val (arrays of nnz entries from Env::owned).
   us_formatted *f = new us_formatted();
   f->desc = desc; f->pattern = plan.pattern; f->swapped = plan.swapped;
@@ -200,7 +200,7 @@ static us_status build_from_sorted(Env &env, const Plan &plan, const us_format_d
     return flag_status(*h);
   };
   Flags h{};
-  if (nnz > 1)
+  if (check_dups && nnz > 1)
     US_LAUNCH(env, "check_unique", 8.0 * nnz, check_unique_unpacked_kernel, ceil_div<int64_t>(nnz, 256), 256,
               (const int32_t *)major, (const int32_t *)minor, nnz, flags);
 
@@ -732,8 +732,8 @@ static us_status convert_with_plan(Env &env, const us_coo &coo, const Plan &plan
   if (!env.ok()) { env.free_raw(major); env.free_raw(minor); env.free_raw(val); return env.status; }
   SortOut so{};
   so.major = major; so.minor = minor; so.val = val;
-  sort_coo(env, coo.row, coo.col, coo.val, n, rowcol_keyspec(coo, plan.swapped), so, flags);
-  return build_from_sorted(env, plan, desc, coo.nrows, coo.ncols, n, major, minor, val, flags, out);
+  const bool checked = sort_coo(env, coo.row, coo.col, coo.val, n, rowcol_keyspec(coo, plan.swapped), so, flags);
+  return build_from_sorted(env, plan, desc, coo.nrows, coo.ncols, n, major, minor, val, flags, !checked, out);
 }
 
 us_status convert_impl(Env &env, const us_coo &coo, const us_format_desc &desc, us_formatted **out) {
@@ -956,8 +956,8 @@ static us_status decompose_rank(Env &env, const us_coo &coo, const Plan &pa, con
   if (!env.ok()) return env.status;
   SortOut so{};
   so.major = major; so.minor = minor; so.val = val;
-  sort_coo(env, coo.row, coo.col, coo.val, n, rowcol_keyspec(coo, false), so, flags);
-  if (n > 1)
+  const bool checked = sort_coo(env, coo.row, coo.col, coo.val, n, rowcol_keyspec(coo, false), so, flags);
+  if (!checked && n > 1)
     US_LAUNCH(env, "check_unique", 8.0 * n, check_unique_unpacked_kernel, ceil_div<int64_t>(n, 256), 256,
               (const int32_t *)major, (const int32_t *)minor, n, flags);
   lower_bound_ptr(env, major, n, nrows, ptr);
@@ -997,7 +997,7 @@ static us_status decompose_rank(Env &env, const us_coo &coo, const Plan &pa, con
     if (row_major_family(p)) {   // the list is already in (row, col) order: no second sort
       Flags *fl = new_flags(env);
       if (!env.ok()) return env.status;
-      us_status s = build_from_sorted(env, p, d, coo.nrows, coo.ncols, cnt, l.r, l.c, l.v, fl, o);
+      us_status s = build_from_sorted(env, p, d, coo.nrows, coo.ncols, cnt, l.r, l.c, l.v, fl, false, o);
       l = CooLists();  // ownership moved
       return s;
     }

@@ -17,6 +17,8 @@ void Env::free_raw(void *p) {
   if (ctx && ctx->alloc) { if (ctx->free) ctx->free(p, ctx->user); }
   else (void)hipFree(p);
 }
+bool g_lds_finish = false;
+
 void Env::release_temps() {
   if (temps.empty()) return;
   (void)hipStreamSynchronize(stream);  // kernels may still read the temporaries

@@ -288,7 +288,7 @@ __global__ __launch_bounds__(RS_T) void radix_scatter_kernel(PassArgs a) {
         a.key32_out[g] = (uint32_t)kk;
       } else {
         skey[k] = kk;   // written together with the value below
-        a.digit_out[g] = (uint8_t)((uint32_t)(kk >> a.next_shift) & a.next_mask);
+        if (a.digit_out) a.digit_out[g] = (uint8_t)((uint32_t)(kk >> a.next_shift) & a.next_mask);
       }
     }
   }
@@ -307,6 +307,295 @@ __global__ __launch_bounds__(RS_T) void radix_scatter_kernel(PassArgs a) {
       else a.val_out[gpos[k]] = s_val[i];
     }
   }
+}
+
+
+// ------------------------------------------------------------------ finishing sort inside LDS
+// After the digit passes over the top bits of the key the list is cut into buckets of equal
+// prefix that sit next to each other.  Keys are unique, so a bucket is small whenever the
+// prefix is long enough, and it is finished where it fits: one workgroup loads the bucket,
+// sorts the remaining low bits (at most 32) with the same stable ballot ranking, digit by
+// digit, exchanging items through LDS only, and writes the final arrays.  Compared with
+// carrying on with whole-array passes this replaces ceil(low_bits / 8) trips through HBM by
+// one.
+//
+// A bucket above LS_CAP items (a heavy row of a power-law matrix, say) gets one more 8-bit
+// split of its own first: its tiles are counted, scanned and scattered like a digit pass, but
+// only its items move.  The pieces are then bundled, in order, into groups of at most LS_CAP
+// items that the same LDS kernel finishes (it sorts by all low bits, so a group may span
+// several pieces).  A bucket beyond LS_MAXTILES tiles, or a piece above LS_GROUP items, sets
+// Flags::sort_retry and the host sorts again with whole-array passes only.
+constexpr int LS_T = 256, LS_IPT = 16, LS_CAP = LS_T * LS_IPT;   // 4096 items, 32 KB of LDS
+constexpr int LS_GROUP = LS_CAP / 2;     // pieces are bundled by the LS_GROUP-sized interval their start falls in
+constexpr int LS_MAXTILES = 64;          // split buckets hold at most 64 * 4096 items
+
+struct BigBucket { uint32_t bucket, first, size, tile_base; };
+struct WorkItem { uint32_t first, size, bucket; };
+
+struct LocalArgs {
+  const Rec *rec_in;     // sorted by the top bits
+  Rec *rec_split;        // big buckets after their extra split (same positions as in rec_in)
+  const uint32_t *off;   // [nbuckets + 1] first record of every bucket
+  uint32_t nbuckets, n;
+  int low_bits;          // bits left to sort, <= 32
+  int b_bits;            // OUT_UNPACK: minor index width
+  // extra split of the big buckets
+  uint32_t *counters;    // [0] big buckets, [1] their tiles, [2] groups
+  BigBucket *big; uint32_t big_cap;
+  uint32_t *tilemap; uint32_t tile_cap;   // tile -> index into big
+  uint32_t *shist;       // [tile_cap][RS_BINS] digit counts per tile, then prefixes inside the bucket
+  uint32_t *sdig;        // [big_cap][RS_BINS] first position of every piece inside its bucket
+  WorkItem *work; uint32_t work_cap;
+  // output
+  int32_t *major_out, *minor_out;
+  uint64_t *key64_out;
+  uint32_t *val_out;
+  Flags *flags;
+};
+
+__device__ __forceinline__ uint32_t split_digit(const LocalArgs &a, uint32_t lo) {
+  const uint32_t low = a.low_bits >= 32 ? lo : (lo & ((1u << a.low_bits) - 1u));
+  return a.low_bits > RS_MAXBITS ? (low >> (a.low_bits - RS_MAXBITS)) : low;   // top 8 of the low bits
+}
+
+__global__ __launch_bounds__(256) void bucket_offsets_kernel(const Rec *rec, uint32_t n, int low_bits, uint32_t nbuckets,
+                                                            uint32_t *off) {
+  const uint32_t b = blockIdx.x * 256 + threadIdx.x;
+  if (b > nbuckets) return;
+  uint32_t lo = 0, hi = n;   // first record whose prefix is >= b
+  while (lo < hi) {
+    const uint32_t mid = lo + ((hi - lo) >> 1);
+    const Rec r = rec[mid];
+    const uint64_t prefix = (((uint64_t)r.hi << 32) | r.lo) >> low_bits;
+    if (prefix < b) lo = mid + 1; else hi = mid;
+  }
+  off[b] = b == nbuckets ? n : lo;
+}
+
+// offsets come from searches over device data (garbage keys when a coordinate was out of range):
+// nothing beyond this check is trusted to keep accesses inside [0, n)
+__device__ __forceinline__ bool bucket_range(const LocalArgs &a, uint32_t b, uint32_t *first, uint32_t *size) {
+  const uint32_t f = a.off[b], l = a.off[b + 1];
+  if (l > a.n || f >= l) return false;
+  *first = f; *size = l - f;
+  return true;
+}
+
+__global__ __launch_bounds__(256) void big_list_kernel(LocalArgs a) {
+  const uint32_t b = blockIdx.x * 256 + threadIdx.x;
+  uint32_t first, size;
+  if (b >= a.nbuckets || !bucket_range(a, b, &first, &size) || size <= (uint32_t)LS_CAP) return;
+  const uint32_t ntiles = (size + RS_TILE - 1) / RS_TILE;
+  if (ntiles > (uint32_t)LS_MAXTILES) { a.flags->sort_retry = 1; return; }
+  const uint32_t k = atomicAdd(&a.counters[0], 1u);
+  const uint32_t tb = atomicAdd(&a.counters[1], ntiles);
+  if (k >= a.big_cap || tb + ntiles > a.tile_cap) { a.flags->sort_retry = 1; return; }   // overlapping garbage ranges only
+  a.big[k] = BigBucket{b, first, size, tb};
+  for (uint32_t j = 0; j < ntiles; ++j) a.tilemap[tb + j] = k;
+}
+
+__global__ __launch_bounds__(RS_T) void seg_hist_kernel(LocalArgs a) {
+  __shared__ uint32_t s_hist[RS_BINS];
+  const uint32_t t = blockIdx.x;
+  if (t >= min(a.counters[1], a.tile_cap)) return;
+  for (int i = threadIdx.x; i < RS_BINS; i += RS_T) s_hist[i] = 0;
+  __syncthreads();
+  const BigBucket B = a.big[min(a.tilemap[t], a.big_cap - 1)];
+  const uint32_t begin = (t - B.tile_base) * RS_TILE, end = min(begin + (uint32_t)RS_TILE, B.size);
+  for (uint32_t i = begin + threadIdx.x; i < end; i += RS_T) atomicAdd(&s_hist[split_digit(a, a.rec_in[B.first + i].lo)], 1u);
+  __syncthreads();
+  for (uint32_t d = threadIdx.x; d < RS_BINS; d += RS_T) a.shist[(size_t)t * RS_BINS + d] = s_hist[d];
+}
+
+// one workgroup per big bucket: prefixes of the (tile, digit) counts, piece starts, bundling into groups
+__global__ __launch_bounds__(RS_BINS) void seg_scan_kernel(LocalArgs a) {
+  __shared__ uint32_t s_wave[RS_BINS / 64 + 1];
+  __shared__ uint32_t s_pos[RS_BINS + 1];    // piece starts, then group starts
+  __shared__ uint32_t s_base;
+  const uint32_t k = blockIdx.x;
+  if (k >= min(a.counters[0], a.big_cap)) return;
+  const BigBucket B = a.big[k];
+  const uint32_t ntiles = (B.size + RS_TILE - 1) / RS_TILE, d = threadIdx.x;
+  uint32_t run = 0;
+  for (uint32_t j = 0; j < ntiles; ++j) {
+    uint32_t *h = a.shist + (size_t)(B.tile_base + j) * RS_BINS + d;
+    const uint32_t v = *h;
+    *h = run;
+    run += v;
+  }
+  uint32_t total;
+  const uint32_t start = block_exclusive_sum<RS_BINS>(run, s_wave, &total);
+  a.sdig[(size_t)k * RS_BINS + d] = start;
+  if (run > (uint32_t)LS_GROUP) a.flags->sort_retry = 1;
+  s_pos[d] = start;
+  if (d == 0) s_pos[RS_BINS] = B.size;
+  __syncthreads();
+  // piece d opens a group when its start falls in another LS_GROUP-sized interval than the one before
+  const bool head = d == 0 || start / LS_GROUP != s_pos[d - 1] / LS_GROUP;
+  uint32_t nheads;
+  const uint32_t rank = block_exclusive_sum<RS_BINS>(head ? 1u : 0u, s_wave, &nheads);
+  if (d == 0) s_base = atomicAdd(&a.counters[2], nheads);
+  __syncthreads();
+  if (head) s_pos[rank] = start;    // ranks <= d: slots below are no longer needed as piece starts
+  if (d == 0) s_pos[nheads] = B.size;
+  __syncthreads();
+  if (head) {
+    const uint32_t g = s_base + rank, gsize = s_pos[rank + 1] - start;
+    if (g < a.work_cap) a.work[g] = WorkItem{B.first + start, gsize, B.bucket};
+    else a.flags->sort_retry = 1;
+  }
+}
+
+__global__ __launch_bounds__(RS_T) void seg_scatter_kernel(LocalArgs a) {
+  __shared__ uint32_t s_next[RS_BINS];
+  const uint32_t t = blockIdx.x;
+  if (t >= min(a.counters[1], a.tile_cap)) return;
+  const uint32_t k = min(a.tilemap[t], a.big_cap - 1);
+  const BigBucket B = a.big[k];
+  for (uint32_t d = threadIdx.x; d < RS_BINS; d += RS_T)
+    s_next[d] = B.first + a.sdig[(size_t)k * RS_BINS + d] + a.shist[(size_t)t * RS_BINS + d];
+  __syncthreads();
+  const uint32_t begin = (t - B.tile_base) * RS_TILE, end = min(begin + (uint32_t)RS_TILE, B.size);
+  for (uint32_t i = begin + threadIdx.x; i < end; i += RS_T) {
+    const Rec r = a.rec_in[B.first + i];
+    // the order inside a piece is settled by the full sort of its group, so any free slot will do
+    const uint32_t at = atomicAdd(&s_next[split_digit(a, r.lo)], 1u);
+    if (at < a.n) a.rec_split[at] = r;
+  }
+}
+
+// Sort the cnt <= NT*IPT items in s_key / s_val [0, cnt) by the low `bits` bits of the keys, in place.
+// Item t belongs to the thread with t = wave*(64*IPT) + j*64 + lane.  Between passes the items live
+// in LDS only: registers hold them just for the exchange, which keeps the kernel near 64 VGPRs.
+template <int NT, int IPT>
+__device__ __forceinline__ void lds_sort(uint32_t cnt, int bits, uint32_t *s_key, uint32_t *s_val,
+                                         uint32_t (*s_cnt)[RS_BINS], uint32_t *s_start, uint32_t *s_wave) {
+  constexpr int NW = NT / 64;
+  const int lane = lane_id(), w = wave_id();
+  const uint32_t lane_lo = lane < 32 ? (1u << lane) - 1u : 0xFFFFFFFFu;
+  const uint32_t lane_hi = lane < 32 ? 0u : (1u << (lane - 32)) - 1u;
+  const int npass = (bits + RS_MAXBITS - 1) / RS_MAXBITS;
+  const uint32_t t0 = w * (64 * IPT) + lane;
+  int shift = 0;
+  for (int p = 0; p < npass; ++p) {
+    const int width = bits / npass + (p < bits % npass ? 1 : 0);
+    const uint32_t mask = (1u << width) - 1u;
+    for (uint32_t i = threadIdx.x; i < NW * RS_BINS; i += NT) (&s_cnt[0][0])[i] = 0;
+    __syncthreads();
+    uint32_t key[IPT], val[IPT], pos[IPT];
+    // reads below are unguarded (t < NT*IPT always lies inside the arrays); a slot past cnt holds
+    // stale data and is masked out of the ranking
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) key[j] = s_key[t0 + j * 64];
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) {
+      const uint32_t t = t0 + j * 64;
+      const bool valid = t < cnt;
+      const uint32_t d = (key[j] >> shift) & mask;
+      const uint64_t vb = __ballot(valid);
+      uint32_t plo = (uint32_t)vb, phi = (uint32_t)(vb >> 32);
+#pragma unroll
+      for (int b = 0; b < RS_MAXBITS; ++b) {
+        const uint64_t bal = __ballot((d >> b) & 1u);
+        const uint32_t keep = (uint32_t)((int32_t)(~d << (31 - b)) >> 31);
+        plo &= (uint32_t)bal ^ keep;
+        phi &= (uint32_t)(bal >> 32) ^ keep;
+      }
+      const uint32_t before = __popc(plo & lane_lo) + __popc(phi & lane_hi);
+      // every peer reads the wave's running count of the digit, then the first peer advances it with
+      // an add that returns nothing: LDS serves one wavefront's accesses in program order, so the
+      // reads see the count before the add and nothing here waits for an LDS round trip
+      const uint32_t old = valid ? s_cnt[w][d] : 0u;
+      if (valid && before == 0) __hip_atomic_fetch_add(&s_cnt[w][d], __popc(plo) + __popc(phi), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+      pos[j] = old + before;
+      __builtin_amdgcn_wave_barrier();
+    }
+    __syncthreads();
+    uint32_t digit_total = 0;
+    if (threadIdx.x < RS_BINS) {
+#pragma unroll
+      for (int ww = 0; ww < NW; ++ww) {
+        const uint32_t c = s_cnt[ww][threadIdx.x];
+        s_cnt[ww][threadIdx.x] = digit_total;
+        digit_total += c;
+      }
+    }
+    uint32_t dummy;
+    const uint32_t start = block_exclusive_sum<NT>(digit_total, s_wave, &dummy);
+    if (threadIdx.x < RS_BINS) s_start[threadIdx.x] = start;
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) {
+      const uint32_t d = (key[j] >> shift) & mask;
+      val[j] = s_val[t0 + j * 64];
+      pos[j] += s_start[d] + s_cnt[w][d];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) {
+      if (t0 + j * 64 < cnt) {
+        s_key[pos[j]] = key[j];
+        s_val[pos[j]] = val[j];
+      }
+    }
+    __syncthreads();
+    shift += width;
+  }
+}
+
+template <int OUT>
+__device__ __forceinline__ void local_emit(const LocalArgs &a, uint32_t bucket, uint32_t g, uint32_t k, uint32_t v) {
+  const uint64_t full = ((uint64_t)bucket << a.low_bits) | (uint64_t)k;
+  if (OUT == OUT_UNPACK) {
+    a.major_out[g] = (int32_t)(full >> a.b_bits);
+    a.minor_out[g] = (int32_t)(full & ((1ull << a.b_bits) - 1ull));
+  } else {
+    a.key64_out[g] = full;
+  }
+  a.val_out[g] = v;
+}
+
+// workgroup i < nbuckets: bucket i if it is small enough; workgroup nbuckets + g: group g of a split bucket
+template <int OUT>
+__global__ __launch_bounds__(LS_T, 4) void local_sort_kernel(LocalArgs a) {
+  __shared__ uint32_t s_key[LS_CAP];
+  __shared__ uint32_t s_val[LS_CAP];
+  __shared__ uint32_t s_cnt[LS_T / 64][RS_BINS];
+  __shared__ uint32_t s_start[RS_BINS];
+  __shared__ uint32_t s_wave[LS_T / 64 + 1];
+  uint32_t first, cnt, bucket;
+  const Rec *src;
+  if (blockIdx.x < a.nbuckets) {
+    bucket = blockIdx.x;
+    if (!bucket_range(a, bucket, &first, &cnt) || cnt > (uint32_t)LS_CAP) return;
+    src = a.rec_in;
+  } else {
+    const uint32_t g = blockIdx.x - a.nbuckets;
+    if (g >= min(a.counters[2], a.work_cap)) return;
+    const WorkItem wi = a.work[g];
+    first = wi.first; cnt = wi.size; bucket = wi.bucket;
+    if (cnt == 0 || cnt > (uint32_t)LS_CAP || first >= a.n || cnt > a.n - first) return;   // oversize pieces have set sort_retry
+    src = a.rec_split;
+  }
+  const uint32_t low_mask = a.low_bits >= 32 ? 0xFFFFFFFFu : ((1u << a.low_bits) - 1u);
+  for (uint32_t i = threadIdx.x; i < cnt; i += LS_T) {
+    const Rec r = src[first + i];
+    s_key[i] = r.lo & low_mask;
+    s_val[i] = r.val;
+  }
+  __syncthreads();
+  if (cnt <= LS_T) lds_sort<LS_T, 1>(cnt, a.low_bits, s_key, s_val, s_cnt, s_start, s_wave);
+  else if (cnt <= 2 * LS_T) lds_sort<LS_T, 2>(cnt, a.low_bits, s_key, s_val, s_cnt, s_start, s_wave);
+  else if (cnt <= 4 * LS_T) lds_sort<LS_T, 4>(cnt, a.low_bits, s_key, s_val, s_cnt, s_start, s_wave);
+  else if (cnt <= 8 * LS_T) lds_sort<LS_T, 8>(cnt, a.low_bits, s_key, s_val, s_cnt, s_start, s_wave);
+  else lds_sort<LS_T, 16>(cnt, a.low_bits, s_key, s_val, s_cnt, s_start, s_wave);
+  bool dup = false;
+  for (uint32_t i = threadIdx.x; i < cnt; i += LS_T) {
+    const uint32_t k = s_key[i];
+    dup |= i > 0 && s_key[i - 1] == k;
+    local_emit<OUT>(a, bucket, first + i, k, s_val[i]);
+  }
+  if (dup) a.flags->duplicate = 1;
 }
 
 template <int IN>
@@ -328,35 +617,49 @@ static void launch_scatter_out(Env &env, const PassArgs &a, int out_mode, double
 }
 
 // in_mode: IN_COO (row, col) or IN_KEY32 (key32_in).  Final output: unpacked (out.major set),
-// 64-bit keys (out.key64) or 32-bit keys (out.key32).
-static void sort_generic(Env &env, int in_mode, const int32_t *row, const int32_t *col, const uint32_t *key32_in,
+// 64-bit keys (out.key64) or 32-bit keys (out.key32).  Returns true when equal keys have been
+// looked for (and flagged) on the way.
+static bool sort_generic(Env &env, int in_mode, const int32_t *row, const int32_t *col, const uint32_t *key32_in,
                          const float *val, int64_t nnz, const KeySpec &ks, const SortOut &out, Flags *flags) {
-  if (nnz <= 0 || !env.ok()) return;
+  if (nnz <= 0 || !env.ok()) return false;
   const int final_mode = out.major ? OUT_UNPACK : (out.key64 ? OUT_KEY64 : OUT_KEY32);
   const int total_bits = ks.total_bits > 0 ? ks.total_bits : 1;
-  const int npass = ceil_div(total_bits, RS_MAXBITS);
+
+  // Whole-array passes over the top `high_bits`, then the in-LDS finish over the rest: enough top
+  // bits for buckets of 1024..2048 items on average, and at most 32 bits left over.
+  int high_bits = total_bits, low_bits = 0;
+  bool finish_local = false;
+  if (env.lds_finish && in_mode == IN_COO && final_mode != OUT_KEY32 && nnz >= 4096) {
+    const int want = bits_for((uint64_t)(nnz - 1) / 2048);
+    high_bits = want < total_bits ? want : total_bits;
+    if (total_bits - high_bits > 32) high_bits = total_bits - 32;
+    low_bits = total_bits - high_bits;
+    finish_local = high_bits > 0 && high_bits <= want + 3;   // else: buckets of a few items each, not worth it
+    if (!finish_local) { high_bits = total_bits; low_bits = 0; }
+  }
+
+  const int npass = ceil_div(high_bits, RS_MAXBITS);
   const uint32_t nblocks = (uint32_t)ceil_div<int64_t>(nnz, RS_TILE);
   const uint32_t nchunks = ceil_div<uint32_t>(nblocks, (uint32_t)RS_CHUNK);
+  const int nrec = finish_local ? npass : npass - 1;   // passes that write records
   Rec *rbuf[2] = {nullptr, nullptr};
   uint8_t *dbuf[2] = {nullptr, nullptr};
-  for (int i = 0; i < 2 && i < npass - 1; ++i) {
-    rbuf[i] = env.temp<Rec>(nnz);
-    dbuf[i] = env.temp<uint8_t>(nnz + 16);
-  }
+  for (int i = 0; i < 2 && i < nrec; ++i) rbuf[i] = env.temp<Rec>(nnz);
+  for (int i = 0; i < 2 && i < npass - 1; ++i) dbuf[i] = env.temp<uint8_t>(nnz + 16);
   uint32_t *hist = env.temp<uint32_t>((size_t)RS_BINS * nblocks);
   uint32_t *chunk = env.temp<uint32_t>((size_t)RS_BINS * nchunks);
   uint32_t *dtotal = env.temp<uint32_t>(RS_BINS);
-  if (!env.ok()) return;
+  if (!env.ok()) return false;
 
   int widths[16], shifts[16];
-  for (int p = 0, sh = 0; p < npass; ++p) {
-    widths[p] = total_bits / npass + (p < total_bits % npass ? 1 : 0);
+  for (int p = 0, sh = low_bits; p < npass; ++p) {
+    widths[p] = high_bits / npass + (p < high_bits % npass ? 1 : 0);
     shifts[p] = sh;
     sh += widths[p];
   }
   const double kb = 8.0;  // key bytes between passes
   for (int p = 0; p < npass; ++p) {
-    const bool first = p == 0, last = p == npass - 1;
+    const bool first = p == 0, last_pass = p == npass - 1, last = last_pass && !finish_local;
     PassArgs a{};
     a.row = first ? row : nullptr;
     a.col = first ? col : nullptr;
@@ -365,15 +668,15 @@ static void sort_generic(Env &env, int in_mode, const int32_t *row, const int32_
     a.val_in = first ? (const uint32_t *)val : nullptr;
     a.digit_in = first ? nullptr : dbuf[(p - 1) & 1];
     a.rec_out = last ? nullptr : rbuf[p & 1];
-    a.digit_out = last ? nullptr : dbuf[p & 1];
+    a.digit_out = last_pass ? nullptr : dbuf[p & 1];
     a.val_out = last ? (uint32_t *)out.val : nullptr;
     a.major_out = last ? out.major : nullptr;
     a.minor_out = last ? out.minor : nullptr;
     a.key64_out = last ? out.key64 : nullptr;
     a.key32_out = last ? out.key32 : nullptr;
     a.n = (uint32_t)nnz; a.shift = shifts[p]; a.mask = (1u << widths[p]) - 1u; a.nblocks = nblocks;
-    a.next_shift = last ? 0 : shifts[p + 1];
-    a.next_mask = last ? 0u : (1u << widths[p + 1]) - 1u;
+    a.next_shift = last_pass ? 0 : shifts[p + 1];
+    a.next_mask = last_pass ? 0u : (1u << widths[p + 1]) - 1u;
     a.tiles_per_xcd = ceil_div<uint32_t>(nblocks, 8u);
     a.hist = hist; a.chunk = chunk; a.dtotal = dtotal; a.nchunks = nchunks; a.ks = ks; a.flags = flags;
 
@@ -393,11 +696,47 @@ static void sort_generic(Env &env, int in_mode, const int32_t *row, const int32_
     else if (in == IN_KEY32) launch_scatter_out<IN_KEY32>(env, a, om, bytes);
     else launch_scatter_out<IN_SPLIT>(env, a, om, bytes);
   }
+  if (!finish_local) return false;
+
+  const uint32_t nbuckets = 1u << high_bits;
+  LocalArgs la{};
+  la.nbuckets = nbuckets; la.n = (uint32_t)nnz; la.low_bits = low_bits; la.b_bits = ks.b_bits;
+  la.big_cap = (uint32_t)(nnz / LS_CAP) + 1;                 // a big bucket holds more than LS_CAP items
+  la.tile_cap = (uint32_t)(nnz / RS_TILE) + la.big_cap;      // each has at most size/RS_TILE + 1 tiles
+  la.work_cap = (uint32_t)(nnz / LS_GROUP) + la.big_cap;     // ... and at most size/LS_GROUP + 1 groups
+  uint32_t *off = env.temp<uint32_t>((size_t)nbuckets + 1);
+  la.rec_in = rbuf[(npass - 1) & 1];
+  la.rec_split = npass >= 2 ? rbuf[npass & 1] : env.temp<Rec>(nnz);
+  la.counters = env.temp<uint32_t>(4);
+  la.big = env.temp<BigBucket>(la.big_cap);
+  la.tilemap = env.temp<uint32_t>(la.tile_cap);
+  la.shist = env.temp<uint32_t>((size_t)la.tile_cap * RS_BINS);
+  la.sdig = env.temp<uint32_t>((size_t)la.big_cap * RS_BINS);
+  la.work = env.temp<WorkItem>(la.work_cap);
+  if (!env.ok()) return false;
+  la.off = off;
+  la.major_out = out.major; la.minor_out = out.minor; la.key64_out = out.key64; la.val_out = (uint32_t *)out.val;
+  la.flags = flags;
+  fill_u32(env, la.counters, 4, 0u);
+  // entries that a garbage input (coordinates out of range) leaves unwritten must still index safely
+  fill_u32(env, (uint32_t *)la.big, (uint64_t)la.big_cap * 4, 0u);
+  fill_u32(env, la.tilemap, la.tile_cap, 0u);
+  US_LAUNCH(env, "bucket_offsets", 4.0 * nbuckets, bucket_offsets_kernel, ceil_div<uint32_t>(nbuckets + 1, 256u), 256,
+            la.rec_in, la.n, low_bits, nbuckets, off);
+  US_LAUNCH(env, "big_list", 8.0 * nbuckets, big_list_kernel, ceil_div<uint32_t>(nbuckets, 256u), 256, la);
+  US_LAUNCH(env, "seg_hist", 0.0, seg_hist_kernel, la.tile_cap, RS_T, la);
+  US_LAUNCH(env, "seg_scan", 0.0, seg_scan_kernel, la.big_cap, RS_BINS, la);
+  US_LAUNCH(env, "seg_scatter", 0.0, seg_scatter_kernel, la.tile_cap, RS_T, la);
+  if (final_mode == OUT_UNPACK)
+    US_LAUNCH(env, "local_sort", 24.0 * nnz, (local_sort_kernel<OUT_UNPACK>), nbuckets + la.work_cap, LS_T, la);
+  else
+    US_LAUNCH(env, "local_sort", 24.0 * nnz, (local_sort_kernel<OUT_KEY64>), nbuckets + la.work_cap, LS_T, la);
+  return true;
 }
 
-void sort_coo(Env &env, const int32_t *row, const int32_t *col, const float *val, int64_t nnz,
+bool sort_coo(Env &env, const int32_t *row, const int32_t *col, const float *val, int64_t nnz,
               const KeySpec &ks, const SortOut &out, Flags *flags_dev) {
-  sort_generic(env, IN_COO, row, col, nullptr, val, nnz, ks, out, flags_dev);
+  return sort_generic(env, IN_COO, row, col, nullptr, val, nnz, ks, out, flags_dev);
 }
 
 // ascending sort of 32-bit keys (no payload of interest)
