@@ -262,6 +262,12 @@ def other_workloads(B, W, torch, ctx, up, K, Wm):
     run("config3_dia_csr_spmv", m, lambda r, c, v: list(B.us_decompose(ctx, m.nrows, m.ncols, r, c, v, DIA, CSR, pd)),
         prod3, 2.0 * m.nnz,
         lambda p: 12.0 * m.nnz + 4.0 * p[0].val().numel() + 8.0 * p[1].nnz + 4.0 * m.nrows)
+    # the same matrix through the program of Figure 3c: blocked DIA (block 4) + CSR, #sum over (d0/4, d1-d0) >= 4
+    BDIA = B.us_desc_preset(B.US_F_BDIA, 4)
+    pb = B.make_predicate([E(B.US_E_DIV, 1, 0, 0, 4), E(B.US_E_AFFINE, -1, 1)], B.US_P_SUM_GE_ABS, abs_=4)
+    run("config3_bdia_csr_spmv", m, lambda r, c, v: list(B.us_decompose(ctx, m.nrows, m.ncols, r, c, v, BDIA, CSR, pb)),
+        prod3, 2.0 * m.nnz,
+        lambda p: 12.0 * m.nnz + 4.0 * p[0].val().numel() + 4.0 * p[0].idx(1).numel() + 8.0 * p[1].nnz + 4.0 * m.nrows)
     # config 4
     m = W.cfg4_blockfem()
     X = up(W.dense_operand(4, (m.ncols, 64))); Y = torch.empty(m.nrows, 64, device=dev)
@@ -269,6 +275,16 @@ def other_workloads(B, W, torch, ctx, up, K, Wm):
     run("config4_bcsr_spmm64", m, lambda r, c, v: [B.us_convert(ctx, m.nrows, m.ncols, r, c, v, BC)],
         lambda p: B.us_spmm(ctx, p[0], X, Y), 2.0 * m.nnz * 64,
         lambda p: 12.0 * m.nnz + 4.0 * p[0].val().numel() + 4.0 * p[0].idx(1).numel())
+    # option: buckets of equal top key bits finished inside LDS (entries spread evenly over block rows here)
+    B.us_set_sort_lds_finish(True)
+    try:
+        r, c, v = up(m.row), up(m.col), up(m.val)
+        ms = timed(torch, lambda: B.us_convert(ctx, m.nrows, m.ncols, r, c, v, BC).free(), K, Wm)
+        res["config4_bcsr_spmm64"]["convert_ms_lds_finish"] = round(ms, 4)
+        res["config4_bcsr_spmm64"]["convert_mnnz_s_lds_finish"] = round(m.nnz / ms / 1e3, 1)
+        del r, c, v
+    finally:
+        B.us_set_sort_lds_finish(False)
     del X, Y
     # config 5
     m = W.cfg5_powerlaw_local()

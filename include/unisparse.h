@@ -103,7 +103,9 @@ us_status us_desc_preset(int32_t format, int64_t b0, int64_t b1, us_format_desc 
  *   US_P_RANK_LT_PERCENTILE      rank < K, K = nearest-rank num/den percentile of the row
  *                                lengths over all rows (empty rows included)
  * group maps supported: (d1-d0), (d0), (d1) for the sum predicates; (d0) for the rank ones;
- * (d0/b, d1-d0) with US_P_SUM_GE_ABS (the #sum query of Figure 3c; part A must then be BDIA with the same b). */
+ * (d0/b, d1-d0) with US_P_SUM_GE_ABS (the #sum query of Figure 3c) and (d0/bh, d1/bw) with US_P_SUM_GE_ABS
+ * (entries per block, the threshold of the BELL/COO case study of Section 7.2.2), 1 <= b, bh, bw <= 16;
+ * a part A stored as BDIA(b) / BCSR(bh,bw) then needs no second sort. */
 enum { US_P_SUM_GE_ABS = 0, US_P_SUM_GE_FRAC_OF_CAPACITY = 1, US_P_RANK_LT_ABS = 2, US_P_RANK_LT_PERCENTILE = 3 };
 typedef struct us_predicate {
   us_expr group[2];

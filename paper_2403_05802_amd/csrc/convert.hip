@@ -1012,9 +1012,9 @@ static us_status decompose_rank(Env &env, const us_coo &coo, const Plan &pa, con
   return st;
 }
 
-// ------------------------------------------------------------------ decompose by (block row, diagonal) -- Figure 3c
-// The #sum query of the BDIA/CSR hybrid groups by (d0/b, d1-d0).  Such groups are exactly the
-// nodes of the BDIA tree, so the entries are sorted by the BDIA tuple first: a group is then a run
+// ------------------------------------------------------------------ decompose by the nodes of a blocked layout
+// The #sum query of the BDIA/CSR hybrid (Figure 3c) groups by (d0/b, d1-d0), the one of the BELL/COO case
+// study (Section 7.2.2) by blocks (d0/bh, d1/bw).  Such groups are exactly the nodes of the BDIA / BCSR tree, so the entries are sorted by the BDIA tuple first: a group is then a run
 // of the sorted list, its count is the run length, and the entries that stay (part A) are already
 // in BDIA order -- no second sort for them.
 __global__ __launch_bounds__(256) void node_head_kernel(const uint64_t *key, int64_t n, int ih_bits, int32_t *head,
@@ -1052,21 +1052,26 @@ __global__ __launch_bounds__(256) void node_split_kernel(const uint64_t *key, co
   const bool a = keep[i] != 0;
   const int64_t at = a ? pos_a[i] : i - pos_a[i];
   if (a && key_a) { key_a[at] = k; val_a[at] = val[i]; return; }
-  const uint64_t bk = k >> ks.ih_bits;
-  const int32_t row = (int32_t)((bk >> ks.b_bits) * ks.bh + (k & ((1ull << ks.ih_bits) - 1)));
-  const int32_t col = row + (int32_t)(bk & ((1ull << ks.b_bits) - 1)) - (int32_t)(ks.a_extent - 1);
+  const int inner = ks.ih_bits + ks.iw_bits;
+  const uint64_t bk = k >> inner;
+  const int32_t row = (int32_t)((bk >> ks.b_bits) * ks.bh + ((k >> ks.iw_bits) & ((1ull << ks.ih_bits) - 1)));
+  const int32_t second = (int32_t)(bk & ((1ull << ks.b_bits) - 1));
+  // blocked diagonal: the second component is d1 - d0 biased by nrows - 1; blocks: d1 / bw, with d1 % bw below
+  const int32_t col = ks.mode == 2 ? row + second - (int32_t)(ks.a_extent - 1)
+                                   : second * (int32_t)ks.bw + (int32_t)(k & ((1ull << ks.iw_bits) - 1));
   const CooLists &l = a ? la : lb;
   l.r[at] = row; l.c[at] = col; l.v[at] = val[i];
 }
 
-static us_status decompose_blockdiag(Env &env, const us_coo &coo, const Plan &pa, const us_format_desc &da,
-                                     const Plan &pb, const us_format_desc &db, int64_t b, int64_t thld,
-                                     us_formatted **oa, us_formatted **ob) {
+static us_status decompose_blocked(Env &env, const us_coo &coo, const Plan &pa, const us_format_desc &da,
+                                   const Plan &pb, const us_format_desc &db, const Plan &pg, int64_t thld,
+                                   us_formatted **oa, us_formatted **ob) {
   Flags *flags = new_flags(env);
   const int64_t n = coo.nnz;
-  Plan pg; pg.pattern = P_BDIA; pg.bh = b; pg.bw = 1;
   const KeySpec ks = blocked_keyspec(pg, coo.nrows, coo.ncols);
-  const bool direct = pa.pattern == P_BDIA && pa.bh == b;   // part A keeps the sorted order
+  const int inner_bits = ks.ih_bits + ks.iw_bits;
+  // part A keeps the sorted order when it is stored by the very tuple the groups were cut by
+  const bool direct = pa.pattern == pg.pattern && pa.bh == pg.bh && pa.bw == pg.bw;
   uint64_t *skey = env.temp<uint64_t>(n);
   float *sval = env.temp<float>(n);
   int32_t *head = env.temp<int32_t>(n), *pos = env.temp<int32_t>(n), *start = env.temp<int32_t>(n + 1);
@@ -1078,7 +1083,7 @@ static us_status decompose_blockdiag(Env &env, const us_coo &coo, const Plan &pa
     so.key64 = skey; so.val = sval;
     sort_coo(env, coo.row, coo.col, coo.val, n, ks, so, flags);
     const int64_t g = ceil_div<int64_t>(n, 256);
-    US_LAUNCH(env, "node_head", 12.0 * n, node_head_kernel, g, 256, (const uint64_t *)skey, n, ks.ih_bits, head, flags);
+    US_LAUNCH(env, "node_head", 12.0 * n, node_head_kernel, g, 256, (const uint64_t *)skey, n, inner_bits, head, flags);
     exclusive_scan_i32(env, head, pos, n, &flags->scalar[0]);
     US_LAUNCH(env, "node_start", 12.0 * n, node_start_kernel, g, 256, (const int32_t *)head, (const int32_t *)pos, n,
               start);
@@ -1128,10 +1133,15 @@ us_status decompose_impl(Env &env, const us_coo &coo, const us_format_desc &da, 
   if (!match_desc(da, &pa) || !match_desc(db, &pb)) return US_ERR_UNSUPPORTED_DESC;
   if ((pa.pattern == P_ELL && pa.swapped) || (pb.pattern == P_ELL && pb.swapped)) return US_ERR_UNSUPPORTED_DESC;
   if (pred.ngroup == 2) {
-    int64_t b;
-    if (!tile(pred.group[0], US_E_DIV, 0, &b) || !aff(pred.group[1], -1, 1) || pred.kind != US_P_SUM_GE_ABS)
-      return US_ERR_UNSUPPORTED_DESC;
-    s = decompose_blockdiag(env, coo, pa, da, pb, db, b, pred.abs, oa, ob);
+    // groups that are the nodes of a blocked layout: (d0/b, d1-d0) of Figure 3c, or the blocks (d0/bh, d1/bw)
+    // of the BELL/COO case study (Section 7.2.2: "non-zero threshold within each block")
+    Plan pg;
+    int64_t bh, bw;
+    if (pred.kind != US_P_SUM_GE_ABS || !tile(pred.group[0], US_E_DIV, 0, &bh)) return US_ERR_UNSUPPORTED_DESC;
+    if (aff(pred.group[1], -1, 1)) { pg.pattern = P_BDIA; pg.bh = bh; pg.bw = 1; }
+    else if (tile(pred.group[1], US_E_DIV, 1, &bw)) { pg.pattern = P_BCSR; pg.bh = bh; pg.bw = bw; }
+    else return US_ERR_UNSUPPORTED_DESC;
+    s = decompose_blocked(env, coo, pa, da, pb, db, pg, pred.abs, oa, ob);
     if (s == US_OK && !env.ok()) s = env.status;
     if (s != US_OK) {
       if (*oa) { free_formatted(env, *oa); *oa = nullptr; }

@@ -1,5 +1,6 @@
-"""The BDIA/CSR hybrid of Figure 3c: decompose by the #sum query over (d0/b, d1-d0), part A
-stored as blocked DIA (Figure 9 addressing val[node*b + d0%b]), part B as CSR; HIP vs oracle."""
+"""Hybrids cut by the nodes of a blocked layout: the BDIA/CSR program of Figure 3c (#sum over (d0/b, d1-d0),
+part A as blocked DIA, Figure 9 addressing val[node*b + d0%b]) and the per-block threshold of the BELL/COO case
+study (Section 7.2.2); HIP vs oracle."""
 import numpy as np
 import pytest
 import torch
@@ -121,3 +122,46 @@ def test_bdia_hybrid_on_scaled_banded_workload(ctx):
     yref = O.spmv(oa, x) + O.spmv(ob, x)
     np.testing.assert_allclose(yref, O.spmv_coo(m.nrows, m.ncols, m.row, m.col, m.val, x), atol=1e-9)
     assert rel_err(host(y), yref, O.abs_row_sums(m.nrows, m.row, m.col, m.val, x)) <= TOL
+
+
+def clustered_blocks(nr, nc, seed, bh, bw, dense_blocks, fill, extra):
+    """`dense_blocks` random bh x bw blocks filled to `fill`, plus `extra` scattered entries, shuffled."""
+    rng = np.random.default_rng(seed)
+    nbr, nbc = -(-nr // bh), -(-nc // bw)
+    blk = rng.choice(nbr * nbc, dense_blocks, replace=False)
+    rows, cols = [], []
+    for b in blk.tolist():
+        br, bc = divmod(b, nbc)
+        ii, jj = np.meshgrid(np.arange(bh), np.arange(bw), indexing="ij")
+        keep = rng.random((bh, bw)) < fill
+        rows.append(br * bh + ii[keep]); cols.append(bc * bw + jj[keep])
+    r = np.concatenate(rows + [rng.integers(0, nr, extra)]); c = np.concatenate(cols + [rng.integers(0, nc, extra)])
+    ok = (r < nr) & (c < nc)
+    lin = np.unique(r[ok].astype(np.int64) * nc + c[ok])
+    lin = lin[rng.permutation(lin.size)]
+    v = rng.uniform(0.1, 1, lin.size).astype(np.float32)
+    return (lin // nc).astype(np.int32), (lin % nc).astype(np.int32), v
+
+
+@pytest.mark.parametrize("bh,bw,thld", [(4, 4, 8), (2, 3, 4), (8, 8, 1), (16, 2, 33), (4, 4, 0)])
+def test_block_threshold_hybrid(ctx, bh, bw, thld):
+    """Decomposition of the BELL/COO case study (Section 7.2.2): blocks holding at least `thld` entries go to
+    the blocked part (stored as BCSR here), the rest stays COO; SpMM over the hybrid."""
+    from paper_2403_05802_amd import binding as B
+    from helpers import TOL, assert_same_layout, dev, host, rel_err, us_desc_of, us_pred_of
+    nr, nc = 1003, 2050
+    r, c, v = clustered_blocks(nr, nc, seed=bh * 10 + bw, bh=bh, bw=bw, dense_blocks=1500, fill=0.8, extra=20_000)
+    pred = O.Predicate((O.div(0, bh), O.div(1, bw)), O.SUM_GE_ABS, abs=thld)
+    for da, db in ((O.BCSR(bh, bw), O.COO()), (O.CSR(), O.DCSR())):
+        oa, ob, mask = O.decompose(nr, nc, r, c, v, da, db, pred)
+        ga, gb = B.us_decompose(ctx, nr, nc, dev(r), dev(c), dev(v), us_desc_of(da), us_desc_of(db), us_pred_of(pred))
+        assert_same_layout(ga, oa, "A"); assert_same_layout(gb, ob, "B")
+        if thld == 8:
+            assert 0 < mask.sum() < mask.size
+        rng = np.random.default_rng(2)
+        X = rng.uniform(-1, 1, (nc, 33)).astype(np.float32)
+        Y = torch.full((nr, 33), 9.0, device="cuda")
+        B.us_spmm(ctx, ga, dev(X), Y); B.us_spmm(ctx, gb, dev(X), Y, accumulate=True)
+        S = O.spmm_coo(nr, nc, r, c, np.abs(v), np.abs(X))
+        assert rel_err(host(Y), O.spmm_coo(nr, nc, r, c, v, X), S) <= TOL
+        ga.free(); gb.free()
