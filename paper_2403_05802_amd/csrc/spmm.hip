@@ -18,6 +18,26 @@ __device__ __forceinline__ int64_t xcd_tile(int64_t i, int64_t per_xcd) { return
 // independent 4x4 += (4x1)(1x4) products; feeding the same A column to all 16 and 64
 // different X columns gives Y[4 x 64] += A[:,k] X[k, 64 cols] per instruction, i.e. lane l
 // ends up holding column l of the 4 output rows.
+//
+// HBM is not what binds this kernel (its fetches are the compulsory ones; the 3.2 GB of gathered X rows
+// come out of L2), instruction issue and L1 traffic are: a wave64 VALU instruction occupies its SIMD for
+// 4 cycles and a 64-lane load of 16 bytes per lane costs the L1 a kilobyte whatever it returns.  So
+//  * block columns are read with one coalesced load per 64 blocks and handed out by v_readlane (scalars),
+//    the address of a gathered row is scalar arithmetic plus a per-lane offset that never changes;
+//  * the values of four blocks (64 floats) are ONE coalesced load, lane (u, k, r) taking element [r][k] of
+//    block u, i.e. the block transposed on the way in: lanes 4q .. 4q+3 then hold column k of block u with
+//    q = 4u + k, exactly the four A values of a 4x4x1 product, and the MFMA's A-broadcast (cbsz = 4,
+//    abid = q) feeds them to all 16 of its blocks -- no copies of A across lanes, no shuffles;
+//  * full groups of four blocks run without any bounds logic (ncols % 4 == 0 means no block sticks out
+//    of the matrix; otherwise the guarded path takes every block).
+constexpr int BCSR_R = 2;   // groups of four blocks in flight: 16 * BCSR_R gathered rows per wavefront before the first MFMA
+
+template <int Q>
+__device__ __forceinline__ float4v mfma_bcast(float a, float x, float4v acc) {
+  return __builtin_amdgcn_mfma_f32_4x4x1f32(a, x, acc, 4, Q, 0);
+}
+
+template <int R>
 __global__ __launch_bounds__(256) void bcsr44_spmm_mfma_kernel(const int32_t *ptr, const int32_t *idx,
                                                               const float *val, int64_t nbr, int64_t per_xcd,
                                                               int64_t nrows, int64_t ncols, const float *X,
@@ -28,30 +48,50 @@ __global__ __launch_bounds__(256) void bcsr44_spmm_mfma_kernel(const int32_t *pt
   if (br >= nbr) return;
   const int64_t c = (int64_t)blockIdx.y * 64 + lane;
   const bool col_ok = c < N;
+  const uint32_t xoff = (uint32_t)(col_ok ? c : N - 1);           // clamped: loads stay in bounds, stores are guarded
+  // lane = 16u + 4k + r reads element 16u + 4r + k of the group's 64 values
+  const uint32_t toff = (uint32_t)((lane & 48) | ((lane & 3) << 2) | ((lane >> 2) & 3));
+  const uint32_t aoff = (uint32_t)(lane & 3) * 4u;                  // guarded path: row of the block this lane feeds
+  const bool cols_divide = (ncols & 3) == 0;
   float4v acc = {0.f, 0.f, 0.f, 0.f};
-  const int b0 = ptr[br], b1 = ptr[br + 1];
-  const int arow = lane & 3;
-  constexpr int U = 4;  // blocks in flight: 16 X-row loads per wavefront before the first MFMA
+  const int b0 = __builtin_amdgcn_readfirstlane(ptr[br]), b1 = __builtin_amdgcn_readfirstlane(ptr[br + 1]);
   for (int bb = b0; bb < b1; bb += 64) {
     const int cnt = min(64, b1 - bb);
     const int32_t my_bc = lane < cnt ? idx[bb + lane] : 0;   // block columns of the next 64 blocks, one per lane
-    for (int j0 = 0; j0 < cnt; j0 += U) {
-      float4v a[U];
-      float xv[U][4];
+    const int full = cols_divide ? cnt / (4 * R) * (4 * R) : 0;
+    for (int j0 = 0; j0 < full; j0 += 4 * R) {
+      float a[R];
+      float xv[R][4][4];
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int j = j0 + u;
-        const bool ok = j < cnt;
-        const int64_t xr = (int64_t)__shfl(my_bc, ok ? j : 0) * 4;
-        a[u] = ok ? *reinterpret_cast<const float4v *>(val + (int64_t)(bb + j) * 16 + arow * 4)
-                  : float4v{0.f, 0.f, 0.f, 0.f};
+      for (int g = 0; g < R; ++g) {
+        a[g] = (val + (int64_t)(bb + j0 + 4 * g) * 16)[toff];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) xv[u][k] = (ok && col_ok && xr + k < ncols) ? X[(xr + k) * ldx + c] : 0.f;
+        for (int u = 0; u < 4; ++u) {
+          const int64_t xr = (int64_t)__builtin_amdgcn_readlane(my_bc, j0 + 4 * g + u) * 4;
+#pragma unroll
+          for (int k = 0; k < 4; ++k) xv[g][u][k] = (X + (xr + k) * ldx)[xoff];
+        }
       }
 #pragma unroll
-      for (int u = 0; u < U; ++u)
+      for (int g = 0; g < R; ++g) {
+        acc = mfma_bcast<0>(a[g], xv[g][0][0], acc);  acc = mfma_bcast<1>(a[g], xv[g][0][1], acc);
+        acc = mfma_bcast<2>(a[g], xv[g][0][2], acc);  acc = mfma_bcast<3>(a[g], xv[g][0][3], acc);
+        acc = mfma_bcast<4>(a[g], xv[g][1][0], acc);  acc = mfma_bcast<5>(a[g], xv[g][1][1], acc);
+        acc = mfma_bcast<6>(a[g], xv[g][1][2], acc);  acc = mfma_bcast<7>(a[g], xv[g][1][3], acc);
+        acc = mfma_bcast<8>(a[g], xv[g][2][0], acc);  acc = mfma_bcast<9>(a[g], xv[g][2][1], acc);
+        acc = mfma_bcast<10>(a[g], xv[g][2][2], acc); acc = mfma_bcast<11>(a[g], xv[g][2][3], acc);
+        acc = mfma_bcast<12>(a[g], xv[g][3][0], acc); acc = mfma_bcast<13>(a[g], xv[g][3][1], acc);
+        acc = mfma_bcast<14>(a[g], xv[g][3][2], acc); acc = mfma_bcast<15>(a[g], xv[g][3][3], acc);
+      }
+    }
+    for (int j = full; j < cnt; ++j) {   // guarded: leftover blocks, or a last block column that sticks out of the matrix
+      const int64_t xr = (int64_t)__builtin_amdgcn_readlane(my_bc, j) * 4;
+      const float4v av = *reinterpret_cast<const float4v *>(val + (int64_t)(bb + j) * 16 + aoff);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) acc = __builtin_amdgcn_mfma_f32_4x4x1f32(a[u][k], xv[u][k], acc, 0, 0, 0);
+      for (int k = 0; k < 4; ++k) {
+        const float x = xr + k < ncols ? X[(xr + k) * ldx + xoff] : 0.f;
+        acc = __builtin_amdgcn_mfma_f32_4x4x1f32(av[k], x, acc, 0, 0, 0);
+      }
     }
   }
   if (col_ok) {
@@ -381,7 +421,7 @@ us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, 
         const int64_t tiles = ceil_div<int64_t>(A.nmajor, 4), per_xcd = ceil_div<int64_t>(tiles, 8);
         if (env.ok()) {
           LaunchScope ls(env, "spmm_bcsr44_mfma", 4.0 * A.nval + 4.0 * A.nblk + 4.0 * (A.nmajor + 1) + xy);
-          hipLaunchKernelGGL(bcsr44_spmm_mfma_kernel, dim3((unsigned)(per_xcd * 8), (unsigned)ncb), dim3(256), 0,
+          hipLaunchKernelGGL(bcsr44_spmm_mfma_kernel<BCSR_R>, dim3((unsigned)(per_xcd * 8), (unsigned)ncb), dim3(256), 0,
                              env.stream, (const int32_t *)A.level[1].ptr, (const int32_t *)A.level[1].idx,
                              (const float *)A.val, A.nmajor, per_xcd, A.nrows, A.ncols, X, N, ldx, Y, ldy, acc);
           env.check(hipGetLastError());

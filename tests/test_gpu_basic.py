@@ -137,3 +137,37 @@ def test_error_paths(ctx):
     with pytest.raises(B.UnisparseError) as ei:   # N = 0
         B._check(B.lib().us_spmm(B.C.byref(ctx.c), g.handle, X.data_ptr(), 0, 4, X.data_ptr(), 4, 0), "us_spmm")
     assert ei.value.code == "US_ERR_SHAPE"
+
+
+@pytest.mark.parametrize("nc", [512, 530])
+@pytest.mark.parametrize("N", [3, 64, 70, 200])
+def test_bcsr44_spmm_fast_and_guarded_groups(ctx, nc, N):
+    """4x4 blocks on the matrix cores: block rows with 0..70 blocks (full groups of eight, leftovers, more than
+    64 blocks), a block grid that divides the matrix (nc = 512) or sticks out of it (530), ragged N."""
+    from paper_2403_05802_amd import binding as B
+    from helpers import TOL, dev, host, rel_err, us_desc_of
+    rng = np.random.default_rng(nc + N)
+    nr = 301
+    rows, cols = [], []
+    for br in range((nr + 3) // 4):
+        nb = int(rng.integers(0, 71)) if br % 5 else 0
+        for bc in rng.choice((nc + 3) // 4, size=min(nb, (nc + 3) // 4), replace=False):
+            k = int(rng.integers(1, 17))
+            e = rng.choice(16, size=k, replace=False)
+            rows.append(br * 4 + e // 4); cols.append(bc * 4 + e % 4)
+    r = np.concatenate(rows).astype(np.int32); c = np.concatenate(cols).astype(np.int32)
+    keep = (r < nr) & (c < nc)
+    r, c = r[keep], c[keep]
+    p = rng.permutation(r.size); r, c = r[p], c[p]
+    v = rng.uniform(-1, 1, r.size).astype(np.float32); v[v == 0] = 0.5
+    g = B.us_convert(ctx, nr, nc, dev(r), dev(c), dev(v), us_desc_of(O.BCSR(4)))
+    X = rng.uniform(-1, 1, (nc, N)).astype(np.float32)
+    S = O.spmm_coo(nr, nc, r, c, np.abs(v), np.abs(X))
+    Y = torch.full((nr, N), -3.0, device="cuda")
+    B.us_spmm(ctx, g, dev(X), Y)
+    assert rel_err(host(Y), O.spmm_coo(nr, nc, r, c, v, X), S) <= TOL
+    Y0 = rng.uniform(-1, 1, (nr, N)).astype(np.float32)
+    Y = dev(Y0)
+    B.us_spmm(ctx, g, dev(X), Y, accumulate=True)
+    assert rel_err(host(Y), O.spmm_coo(nr, nc, r, c, v, X) + Y0, S + np.abs(Y0)) <= TOL
+    g.free()
