@@ -137,20 +137,27 @@ template <> struct VecT<1> { typedef float type; };
 template <> struct VecT<2> { typedef float type __attribute__((ext_vector_type(2))); };
 template <> struct VecT<4> { typedef float type __attribute__((ext_vector_type(4))); };
 
-// ELL: a wavefront owns 8 consecutive rows.  One coalesced load brings the column indices of
-// 8 slots x 8 rows (lane = slot*8 + row), which are then broadcast one by one while every
-// lane gathers its columns of X: up to 64 independent 256/512-byte gathers per wavefront are
-// in flight, instead of one row's worth.  Pad slots gather row 0 (cached) and are not added.
+// ELL: a wavefront owns 8 consecutive rows.  One coalesced load brings the column indices and values
+// of 8 slots x 8 rows (lane = slot*8 + row); they are handed out by v_readlane, i.e. as scalars, so
+// the address of a gathered row is scalar arithmetic plus a fixed per-lane offset, the gather of a pad
+// slot is skipped by a scalar branch (two thirds of the slots of a percentile-wide slab are pads; its
+// operand is a zero, written unconditionally: a vector-typed register array assigned only inside
+// branches makes the compiler copy it per branch, 46 -> 300 VGPRs), and up to 8 independent
+// 256/512-byte gathers per wavefront are in flight.
+// Workgroups are dealt round-robin to the 8 XCDs; launch index -> row tile goes through xcd_tile so
+// that each XCD sweeps one contiguous range of rows and the rows of X that neighbouring matrix rows
+// share (local columns) are found again in that XCD's L2.
 template <int VEC>
 __global__ __launch_bounds__(256) void ell_spmm_kernel(const int32_t *ecol, const float *ev, int64_t K, int64_t nrows,
-                                                      const float *X, int64_t N, int64_t ldx, float *Y, int64_t ldy,
-                                                      int accumulate) {
+                                                      int64_t per_xcd, const float *X, int64_t N, int64_t ldx, float *Y,
+                                                      int64_t ldy, int accumulate) {
   typedef typename VecT<VEC>::type V;
   const int lane = lane_id();
-  const int64_t i0 = ((int64_t)blockIdx.x * 4 + wave_id()) * 8;
+  const int64_t i0 = (xcd_tile(blockIdx.x, per_xcd) * 4 + wave_id()) * 8;
   if (i0 >= nrows) return;
   const int64_t c = ((int64_t)blockIdx.y * 64 + lane) * VEC;
   const bool col_ok = c < N;
+  const uint32_t xoff = (uint32_t)(col_ok ? c : 0);   // clamped: loads stay in bounds (N >= VEC), stores are guarded
   V acc[8];
 #pragma unroll
   for (int r = 0; r < 8; ++r)
@@ -161,22 +168,26 @@ __global__ __launch_bounds__(256) void ell_spmm_kernel(const int32_t *ecol, cons
     const bool ok = kk < K && i < nrows;
     const int32_t mycol = ok ? __builtin_nontemporal_load(ecol + kk * nrows + i) : -1;
     const float myval = ok ? __builtin_nontemporal_load(ev + kk * nrows + i) : 0.f;
-    if (__ballot(mycol >= 0) == 0) break;  // slots fill from the front: all 8 rows have ended
+    const uint64_t live = __ballot(mycol >= 0);   // bit slot*8 + row
+    if (live == 0) break;  // slots fill from the front: all 8 rows have ended
 #pragma unroll
     for (int s8 = 0; s8 < 8; ++s8) {
-      int32_t cs[8];
-      float vs[8];
+      const uint32_t live8 = (uint32_t)(live >> (s8 * 8)) & 0xFFu;   // scalar: which of the 8 rows have this slot
+      if (live8 == 0) break;
       V xv[8];
 #pragma unroll
       for (int r = 0; r < 8; ++r) {
-        cs[r] = __builtin_amdgcn_readlane(mycol, s8 * 8 + r);
-        vs[r] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, myval), s8 * 8 + r));
+        xv[r] = V(0.f);
+        if (live8 & (1u << r)) {
+          const int64_t cs = __builtin_amdgcn_readlane(mycol, s8 * 8 + r);
+          xv[r] = *reinterpret_cast<const V *>(X + cs * ldx + xoff);
+        }
       }
 #pragma unroll
-      for (int r = 0; r < 8; ++r)
-        xv[r] = col_ok ? *reinterpret_cast<const V *>(X + (int64_t)(cs[r] < 0 ? 0 : cs[r]) * ldx + c) : V(0.f);
-#pragma unroll
-      for (int r = 0; r < 8; ++r) acc[r] += cs[r] >= 0 ? vs[r] * xv[r] : V(0.f);
+      for (int r = 0; r < 8; ++r) {
+        const float vs = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, myval), s8 * 8 + r));
+        acc[r] += vs * xv[r];
+      }
     }
   }
   if (col_ok) {
@@ -254,16 +265,19 @@ constexpr int CS_CHUNK = 512;
 
 template <int VEC>
 __global__ __launch_bounds__(256) void coo_spmm_kernel(RowSrc row, const int32_t *col, const float *val,
-                                                      int64_t nnz, const float *X, int64_t N, int64_t ldx, float *Y,
-                                                      int64_t ldy, int32_t *carry_row, float *carry) {
+                                                      int64_t nnz, int64_t per_xcd, const float *X, int64_t N, int64_t ldx,
+                                                      float *Y, int64_t ldy, int32_t *carry_row, float *carry) {
   typedef typename VecT<VEC>::type V;
   const int lane = lane_id();
-  const int64_t chunk = (int64_t)blockIdx.x * 4 + wave_id();
+  // launch index -> chunk through xcd_tile: an XCD walks one contiguous range of entries (rows), so the
+  // rows of X that neighbouring matrix rows share are found again in its own L2
+  const int64_t chunk = xcd_tile(blockIdx.x, per_xcd) * 4 + wave_id();
   const int64_t e0 = chunk * CS_CHUNK;
   if (e0 >= nnz) return;
   const int64_t e1 = min(e0 + CS_CHUNK, nnz);
   const int64_t c = ((int64_t)blockIdx.y * 64 + lane) * VEC;
   const bool col_ok = c < N;
+  const uint32_t xoff = (uint32_t)(col_ok ? c : 0);   // clamped: loads stay in bounds, stores are guarded
   const int32_t row_before = e0 > 0 ? row.of(e0 - 1) : -1;
   const int32_t row_after = e1 < nnz ? row.of(e1) : -1;
   const int32_t first_row = row.of(e0), last_row = row.of(e1 - 1);
@@ -276,20 +290,22 @@ __global__ __launch_bounds__(256) void coo_spmm_kernel(RowSrc row, const int32_t
   constexpr int U = 8;
   for (int64_t base = e0; base < e1; base += 64) {
     const int64_t e = base + lane;
-    int32_t r = e < e1 ? row.of(e) : -1, cc = e < e1 ? __builtin_nontemporal_load(col + e) : 0;
-    float v = e < e1 ? __builtin_nontemporal_load(val + e) : 0.f;
+    const int32_t r = e < e1 ? row.of(e) : -1, cc = e < e1 ? __builtin_nontemporal_load(col + e) : 0;
+    const float v = e < e1 ? __builtin_nontemporal_load(val + e) : 0.f;
     const int cnt = (int)min((int64_t)64, e1 - base);
     for (int t0 = 0; t0 < cnt; t0 += U) {
+      // row, column and value of entry t are scalars (v_readlane): the gather address is scalar
+      // arithmetic plus a fixed per-lane offset and the row-change test is a scalar branch
       int32_t rt[U];
       float vt[U];
       V xv[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {   // 8 gathers of X rows in flight
         const int t = t0 + u < cnt ? t0 + u : cnt - 1;
-        rt[u] = __shfl(r, t);
-        vt[u] = __shfl(v, t);
-        const int32_t ct = __shfl(cc, t);
-        xv[u] = col_ok ? *reinterpret_cast<const V *>(X + (int64_t)ct * ldx + c) : V(0.f);
+        rt[u] = __builtin_amdgcn_readlane(r, t);
+        vt[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), t));
+        const int64_t ct = __builtin_amdgcn_readlane(cc, t);
+        xv[u] = *reinterpret_cast<const V *>(X + ct * ldx + xoff);
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
@@ -391,10 +407,11 @@ static void entry_balanced_spmm(Env &env, const us_formatted &A, const RowSrc &r
   float *carry = (float *)(ws + rows_pad);
   {
     LaunchScope ls(env, name, 12.0 * A.nnz + xy);
-    const dim3 grid((unsigned)ceil_div<int64_t>(nchunks, 4), (unsigned)ncbv);
-    if (vec == 4) hipLaunchKernelGGL(coo_spmm_kernel<4>, grid, dim3(256), 0, env.stream, rs, col, (const float *)A.val, A.nnz, X, N, ldx, Y, ldy, carry_row, carry);
-    else if (vec == 2) hipLaunchKernelGGL(coo_spmm_kernel<2>, grid, dim3(256), 0, env.stream, rs, col, (const float *)A.val, A.nnz, X, N, ldx, Y, ldy, carry_row, carry);
-    else hipLaunchKernelGGL(coo_spmm_kernel<1>, grid, dim3(256), 0, env.stream, rs, col, (const float *)A.val, A.nnz, X, N, ldx, Y, ldy, carry_row, carry);
+    const int64_t per_xcd = ceil_div<int64_t>(ceil_div<int64_t>(nchunks, 4), 8);
+    const dim3 grid((unsigned)(per_xcd * 8), (unsigned)ncbv);
+    if (vec == 4) hipLaunchKernelGGL(coo_spmm_kernel<4>, grid, dim3(256), 0, env.stream, rs, col, (const float *)A.val, A.nnz, per_xcd, X, N, ldx, Y, ldy, carry_row, carry);
+    else if (vec == 2) hipLaunchKernelGGL(coo_spmm_kernel<2>, grid, dim3(256), 0, env.stream, rs, col, (const float *)A.val, A.nnz, per_xcd, X, N, ldx, Y, ldy, carry_row, carry);
+    else hipLaunchKernelGGL(coo_spmm_kernel<1>, grid, dim3(256), 0, env.stream, rs, col, (const float *)A.val, A.nnz, per_xcd, X, N, ldx, Y, ldy, carry_row, carry);
     env.check(hipGetLastError());
   }
   if (env.ok()) {
@@ -438,11 +455,12 @@ us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, 
     case P_ELL:
       if (env.ok()) {
         LaunchScope ls(env, "spmm_ell", 8.0 * A.nval + xy);
-        const dim3 grid((unsigned)ceil_div<int64_t>(A.nrows, 32), (unsigned)ceil_div<int64_t>(N, 64 * vec));
+        const int64_t tiles = ceil_div<int64_t>(A.nrows, 32), per_xcd = ceil_div<int64_t>(tiles, 8);
+        const dim3 grid((unsigned)(per_xcd * 8), (unsigned)ceil_div<int64_t>(N, 64 * vec));
         const int32_t *ec = A.level[2].idx;
-        if (vec == 4) hipLaunchKernelGGL(ell_spmm_kernel<4>, grid, dim3(256), 0, env.stream, ec, (const float *)A.val, A.nmajor, A.nrows, X, N, ldx, Y, ldy, acc);
-        else if (vec == 2) hipLaunchKernelGGL(ell_spmm_kernel<2>, grid, dim3(256), 0, env.stream, ec, (const float *)A.val, A.nmajor, A.nrows, X, N, ldx, Y, ldy, acc);
-        else hipLaunchKernelGGL(ell_spmm_kernel<1>, grid, dim3(256), 0, env.stream, ec, (const float *)A.val, A.nmajor, A.nrows, X, N, ldx, Y, ldy, acc);
+        if (vec == 4) hipLaunchKernelGGL(ell_spmm_kernel<4>, grid, dim3(256), 0, env.stream, ec, (const float *)A.val, A.nmajor, A.nrows, per_xcd, X, N, ldx, Y, ldy, acc);
+        else if (vec == 2) hipLaunchKernelGGL(ell_spmm_kernel<2>, grid, dim3(256), 0, env.stream, ec, (const float *)A.val, A.nmajor, A.nrows, per_xcd, X, N, ldx, Y, ldy, acc);
+        else hipLaunchKernelGGL(ell_spmm_kernel<1>, grid, dim3(256), 0, env.stream, ec, (const float *)A.val, A.nmajor, A.nrows, per_xcd, X, N, ldx, Y, ldy, acc);
         env.check(hipGetLastError());
       }
       return env.status;
