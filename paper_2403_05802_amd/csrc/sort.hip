@@ -18,7 +18,9 @@
 // dropped: with ~770 tiles resident at once and status words that must cross the XCDs' L2s,
 // the serial look-back (one device-scope load per predecessor and digit) ran 40x slower than
 // the separate histogram + scan.  Digit totals accumulated with device atomics were dropped
-// too: same-address atomics cost ~20 ns each here and serialised the histogram kernel.
+// too: same-address atomics cost ~20 ns each here and serialised the histogram kernel.  Wider digits do not
+// pay either: with 10 bits (4 passes instead of 5 for 40-bit keys, 48-byte runs per tile and digit) a scatter
+// pass took 152 us instead of 107.
 #include "common.h"
 #include "device.h"
 
