@@ -38,8 +38,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--only-headline", action="store_true", help="skip the four other workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--pmc", action="store_true",
-                    help="counter-collection workload: 3 plain copies of 256 MiB (calibration), then 3 headline steps")
+    ap.add_argument("--pmc", nargs="?", const="headline", default=None, choices=["headline", "config4", "config5"],
+                    help="counter-collection workload for rocprofv3 --pmc: 3 plain copies of 256 MiB (calibration), "
+                         "then 3 headline steps (default), or 3 products of config 4 (BCSR SpMM) / config 5 (ELL+COO SpMM)")
     return ap.parse_args()
 
 
@@ -115,10 +116,16 @@ def main():
         for _ in range(3):
             b.copy_(a)
         torch.cuda.synchronize()
-        for _ in range(3):
-            step()
-        torch.cuda.synchronize()
-        print(json.dumps({"pmc_workload": "3 copies of 268435456 B, then 3 headline steps", "nnz": nnz}))
+        del a, b
+        if args.pmc == "headline":
+            for _ in range(3):
+                step()
+            torch.cuda.synchronize()
+            what = "3 headline steps"
+        else:
+            del r, c, v
+            what = pmc_products(B, W, torch, ctx, up, args.pmc)
+        print(json.dumps({"pmc_workload": "3 copies of 268435456 B, then " + what}))
         return
 
     # the timed steps: W warm-up, then exactly K, with a HIP event pair around every launch of the
@@ -223,6 +230,28 @@ def main():
     }
     line.update(out)
     print(json.dumps(line))
+
+
+def pmc_products(B, W, torch, ctx, up, which):
+    """Three products of config 4 (COO->BCSR once, then SpMM N=64) or config 5 (decompose once, then the
+    hybrid SpMM N=128), for a rocprofv3 --pmc run."""
+    dev = torch.device("cuda:0")
+    if which == "config4":
+        m = W.cfg4_blockfem()
+        parts = [B.us_convert(ctx, m.nrows, m.ncols, up(m.row), up(m.col), up(m.val), B.us_desc_preset(B.US_F_BCSR, 4, 4))]
+        N = 64
+    else:
+        m = W.cfg5_powerlaw_local()
+        pr = B.make_predicate([B.expr(B.US_E_AFFINE, 1, 0)], B.US_P_RANK_LT_PERCENTILE, 9, 10)
+        parts = list(B.us_decompose(ctx, m.nrows, m.ncols, up(m.row), up(m.col), up(m.val),
+                                    B.us_desc_preset(B.US_F_ELL), B.us_desc_preset(B.US_F_COO), pr))
+        N = 128
+    X = up(W.dense_operand(int(which[-1]), (m.ncols, N))); Y = torch.empty(m.nrows, N, device=dev)
+    for _ in range(3):
+        for k, p in enumerate(parts):
+            B.us_spmm(ctx, p, X, Y, accumulate=k > 0)
+        torch.cuda.synchronize()
+    return f"3 products of {which} (N = {N}, {m.nnz} nnz)"
 
 
 def other_workloads(B, W, torch, ctx, up, K, Wm):
