@@ -197,19 +197,6 @@ __global__ __launch_bounds__(256) void ell_spmm_kernel(const int32_t *ecol, cons
   }
 }
 
-__global__ __launch_bounds__(256) void csr_spmm_kernel(const int32_t *ptr, const int32_t *idx, const float *val,
-                                                      const int32_t *row_ids, int64_t nrows_stored, const float *X,
-                                                      int64_t N, int64_t ldx, float *Y, int64_t ldy, int accumulate) {
-  const int64_t i = (int64_t)blockIdx.x * 4 + wave_id();
-  if (i >= nrows_stored) return;
-  const int64_t c = (int64_t)blockIdx.y * 64 + lane_id();
-  if (c >= N) return;
-  const int64_t row = row_ids ? row_ids[i] : i;
-  float s = accumulate ? Y[row * ldy + c] : 0.f;
-  for (int e = ptr[i]; e < ptr[i + 1]; ++e) s += val[e] * X[(int64_t)idx[e] * ldx + c];
-  Y[row * ldy + c] = s;
-}
-
 __global__ __launch_bounds__(256) void dia_spmm_kernel(const int32_t *off, const float *val, int64_t ndiag,
                                                       int64_t nrows, int64_t ncols, int by_col, const float *X,
                                                       int64_t N, int64_t ldx, float *Y, int64_t ldy, int accumulate) {
