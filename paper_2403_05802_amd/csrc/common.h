@@ -42,7 +42,8 @@ struct Env {
   Profile *prof;
   us_status status = US_OK;
   std::vector<void *> temps;  // temporaries, released by release_temps() after the stream is idle
-  bool lds_finish;            // sort: finish buckets inside LDS (cleared for the retry after Flags::sort_retry)
+  bool lds_finish;            // sort: finish buckets inside LDS (cleared for the retry after Flags::retry)
+  bool dia_marks = false;     // DIA slab: find occupied slots with a byte map instead of the fill pattern (set for the retry)
 
   explicit Env(const us_ctx *c)
       : ctx(c), stream(c ? (hipStream_t)c->hip_stream : nullptr), prof(c ? (Profile *)c->profile : nullptr),
@@ -120,16 +121,18 @@ struct us_formatted {
 
 namespace us {
 
-// internal status: the sort met a bucket too large for its in-LDS finish (Flags::sort_retry); the
-// entry point runs the call again with Env::lds_finish cleared.  Never returned to the caller.
+// internal status: a fast path met an input it cannot take (Flags::retry): a bucket too large for the
+// in-LDS finish of the sort, or a value carrying the bit pattern that marks empty DIA slots.  The entry
+// point runs the call again with Env::lds_finish cleared and Env::dia_marks set.  Never returned to the caller.
 constexpr us_status US_SORT_RETRY = -100;
+enum { RETRY_SORT_LDS = 1, RETRY_DIA_MARKS = 2 };
 
 // device-side status flags written by kernels, read back once per call
 struct Flags {
   int32_t index_range;  // != 0: some coordinate out of range
   int32_t duplicate;    // != 0: two equal keys
   int32_t ell_overflow; // != 0: an entry's rank >= fixed ELL width
-  int32_t sort_retry;   // != 0: a bucket was too large for the in-LDS finish; the host sorts again without it
+  int32_t retry;        // != 0: a fast path met an input it cannot take (RETRY_*); the entry point runs the call again without them
   int32_t scalar[4];    // data-dependent sizes (nnr, ndiag, nblk, K, nnz_a ...)
 };
 

@@ -96,10 +96,20 @@ __global__ __launch_bounds__(256) void dcsr_compact_kernel(const int32_t *ptr, c
   }
 }
 
+// Kernels that end with one atomic per workgroup on a single counter run on at most ONE_COUNTER_GRID
+// workgroups (grid-stride loops): same-address device atomics cost ~20 ns apiece on this part, so
+// thousands of them would outlast the kernel's real work.
+constexpr int ONE_COUNTER_GRID = 768;
+static inline int64_t one_counter_grid(int64_t items, int per_block) {
+  const int64_t g = ceil_div<int64_t>(items, per_block);
+  return g < ONE_COUNTER_GRID ? (g > 0 ? g : 1) : ONE_COUNTER_GRID;
+}
+
 __global__ __launch_bounds__(256) void max_len_kernel(const int32_t *ptr, int64_t n, int32_t *out_max) {
   __shared__ int32_t s_max[4];
-  int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  int32_t len = g < n ? ptr[g + 1] - ptr[g] : 0;
+  int32_t len = 0;
+  for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < n; g += (int64_t)gridDim.x * 256)
+    len = max(len, ptr[g + 1] - ptr[g]);
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) len = max(len, __shfl_xor(len, d));
   if (lane_id() == 0) s_max[wave_id()] = len;
@@ -133,7 +143,7 @@ static bool read_flags(Env &env, Flags *dev, Flags *host) {
 }
 
 static us_status flag_status(const Flags &h) {
-  if (h.sort_retry) return US_SORT_RETRY;
+  if (h.retry) return US_SORT_RETRY;
   if (h.index_range) return US_ERR_INDEX_RANGE;
   if (h.duplicate) return US_ERR_DUPLICATE;
   if (h.ell_overflow) return US_ERR_SHAPE;
@@ -262,7 +272,7 @@ static us_status build_from_sorted(Env &env, const Plan &plan, const us_format_d
   if (plan.pattern == P_ELL) {
     int64_t K = plan.ell_width;
     if (K == 0)
-      US_LAUNCH(env, "max_row_len", 4.0 * nmaj, max_len_kernel, ceil_div<int64_t>(nmaj, 256), 256,
+      US_LAUNCH(env, "max_row_len", 4.0 * nmaj, max_len_kernel, one_counter_grid(nmaj, 256), 256,
                 (const int32_t *)ptr, nmaj, &flags->scalar[0]);
     us_status s = flags_ok(&h);
     if (s != US_OK) return finish(s);
@@ -296,10 +306,15 @@ __device__ __forceinline__ uint32_t group_bin(int gkind, uint32_t r, uint32_t c,
 }
 
 // One counter per group.  A matrix whose entries sit on a handful of diagonals would send
-// almost every update to the same few counters, so updates are combined twice before they
-// reach HBM: lanes of a wavefront that hit the same bin elect a leader (a few rounds), and the
-// leaders accumulate into a small LDS hash table that the workgroup flushes once.
-constexpr int GH_T = 256, GH_IPT = 16, GH_TILE = GH_T * GH_IPT, GH_SLOTS = 1024, GH_ROUNDS = 8, GH_PROBES = 8;
+// almost every update to the same few counters, and same-address HBM atomics cost ~20 ns apiece
+// on this part, so updates are combined in a small LDS hash table first (LDS takes 64 lanes
+// hitting one slot in about as many cycles; electing one lane per bin with ballots beforehand was
+// slower).  A workgroup walks several tiles; after each it flushes and frees the slots that stayed
+// cold and keeps the hot ones, so a hot counter gets one HBM atomic per workgroup (at most
+// ONE_COUNTER_GRID of them), not one per tile.  Freeing a slot may cut a probe chain; the bin then
+// simply takes a second slot, and counts add up all the same.
+constexpr int GH_T = 256, GH_IPT = 16, GH_TILE = GH_T * GH_IPT, GH_SLOTS = 1024, GH_PROBES = 8;
+constexpr uint32_t GH_HOT = 64;
 
 __global__ __launch_bounds__(GH_T) void group_hist_kernel(const int32_t *row, const int32_t *col, int64_t n,
                                                          int gkind, uint32_t nrows, uint32_t ncols, uint32_t *count,
@@ -308,47 +323,45 @@ __global__ __launch_bounds__(GH_T) void group_hist_kernel(const int32_t *row, co
   __shared__ uint32_t s_cnt[GH_SLOTS];
   for (int i = threadIdx.x; i < GH_SLOTS; i += GH_T) { s_key[i] = 0xFFFFFFFFu; s_cnt[i] = 0; }
   __syncthreads();
-  const int64_t base = (int64_t)blockIdx.x * GH_TILE;
-  uint32_t bin[GH_IPT];
   bool bad = false;
+  for (int64_t base = (int64_t)blockIdx.x * GH_TILE; base < n; base += (int64_t)gridDim.x * GH_TILE) {
+    uint32_t bin[GH_IPT];
 #pragma unroll
-  for (int k = 0; k < GH_IPT; ++k) {
-    int64_t i = base + k * GH_T + threadIdx.x;
-    bin[k] = 0xFFFFFFFFu;
-    if (i < n) {
-      uint32_t r = (uint32_t)row[i], c = (uint32_t)col[i];
-      if (r >= nrows || c >= ncols) bad = true;
-      else bin[k] = group_bin(gkind, r, c, nrows);
+    for (int k = 0; k < GH_IPT; ++k) {
+      int64_t i = base + k * GH_T + threadIdx.x;
+      bin[k] = 0xFFFFFFFFu;
+      if (i < n) {
+        uint32_t r = (uint32_t)row[i], c = (uint32_t)col[i];
+        if (r >= nrows || c >= ncols) bad = true;
+        else bin[k] = group_bin(gkind, r, c, nrows);
+      }
     }
-  }
-  if (bad) flags->index_range = 1;
-  const int lane = lane_id();
 #pragma unroll 1
-  for (int k = 0; k < GH_IPT; ++k) {
-    uint32_t b = bin[k], add = b != 0xFFFFFFFFu ? 1u : 0u;
-    uint64_t todo = __ballot(add != 0);
-    for (int round = 0; round < GH_ROUNDS && todo; ++round) {
-      int leader = __ffsll((unsigned long long)todo) - 1;
-      uint32_t lb = __shfl(b, leader);
-      uint64_t same = __ballot(add != 0 && b == lb) & todo;
-      if (lane == leader) add = (uint32_t)__popcll(same);
-      else if ((same >> lane) & 1ull) add = 0;   // counted by the leader
-      todo &= ~same;
-    }
-    if (add) {
+    for (int k = 0; k < GH_IPT; ++k) {
+      const uint32_t b = bin[k];
+      if (b == 0xFFFFFFFFu) continue;
       uint32_t h = (b * 2654435761u) >> 22;
       bool done = false;
       for (int probe = 0; probe < GH_PROBES && !done; ++probe) {
-        uint32_t old = atomicCAS(&s_key[h], 0xFFFFFFFFu, b);
-        if (old == 0xFFFFFFFFu || old == b) { atomicAdd(&s_cnt[h], add); done = true; }
+        uint32_t old = s_key[h];   // a bin that is already in the table (the hot ones, soon) needs no CAS
+        if (old == 0xFFFFFFFFu) old = atomicCAS(&s_key[h], 0xFFFFFFFFu, b);
+        if (old == 0xFFFFFFFFu || old == b) { atomicAdd(&s_cnt[h], 1u); done = true; }
         h = (h + 1) & (GH_SLOTS - 1);
       }
-      if (!done) atomicAdd(&count[b], add);
+      if (!done) atomicAdd(&count[b], 1u);
     }
+    __syncthreads();
+    const bool last = base + (int64_t)gridDim.x * GH_TILE >= n;
+    for (int i = threadIdx.x; i < GH_SLOTS; i += GH_T) {
+      const uint32_t c = s_cnt[i];
+      if (s_key[i] != 0xFFFFFFFFu && (last || c < GH_HOT)) {
+        if (c) atomicAdd(&count[s_key[i]], c);
+        s_key[i] = 0xFFFFFFFFu; s_cnt[i] = 0;
+      }
+    }
+    __syncthreads();
   }
-  __syncthreads();
-  for (int i = threadIdx.x; i < GH_SLOTS; i += GH_T)
-    if (s_key[i] != 0xFFFFFFFFu && s_cnt[i]) atomicAdd(&count[s_key[i]], s_cnt[i]);
+  if (bad) flags->index_range = 1;
 }
 
 // flag[g] = group g goes to part A.  pkind < 0: every non-empty group (plain conversion).
@@ -356,27 +369,30 @@ __global__ __launch_bounds__(GH_T) void group_hist_kernel(const int32_t *row, co
 __global__ __launch_bounds__(256) void group_flag_kernel(const uint32_t *count, int64_t nbins, int gkind, int pkind,
                                                         int64_t num, int64_t den, int64_t thr, int64_t nrows,
                                                         int64_t ncols, int32_t *flag, int32_t *nnz_a) {
-  int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  uint32_t cnt = g < nbins ? count[g] : 0u;
-  bool f = false;
-  if (cnt > 0) {
-    if (pkind < 0) f = true;
-    else if (pkind == US_P_SUM_GE_ABS) f = (int64_t)cnt >= thr;
-    else {
-      int64_t cap;
-      if (gkind == G_DIAG) {
-        int64_t off = g - (nrows - 1);
-        int64_t hi = nrows < ncols - off ? nrows : ncols - off, lo = off < 0 ? -off : 0;
-        cap = hi > lo ? hi - lo : 0;
-      } else cap = gkind == G_ROW ? ncols : nrows;
-      f = den * (int64_t)cnt >= num * cap;
+  __shared__ uint32_t s_wave[256 / 64 + 1];
+  uint32_t mine = 0;
+  for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < nbins; g += (int64_t)gridDim.x * 256) {
+    const uint32_t cnt = count[g];
+    bool f = false;
+    if (cnt > 0) {
+      if (pkind < 0) f = true;
+      else if (pkind == US_P_SUM_GE_ABS) f = (int64_t)cnt >= thr;
+      else {
+        int64_t cap;
+        if (gkind == G_DIAG) {
+          int64_t off = g - (nrows - 1);
+          int64_t hi = nrows < ncols - off ? nrows : ncols - off, lo = off < 0 ? -off : 0;
+          cap = hi > lo ? hi - lo : 0;
+        } else cap = gkind == G_ROW ? ncols : nrows;
+        f = den * (int64_t)cnt >= num * cap;
+      }
     }
+    flag[g] = f ? 1 : 0;
+    if (f) mine += cnt;
   }
-  if (g < nbins) flag[g] = f ? 1 : 0;
-  uint32_t mine = f ? cnt : 0u;
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) mine += __shfl_xor(mine, d);
-  if (lane_id() == 0 && mine) atomicAdd(nnz_a, (int32_t)mine);
+  uint32_t total;
+  block_exclusive_sum<256>(mine, s_wave, &total);
+  if (threadIdx.x == 0 && total) atomicAdd(nnz_a, (int32_t)total);
 }
 
 // gmap[g] = position of group g among the flagged groups, or -1; offsets of the flagged diagonals
@@ -394,10 +410,13 @@ __global__ __launch_bounds__(256) void diag_offsets_kernel(const int32_t *gmap, 
 struct CooLists { int32_t *r = nullptr, *c = nullptr; float *v = nullptr; };
 
 // One pass over the COO list that sends every entry to its part of a decomposition.
-//   TO_SLAB: entries of flagged diagonals go straight into the zero-filled DIA slab
-//            val[k*L + i] (Devectorize/Fill/Vectorize) and mark their slot in a byte map (a
-//            slot marked twice = duplicate coordinate: the number of marked slots then falls
-//            short of the number of entries, checked afterwards);
+//   TO_SLAB: entries of flagged diagonals go straight into the DIA slab val[k*L + i]
+//            (Devectorize/Fill/Vectorize).  A duplicate coordinate shows as fewer occupied slots
+//            than entries, counted afterwards.  Occupied = not the fill pattern: the slab starts
+//            out filled with DIA_EMPTY (a NaN bit pattern no computation produces) and a finishing
+//            pass counts and zeroes what is left of it, which costs two streaming passes over the
+//            slab instead of one more scattered byte store per entry (a byte map of marked slots,
+//            the form used when an input value happens to carry that very bit pattern);
 //   otherwise they are appended to list A.  Entries of unflagged groups are appended to list B.
 // Appends reserve space once per workgroup (one atomic per list), so order inside a list is
 // arbitrary; each part is put into canonical order by its conversion.
@@ -405,12 +424,13 @@ struct CooLists { int32_t *r = nullptr, *c = nullptr; float *v = nullptr; };
 // L2-sized window, was measured and dropped: the extra pass cost more than the ~110 G
 // scattered store transactions per second the direct form already sustains.)
 constexpr int SP_T = 512, SP_IPT = 16, SP_TILE = SP_T * SP_IPT;
+constexpr uint32_t DIA_EMPTY = 0x7FC5A5A5u;
 
 template <bool TO_SLAB>
 __global__ __launch_bounds__(SP_T) void split_kernel(const int32_t *row, const int32_t *col, const float *val,
                                                     int64_t n, int gkind, uint32_t nrows, const int32_t *gmap,
                                                     int64_t L, int by_col, float *slab, uint8_t *slotmap,
-                                                    CooLists la, CooLists lb, int32_t *cursors) {
+                                                    CooLists la, CooLists lb, int32_t *cursors, Flags *flags) {
   __shared__ uint32_t s_wave[SP_T / 64 + 1];
   __shared__ int32_t s_base[2];
   const int64_t base = (int64_t)blockIdx.x * SP_TILE;
@@ -448,7 +468,8 @@ __global__ __launch_bounds__(SP_T) void split_kernel(const int32_t *row, const i
       if (TO_SLAB) {
         int64_t slot = (int64_t)g[k] * L + (by_col ? c[k] : r[k]);
         slab[slot] = v[k];
-        slotmap[slot] = 1;
+        if (slotmap) slotmap[slot] = 1;
+        else if (__float_as_uint(v[k]) == DIA_EMPTY) flags->retry = RETRY_DIA_MARKS;
       } else if (la.r) {
         la.r[pa] = (int32_t)r[k]; la.c[pa] = (int32_t)c[k]; la.v[pa] = v[k]; ++pa;
       }
@@ -456,6 +477,26 @@ __global__ __launch_bounds__(SP_T) void split_kernel(const int32_t *row, const i
       lb.r[pb] = (int32_t)r[k]; lb.c[pb] = (int32_t)c[k]; lb.v[pb] = v[k]; ++pb;
     }
   }
+}
+
+// occupied slots of a slab that started out as DIA_EMPTY; what is still empty becomes +0.0
+__global__ __launch_bounds__(256) void dia_finish_kernel(uint4 *slab4, int64_t nvec, int64_t nslots, int32_t *out) {
+  __shared__ uint32_t s_wave[256 / 64 + 1];
+  uint32_t cnt = 0;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * 256) {
+    uint4 w = slab4[i];
+    uint32_t *e = reinterpret_cast<uint32_t *>(&w);
+    bool changed = false;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (i * 4 + k >= nslots) continue;   // the allocation is padded to whole vectors
+      if (e[k] == DIA_EMPTY) { e[k] = 0u; changed = true; } else ++cnt;
+    }
+    if (changed) slab4[i] = w;
+  }
+  uint32_t total;
+  block_exclusive_sum<256>(cnt, s_wave, &total);
+  if (threadIdx.x == 0 && total) atomicAdd(out, (int32_t)total);
 }
 
 // number of marked slots (bytes are 0 or 1; the map is padded with zeros to a multiple of 16)
@@ -506,23 +547,27 @@ static us_status dia_from_flags(Env &env, const us_coo &coo, const Plan &plan, c
   f->nlevels = 2;
   f->level[0].idx = env.owned<int32_t>(ndiag); f->level[0].nidx = ndiag;
   f->level[1].size = L;
-  f->val = env.owned<float>(ndiag * L); f->nval = ndiag * L; f->nmajor = ndiag;
+  const int64_t nslab4 = ceil_div<int64_t>(ndiag * L, 4);
+  f->val = env.owned<float>(nslab4 * 4); f->nval = ndiag * L; f->nmajor = ndiag;   // whole 16-byte vectors
+  const bool marks = env.dia_marks;
   const int64_t nvec = ceil_div<int64_t>(ndiag * L, 16) + 1;
-  uint8_t *slotmap = (uint8_t *)env.temp<uint4>(nvec);
+  uint8_t *slotmap = marks ? (uint8_t *)env.temp<uint4>(nvec) : nullptr;
   CooLists lb;
   if (rest) { *nrest = n - na; lb = alloc_lists(env, n - na); *rest = lb; }
   if (!env.ok()) { free_formatted(env, f); return env.status; }
-  fill_u32(env, (uint32_t *)f->val, ndiag * L, 0u);
-  fill_u32(env, (uint32_t *)slotmap, nvec * 4, 0u);
+  fill_u32(env, (uint32_t *)f->val, ndiag * L, marks ? 0u : DIA_EMPTY);
+  if (marks) fill_u32(env, (uint32_t *)slotmap, nvec * 4, 0u);
   fill_u32(env, (uint32_t *)cursors, 2, 0u);
   US_LAUNCH(env, "diag_offsets", 8.0 * nbins, diag_offsets_kernel, ceil_div<int64_t>(nbins, 256), 256,
             (const int32_t *)gmap, nbins, (int32_t)coo.nrows, f->level[0].idx);
   if (n > 0)
     US_LAUNCH(env, "dia_split_scatter", 12.0 * n + 5.0 * na + 12.0 * (rest ? n - na : 0), (split_kernel<true>),
               ceil_div<int64_t>(n, SP_TILE), SP_T, coo.row, coo.col, coo.val, n, (int)G_DIAG, (uint32_t)coo.nrows,
-              (const int32_t *)gmap, L, plan.swapped ? 1 : 0, f->val, slotmap, CooLists(), lb, cursors);
-  US_LAUNCH(env, "count_marks", 1.0 * ndiag * L, count_marks_kernel, nvec < 4096 * 256 ? ceil_div<int64_t>(nvec, 256) : 4096,
-            256, (const uint4 *)slotmap, nvec, &flags->scalar[3]);
+              (const int32_t *)gmap, L, plan.swapped ? 1 : 0, f->val, slotmap, CooLists(), lb, cursors, flags);
+  if (marks)
+    US_LAUNCH(env, "count_marks", 1.0 * ndiag * L, count_marks_kernel, one_counter_grid(nvec, 256), 256, (const uint4 *)slotmap, nvec, &flags->scalar[3]);
+  else if (nslab4 > 0)
+    US_LAUNCH(env, "dia_finish", 4.0 * ndiag * L, dia_finish_kernel, one_counter_grid(nslab4, 256), 256, (uint4 *)f->val, nslab4, ndiag * L, &flags->scalar[3]);
   if (!read_flags(env, flags, &h)) { free_formatted(env, f); return env.status; }
   if (flag_status(h) != US_OK) { free_formatted(env, f); return flag_status(h); }
   if (h.scalar[3] != na) { free_formatted(env, f); return US_ERR_DUPLICATE; }
@@ -542,9 +587,9 @@ static GroupCounts group_flags(Env &env, const us_coo &coo, int gkind, int pkind
   if (!env.ok()) return g;
   fill_u32(env, g.count, g.nbins, 0);
   if (coo.nnz > 0)
-    US_LAUNCH(env, "group_hist", 8.0 * coo.nnz, group_hist_kernel, ceil_div<int64_t>(coo.nnz, GH_TILE), GH_T, coo.row,
+    US_LAUNCH(env, "group_hist", 8.0 * coo.nnz, group_hist_kernel, one_counter_grid(coo.nnz, GH_TILE), GH_T, coo.row,
               coo.col, coo.nnz, gkind, (uint32_t)coo.nrows, (uint32_t)coo.ncols, g.count, flags);
-  US_LAUNCH(env, "group_flag", 8.0 * g.nbins, group_flag_kernel, ceil_div<int64_t>(g.nbins, 256), 256,
+  US_LAUNCH(env, "group_flag", 8.0 * g.nbins, group_flag_kernel, one_counter_grid(g.nbins, 256), 256,
             (const uint32_t *)g.count, g.nbins, gkind, pkind, num, den, thr, coo.nrows, coo.ncols, g.flag,
             &flags->scalar[1]);
   return g;
@@ -927,7 +972,7 @@ static us_status decompose_sum(Env &env, const us_coo &coo, const Plan &pa, cons
       if (n > 0)
         US_LAUNCH(env, "split", 24.0 * n, (split_kernel<false>), ceil_div<int64_t>(n, SP_TILE), SP_T, coo.row, coo.col,
                   coo.val, n, gkind, (uint32_t)coo.nrows, (const int32_t *)gmap, (int64_t)0, 0, (float *)nullptr,
-                  (uint8_t *)nullptr, la, lb, cursors);
+                  (uint8_t *)nullptr, la, lb, cursors, flags);
       st = env.status;
     }
     if (st == US_OK) {

@@ -326,7 +326,7 @@ __global__ __launch_bounds__(RS_T) void radix_scatter_kernel(PassArgs a) {
 // only its items move.  The pieces are then bundled, in order, into groups of at most LS_CAP
 // items that the same LDS kernel finishes (it sorts by all low bits, so a group may span
 // several pieces).  A bucket beyond LS_MAXTILES tiles, or a piece above LS_GROUP items, sets
-// Flags::sort_retry and the host sorts again with whole-array passes only.
+// Flags::retry and the host sorts again with whole-array passes only.
 constexpr int LS_T = 256, LS_IPT = 16, LS_CAP = LS_T * LS_IPT;   // 4096 items, 32 KB of LDS
 constexpr int LS_GROUP = LS_CAP / 2;     // pieces are bundled by the LS_GROUP-sized interval their start falls in
 constexpr int LS_MAXTILES = 64;          // split buckets hold at most 64 * 4096 items
@@ -388,10 +388,10 @@ __global__ __launch_bounds__(256) void big_list_kernel(LocalArgs a) {
   uint32_t first, size;
   if (b >= a.nbuckets || !bucket_range(a, b, &first, &size) || size <= (uint32_t)LS_CAP) return;
   const uint32_t ntiles = (size + RS_TILE - 1) / RS_TILE;
-  if (ntiles > (uint32_t)LS_MAXTILES) { a.flags->sort_retry = 1; return; }
+  if (ntiles > (uint32_t)LS_MAXTILES) { a.flags->retry = RETRY_SORT_LDS; return; }
   const uint32_t k = atomicAdd(&a.counters[0], 1u);
   const uint32_t tb = atomicAdd(&a.counters[1], ntiles);
-  if (k >= a.big_cap || tb + ntiles > a.tile_cap) { a.flags->sort_retry = 1; return; }   // overlapping garbage ranges only
+  if (k >= a.big_cap || tb + ntiles > a.tile_cap) { a.flags->retry = RETRY_SORT_LDS; return; }   // overlapping garbage ranges only
   a.big[k] = BigBucket{b, first, size, tb};
   for (uint32_t j = 0; j < ntiles; ++j) a.tilemap[tb + j] = k;
 }
@@ -428,7 +428,7 @@ __global__ __launch_bounds__(RS_BINS) void seg_scan_kernel(LocalArgs a) {
   uint32_t total;
   const uint32_t start = block_exclusive_sum<RS_BINS>(run, s_wave, &total);
   a.sdig[(size_t)k * RS_BINS + d] = start;
-  if (run > (uint32_t)LS_GROUP) a.flags->sort_retry = 1;
+  if (run > (uint32_t)LS_GROUP) a.flags->retry = RETRY_SORT_LDS;
   s_pos[d] = start;
   if (d == 0) s_pos[RS_BINS] = B.size;
   __syncthreads();
@@ -444,7 +444,7 @@ __global__ __launch_bounds__(RS_BINS) void seg_scan_kernel(LocalArgs a) {
   if (head) {
     const uint32_t g = s_base + rank, gsize = s_pos[rank + 1] - start;
     if (g < a.work_cap) a.work[g] = WorkItem{B.first + start, gsize, B.bucket};
-    else a.flags->sort_retry = 1;
+    else a.flags->retry = RETRY_SORT_LDS;
   }
 }
 

@@ -152,3 +152,34 @@ def test_dia_large_slab(ctx):
         B.us_decompose(ctx, m.nrows, m.ncols, dev(r), dev(c), dev(v), us_desc_of(O.DIA()), us_desc_of(O.DCSR()),
                        us_pred_of(pred))
     assert ei.value.code == "US_ERR_DUPLICATE", on_diag
+
+
+def test_dia_value_equal_to_the_empty_slot_pattern(ctx):
+    """The sort-free DIA path tells occupied slots from empty ones by a NaN fill pattern; an input value
+    that carries this very pattern makes the call fall back to its byte-map form: same arrays, bit for bit."""
+    from paper_2403_05802_amd import binding as B
+    from helpers import assert_same_layout, dev, us_desc_of, us_pred_of
+    rng = np.random.default_rng(21)
+    n = 3000
+    rows, cols = [], []
+    for off in (-5, 0, 2, 700):
+        i = np.arange(max(0, -off), min(n, n - off))
+        keep = rng.random(i.size) < 0.95
+        rows.append(i[keep]); cols.append(i[keep] + off)
+    r = np.concatenate(rows).astype(np.int32); c = np.concatenate(cols).astype(np.int32)
+    p = rng.permutation(r.size); r, c = r[p], c[p]
+    v = rng.uniform(0.1, 1, r.size).astype(np.float32)
+    v[17] = np.array([0x7FC5A5A5], dtype=np.uint32).view(np.float32)[0]
+    for desc in (O.DIA(), O.DIA_VARIANT()):
+        g = B.us_convert(ctx, n, n, dev(r), dev(c), dev(v), us_desc_of(desc))
+        assert_same_layout(g, O.convert(n, n, r, c, v, desc), "DIA with the pattern as a value")
+    pred = O.Predicate((O.diag(),), O.SUM_GE_FRAC_OF_CAPACITY, num=9, den=10)
+    oa, ob, _ = O.decompose(n, n, r, c, v, O.DIA(), O.CSR(), pred)
+    ga, gb = B.us_decompose(ctx, n, n, dev(r), dev(c), dev(v), us_desc_of(O.DIA()), us_desc_of(O.CSR()), us_pred_of(pred))
+    assert_same_layout(ga, oa, "A"); assert_same_layout(gb, ob, "B")
+    # and a duplicate is still a duplicate on both forms
+    r2 = np.append(r, r[3]); c2 = np.append(c, c[3])
+    for vv in (np.append(v, np.float32(2)), np.append(np.where(np.isnan(v), np.float32(1), v), np.float32(2))):
+        with pytest.raises(B.UnisparseError) as ei:
+            B.us_convert(ctx, n, n, dev(r2), dev(c2), dev(vv), us_desc_of(O.DIA()))
+        assert ei.value.code == "US_ERR_DUPLICATE"
