@@ -341,11 +341,31 @@ __global__ __launch_bounds__(256) void coo_spmm_fixup_kernel(const int32_t *carr
   if (r < 0) return;
   // only the first entry of the run of row r works (a run never skips an entry, see above)
   if (e > 0 && carry_row[e - 1] == r) return;
+  // length of the run, 64 entries per look (a 20,000-entry row leaves ~80 pieces: walking them one
+  // dependent load at a time made this kernel the tail of the whole product)
+  int64_t len = 0;
+  for (;;) {
+    const int64_t j = e + len + lane;
+    const uint64_t same = __ballot(j < nentries && carry_row[j] == r);
+    const int run = same == ~0ull ? 64 : __ffsll((unsigned long long)~same) - 1;
+    len += run;
+    if (run < 64) break;
+  }
   for (int q = lane; q < cbw; q += 64) {
     const int64_t c = (int64_t)blockIdx.y * cbw + q;
     if (c >= N) continue;
+    const float *p = carry + (e * ncb + blockIdx.y) * cbw + q;
+    const int64_t stride = ncb * cbw;
     float s = 0.f;
-    for (int64_t j = e; j < nentries && carry_row[j] == r; ++j) s += carry[(j * ncb + blockIdx.y) * cbw + q];
+    int64_t j = 0;
+    for (; j + 8 <= len; j += 8) {   // 8 independent loads in flight, added in piece order
+      float t[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) t[u] = p[(j + u) * stride];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += t[u];
+    }
+    for (; j < len; ++j) s += p[j * stride];
     Y[(int64_t)r * ldy + c] += s;
   }
 }
