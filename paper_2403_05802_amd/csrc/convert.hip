@@ -921,21 +921,24 @@ __global__ __launch_bounds__(256) void clipped_len_kernel(const int32_t *ptr, in
   if (g < n) { int64_t l = ptr[g + 1] - ptr[g]; out[g] = (int32_t)(l < K ? l : K); }
 }
 
-// stable split of the sorted list by rank-in-row: rank < K -> part A, else part B
+// stable split of the sorted list by rank-in-row: rank < K -> part A, else part B; on the way, equal
+// neighbours are flagged as duplicates if the sort has not looked for them (the two copies of a
+// coordinate may end up in different parts, so this is the last place that sees them side by side)
 __global__ __launch_bounds__(256) void rank_split_kernel(const int32_t *major, const int32_t *minor, const float *val,
                                                         const int32_t *ptr, const int32_t *ptr_a, int64_t n,
                                                         int64_t K, int32_t *ar, int32_t *ac, float *av, int32_t *br,
-                                                        int32_t *bc, float *bv) {
+                                                        int32_t *bc, float *bv, int check_dups, Flags *flags) {
   int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= n) return;
-  int32_t r = major[i];
+  const int32_t r = major[i], c = minor[i];
+  if (check_dups && i > 0 && major[i - 1] == r && minor[i - 1] == c) flags->duplicate = 1;
   int64_t rank = i - ptr[r];
   if (rank < K) {
     int64_t p = ptr_a[r] + rank;
-    ar[p] = r; ac[p] = minor[i]; av[p] = val[i];
+    ar[p] = r; ac[p] = c; av[p] = val[i];
   } else {
     int64_t p = (int64_t)(ptr[r] - ptr_a[r]) + (rank - K);
-    br[p] = r; bc[p] = minor[i]; bv[p] = val[i];
+    br[p] = r; bc[p] = c; bv[p] = val[i];
   }
 }
 
@@ -1002,9 +1005,6 @@ static us_status decompose_rank(Env &env, const us_coo &coo, const Plan &pa, con
   SortOut so{};
   so.major = major; so.minor = minor; so.val = val;
   const bool checked = sort_coo(env, coo.row, coo.col, coo.val, n, rowcol_keyspec(coo, false), so, flags);
-  if (!checked && n > 1)
-    US_LAUNCH(env, "check_unique", 8.0 * n, check_unique_unpacked_kernel, ceil_div<int64_t>(n, 256), 256,
-              (const int32_t *)major, (const int32_t *)minor, n, flags);
   lower_bound_ptr(env, major, n, nrows, ptr);
   Flags h{};
   int64_t K = pred.abs;
@@ -1035,17 +1035,21 @@ static us_status decompose_rank(Env &env, const us_coo &coo, const Plan &pa, con
   if (st == US_OK && n > 0) {
     US_LAUNCH(env, "rank_split", 16.0 * n + 12.0 * n, rank_split_kernel, ceil_div<int64_t>(n, 256), 256,
               (const int32_t *)major, (const int32_t *)minor, (const float *)val, (const int32_t *)ptr,
-              (const int32_t *)ptr_a, n, K, la.r, la.c, la.v, lb.r, lb.c, lb.v);
+              (const int32_t *)ptr_a, n, K, la.r, la.c, la.v, lb.r, lb.c, lb.v, checked ? 0 : 1, flags);
     st = env.status;
   }
   auto finish_part = [&](const Plan &p, const us_format_desc &d, CooLists &l, int64_t cnt, us_formatted **o) {
     if (row_major_family(p)) {   // the list is already in (row, col) order: no second sort
-      Flags *fl = new_flags(env);
+      // the same flag block goes on (its duplicate flag may have been set by the split); sizes start from zero
+      fill_u32(env, (uint32_t *)&flags->scalar[0], 4, 0u);
       if (!env.ok()) return env.status;
-      us_status s = build_from_sorted(env, p, d, coo.nrows, coo.ncols, cnt, l.r, l.c, l.v, fl, false, o);
+      us_status s = build_from_sorted(env, p, d, coo.nrows, coo.ncols, cnt, l.r, l.c, l.v, flags, false, o);
       l = CooLists();  // ownership moved
       return s;
     }
+    Flags hh{};
+    if (!read_flags(env, flags, &hh)) return env.status;
+    if (flag_status(hh) != US_OK) return flag_status(hh);
     us_coo c{coo.nrows, coo.ncols, cnt, l.r, l.c, l.v};
     return convert_with_plan(env, c, p, d, o);
   };

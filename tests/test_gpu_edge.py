@@ -183,3 +183,23 @@ def test_dia_value_equal_to_the_empty_slot_pattern(ctx):
         with pytest.raises(B.UnisparseError) as ei:
             B.us_convert(ctx, n, n, dev(r2), dev(c2), dev(vv), us_desc_of(O.DIA()))
         assert ei.value.code == "US_ERR_DUPLICATE"
+
+
+def test_duplicate_cut_in_two_by_a_rank_split(ctx):
+    """The two copies of a coordinate get ranks K-1 and K: each part alone looks clean."""
+    from paper_2403_05802_amd import binding as B
+    from helpers import dev, us_desc_of, us_pred_of
+    rng = np.random.default_rng(5)
+    n = 500
+    lin = rng.choice(n * n, 4000, replace=False)
+    r, c = (lin // n).astype(np.int32), (lin % n).astype(np.int32)
+    keep = r != 5
+    r = np.concatenate([r[keep], np.array([5, 5, 5, 5], np.int32)])
+    c = np.concatenate([c[keep], np.array([1, 2, 3, 3], np.int32)])
+    p = rng.permutation(r.size); r, c = r[p], c[p]
+    v = rng.uniform(0.1, 1, r.size).astype(np.float32)
+    pred = us_pred_of(O.Predicate((O.d0(),), O.RANK_LT_ABS, abs=3))
+    for da, db in ((O.ELL(), O.COO()), (O.CSR(), O.DCSR()), (O.BCSR(4), O.CSC()), (O.COO(), O.BDIA(3))):
+        with pytest.raises(B.UnisparseError) as ei:
+            B.us_decompose(ctx, n, n, dev(r), dev(c), dev(v), us_desc_of(da), us_desc_of(db), pred)
+        assert ei.value.code == "US_ERR_DUPLICATE", (da, db)
