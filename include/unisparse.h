@@ -129,13 +129,15 @@ us_status us_convert(const us_ctx *ctx, const us_coo *coo, const us_format_desc 
 us_status us_convert_formatted(const us_ctx *ctx, const us_formatted *src, const us_format_desc *target,
                                us_formatted **out);
 
-/* Option, process-wide, default off: the Sort step (Figure 8) runs its whole-array digit passes
- * over the top key bits only and finishes every bucket of equal top bits inside LDS.  Pays off when
- * entries spread evenly over the rows (block rows, ...): 29 % faster COO->BCSR on a 50 M-entry FEM-like
- * matrix; heavy rows of a power-law matrix need extra splitting passes and gain nothing.  Results are
- * identical either way; an input the finish cannot take (more than 262,144 entries sharing their top
- * key bits, or 2,048 sharing 8 more) is sorted again with whole-array passes by the same call. */
-us_status us_set_sort_lds_finish(int32_t enabled);
+/* Option, process-wide: how the Sort step (Figure 8) finishes.  mode 1: whole-array digit passes run over
+ * the top key bits only and every bucket of equal top bits is finished inside LDS; mode 0: whole-array
+ * passes over all bits; mode -1 (default): the first for blocked target tuples (BCSR, BDIA and the blocked
+ * #sum queries), the second for (row, col) tuples.  The finish pays off when entries spread evenly over the
+ * buckets (block rows of a FEM-like matrix: COO->BCSR of 50 M entries 27 % faster); heavy rows of a power-law
+ * matrix need extra splitting passes and gain nothing.  Results are identical in every mode; an input the
+ * finish cannot take (more than 262,144 entries sharing their top key bits, or 2,048 sharing 8 more) is
+ * sorted again with whole-array passes by the same call. */
+us_status us_set_sort_lds_finish(int32_t mode);
 
 /* decompose + convert of a hybrid (Figure 3c lines "decompose" and "convert"): entries that
  * satisfy `pred` form part A (stored as desc_a), the rest part B (desc_b).  Both parts keep

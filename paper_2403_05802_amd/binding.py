@@ -239,8 +239,9 @@ def make_predicate(group, kind: int, num: int = 0, den: int = 1, abs_: int = 0) 
     return p
 
 
-def us_set_sort_lds_finish(enabled: bool) -> None:
-    _check(lib().us_set_sort_lds_finish(1 if enabled else 0), "us_set_sort_lds_finish")
+def us_set_sort_lds_finish(mode) -> None:
+    """True / False, or None for the default (chosen by the key layout)."""
+    _check(lib().us_set_sort_lds_finish(-1 if mode is None else (1 if mode else 0)), "us_set_sort_lds_finish")
 
 
 # ----------------------------------------------------------------------------- formatted tensor

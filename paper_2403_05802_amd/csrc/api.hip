@@ -70,7 +70,7 @@ us_status us_convert(const us_ctx *ctx, const us_coo *coo, const us_format_desc 
   if (!ctx || !coo || !target || !out) return US_ERR_NULL;
   us_status s;
   { Env env(ctx); s = convert_impl(env, *coo, *target, out); }
-  if (s == US_SORT_RETRY) { Env env(ctx); env.lds_finish = false; env.dia_marks = true; s = convert_impl(env, *coo, *target, out); }
+  if (s == US_SORT_RETRY) { Env env(ctx); env.lds_finish = 0; env.dia_marks = true; s = convert_impl(env, *coo, *target, out); }
   return s;
 }
 
@@ -80,7 +80,7 @@ us_status us_convert_formatted(const us_ctx *ctx, const us_formatted *src, const
   if (!ctx || !src || !target || !out) return US_ERR_NULL;
   us_status s;
   { Env env(ctx); s = convert_formatted_impl(env, *src, *target, out); }
-  if (s == US_SORT_RETRY) { Env env(ctx); env.lds_finish = false; env.dia_marks = true; s = convert_formatted_impl(env, *src, *target, out); }
+  if (s == US_SORT_RETRY) { Env env(ctx); env.lds_finish = 0; env.dia_marks = true; s = convert_formatted_impl(env, *src, *target, out); }
   return s;
 }
 
@@ -93,14 +93,14 @@ us_status us_decompose(const us_ctx *ctx, const us_coo *coo, const us_format_des
   us_status s;
   { Env env(ctx); s = decompose_impl(env, *coo, *desc_a, *desc_b, *pred, out_a, out_b); }
   if (s == US_SORT_RETRY) {
-    Env env(ctx); env.lds_finish = false; env.dia_marks = true;
+    Env env(ctx); env.lds_finish = 0; env.dia_marks = true;
     s = decompose_impl(env, *coo, *desc_a, *desc_b, *pred, out_a, out_b);
   }
   return s;
 }
 
-us_status us_set_sort_lds_finish(int32_t enabled) {
-  us::g_lds_finish = enabled != 0;
+us_status us_set_sort_lds_finish(int32_t mode) {
+  us::g_lds_finish = mode < 0 ? -1 : (mode != 0 ? 1 : 0);
   return US_OK;
 }
 

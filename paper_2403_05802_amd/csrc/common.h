@@ -35,14 +35,15 @@ struct Profile {
 };
 
 // ------------------------------------------------------------------ per-call environment
-extern bool g_lds_finish;   // process-wide default of Env::lds_finish (us_set_sort_lds_finish)
+extern int g_lds_finish;    // process-wide default of Env::lds_finish (us_set_sort_lds_finish)
 struct Env {
   const us_ctx *ctx;
   hipStream_t stream;
   Profile *prof;
   us_status status = US_OK;
   std::vector<void *> temps;  // temporaries, released by release_temps() after the stream is idle
-  bool lds_finish;            // sort: finish buckets inside LDS (cleared for the retry after Flags::retry)
+  int lds_finish;             // sort: finish buckets inside LDS: 1 always, 0 never (also the retry after Flags::retry),
+                              // -1 by key layout (blocked tuples yes, (row, col) tuples no)
   bool dia_marks = false;     // DIA slab: find occupied slots with a byte map instead of the fill pattern (set for the retry)
 
   explicit Env(const us_ctx *c)

@@ -17,7 +17,7 @@ void Env::free_raw(void *p) {
   if (ctx && ctx->alloc) { if (ctx->free) ctx->free(p, ctx->user); }
   else (void)hipFree(p);
 }
-bool g_lds_finish = false;
+int g_lds_finish = -1;
 
 void Env::release_temps() {
   if (temps.empty()) return;

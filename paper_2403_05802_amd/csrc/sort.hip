@@ -631,7 +631,10 @@ static bool sort_generic(Env &env, int in_mode, const int32_t *row, const int32_
   // bits for buckets of 1024..2048 items on average, and at most 32 bits left over.
   int high_bits = total_bits, low_bits = 0;
   bool finish_local = false;
-  if (env.lds_finish && in_mode == IN_COO && final_mode != OUT_KEY32 && nnz >= 4096) {
+  // by default for blocked tuples only: block rows of FEM-like matrices fill evenly, while the rows of a
+  // power-law graph do not (a heavy row's bucket needs extra splitting levels and the finish loses)
+  const bool want_finish = env.lds_finish > 0 || (env.lds_finish < 0 && ks.mode != 0);
+  if (want_finish && in_mode == IN_COO && final_mode != OUT_KEY32 && nnz >= 4096) {
     const int want = bits_for((uint64_t)(nnz - 1) / 2048);
     high_bits = want < total_bits ? want : total_bits;
     if (total_bits - high_bits > 32) high_bits = total_bits - 32;

@@ -25,7 +25,7 @@ def lds_finish():
     try:
         yield
     finally:
-        B.us_set_sort_lds_finish(False)
+        B.us_set_sort_lds_finish(None)
 
 
 def distinct(nr, nc, r, c):
