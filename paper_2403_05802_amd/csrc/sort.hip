@@ -327,6 +327,9 @@ __global__ __launch_bounds__(RS_T) void radix_scatter_kernel(PassArgs a) {
 // items that the same LDS kernel finishes (it sorts by all low bits, so a group may span
 // several pieces).  A bucket beyond LS_MAXTILES tiles, or a piece above LS_GROUP items, sets
 // Flags::retry and the host sorts again with whole-array passes only.
+// (Replacing the digit passes inside LDS by one 8-bit split plus counting smaller keys inside each piece
+// was tried: the keys of a blocked layout cluster -- block columns inside a band, 16 entries per block --
+// so pieces come out uneven whichever bits are taken, the count goes quadratic, and it lost.)
 constexpr int LS_T = 256, LS_IPT = 16, LS_CAP = LS_T * LS_IPT;   // 4096 items, 32 KB of LDS
 constexpr int LS_GROUP = LS_CAP / 2;     // pieces are bundled by the LS_GROUP-sized interval their start falls in
 constexpr int LS_MAXTILES = 64;          // split buckets hold at most 64 * 4096 items
