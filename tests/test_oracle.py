@@ -330,3 +330,51 @@ def test_decompose_ell_coo_brute_force(seed):
     assert m2.sum() == np.minimum(lens, 2).sum()
     m3 = O.predicate_mask(nr, nc, r, c, O.Predicate((O.d0(),), O.SUM_GE_ABS, abs=10))
     assert np.array_equal(m3, lens[r] >= 10)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_decompose_blocked_groups_brute_force(seed):
+    """#sum over (d0/b, d1-d0) (the BDIA/CSR program of Figure 3c) and over blocks (d0/bh, d1/bw) (the per-block
+    threshold of the BELL/COO case study): per-entry group counts recomputed with plain loops; BDIA slots
+    addressed as Figure 9 does (val[node*b + d0%b], d0 = e0*b + e2, d1 = e1 + d0)."""
+    rng = np.random.default_rng(70 + seed)
+    nr, nc = 29, 31
+    r, c, v = random_coo(rng, nr, nc, 260)
+    b = [2, 3, 4, 5][seed]
+    thld = [2, 3, 2, 4][seed]
+    pred = O.Predicate((O.div(0, b), O.diag()), O.SUM_GE_ABS, abs=thld)
+    pa, pb, m = O.decompose(nr, nc, r, c, v, O.BDIA(b), O.CSR(), pred)
+    for t in range(r.size):
+        cnt = sum(1 for u in range(r.size) if r[u] // b == r[t] // b and c[u] - r[u] == c[t] - r[t])
+        assert bool(m[t]) == (cnt >= thld)
+    A = dense_of(nr, nc, r, c, v).astype(np.float32).astype(np.float64)
+    assert np.array_equal(O.to_dense(pa) + O.to_dense(pb), A)
+    # walk the BDIA arrays by hand
+    size0, ptr, idx, size2 = pa.levels[0].size, pa.levels[1].ptr, pa.levels[1].idx, pa.levels[2].size
+    assert size0 == -(-nr // b) and size2 == b and ptr[0] == 0 and ptr[-1] == idx.size and pa.val.size == idx.size * b
+    D = np.zeros((nr, nc))
+    for e0 in range(size0):
+        offs = idx[ptr[e0]:ptr[e0 + 1]]
+        assert np.all(np.diff(offs) > 0)                      # diagonals of a block row ascend, no repeats
+        for node in range(ptr[e0], ptr[e0 + 1]):
+            seen = 0
+            for e2 in range(b):
+                d0 = e0 * b + e2
+                d1 = int(idx[node]) + d0
+                x = pa.val[node * b + e2]
+                if 0 <= d0 < nr and 0 <= d1 < nc:
+                    D[d0, d1] = x
+                    seen += x != 0
+                else:
+                    assert x == 0                              # slots outside the matrix are padding
+            assert seen >= thld                                # only groups that met the threshold are stored
+    assert np.array_equal(D, O.to_dense(pa))
+    # blocks
+    bh, bw = [2, 3, 4, 2][seed], [2, 2, 4, 5][seed]
+    pred = O.Predicate((O.div(0, bh), O.div(1, bw)), O.SUM_GE_ABS, abs=thld)
+    qa, qb, m = O.decompose(nr, nc, r, c, v, O.BCSR(bh, bw), O.COO(), pred)
+    for t in range(r.size):
+        cnt = sum(1 for u in range(r.size) if r[u] // bh == r[t] // bh and c[u] // bw == c[t] // bw)
+        assert bool(m[t]) == (cnt >= thld)
+    assert np.array_equal(O.to_dense(qa) + O.to_dense(qb), A)
+    assert qa.val.size % (bh * bw) == 0 and qa.nnz + qb.nnz == r.size
