@@ -155,6 +155,14 @@ def test_cfg2_full(ctx):
     assert torch.equal(g2.ptr(1), g.ptr(1)) and torch.equal(g2.idx(1), g.idx(1)) and torch.equal(g2.val(), g.val())
     y2 = check_spmv(ctx, [g2], m, x)
     assert torch.equal(y1.view(torch.int32), y2.view(torch.int32))
+    # the other Sort path at full size: forced in-LDS finish (its heavy rows end in the fall-back) gives the same bytes
+    B.us_set_sort_lds_finish(True)
+    try:
+        g3 = B.us_convert(ctx, m.nrows, m.ncols, *d, us_desc_of(O.CSR()))
+    finally:
+        B.us_set_sort_lds_finish(None)
+    assert torch.equal(g3.ptr(1), g.ptr(1)) and torch.equal(g3.idx(1), g.idx(1))
+    assert torch.equal(g3.val().view(torch.int32), g.val().view(torch.int32))
 
 
 def test_cfg3_full(ctx):
@@ -188,6 +196,15 @@ def test_cfg4_full(ctx):
     assert np.array_equal(o.levels[1].ptr, 24 * np.arange(nbr + 1))    # closed form: 24 blocks per block row
     assert o.val.shape[0] == m.nnz and np.count_nonzero(o.val) == m.nnz  # blocks are dense: no padding
     assert_same_layout(g, o, "cfg4 BCSR")
+    # the other Sort path at full size (blocked tuples finish inside LDS by default): whole-array passes only
+    B.us_set_sort_lds_finish(False)
+    try:
+        g2 = B.us_convert(ctx, m.nrows, m.ncols, *coo_to_dev(m), us_desc_of(O.BCSR(4)))
+    finally:
+        B.us_set_sort_lds_finish(None)
+    assert torch.equal(g2.ptr(1), g.ptr(1)) and torch.equal(g2.idx(1), g.idx(1))
+    assert torch.equal(g2.val().view(torch.int32), g.val().view(torch.int32))
+    g2.free()
     X = W.dense_operand(4, (m.ncols, 64))
     rows = np.random.default_rng(1).choice(m.nrows, 3000, replace=False)
     check_spmm_rows(ctx, [g], m, X, np.sort(rows))
