@@ -79,7 +79,9 @@ typedef struct us_expr {
  *   DIA  (d1-d0,d0) merge(0) trim(0,0)  DIA variant (d1-d0,d1)
  *   BCSR (d0/bh,d1/bw,d0%bh,d1%bw) merge(0,1) trim(1,1), 1 <= bh,bw <= 16
  *   ELL  (indirect(d1),d0,d1) merge(0) trim(0,0)
- *   BDIA (d0/b,d1-d0,d0%b) merge(0) trim(1,1), 1 <= b <= 16 (the blocked DIA of Figure 3c)  */
+ *   BDIA (d0/b,d1-d0,d0%b) merge(0) trim(1,1), 1 <= b <= 16 (the blocked DIA of Figure 3c)
+ *   CSB  (d0/bh,d1/bw,d0%bh,d1%bw) merge(1) trim(2,3), 1 <= bh,bw <= 65536 and fewer than 2^31 blocks:
+ *        a dense grid of blocks (two sizes), one ptr over the blocks, (d0%bh, d1%bw) per entry        */
 typedef struct us_format_desc {
   int32_t nlevels;
   us_expr level[4];
@@ -88,9 +90,9 @@ typedef struct us_format_desc {
   int64_t ell_width;      /* ELL only: 0 = longest row, >0 = fixed number of slots */
 } us_format_desc;
 
-enum { US_F_COO = 0, US_F_CSR, US_F_DCSR, US_F_CSC, US_F_DCSC, US_F_DIA, US_F_DIA_VARIANT, US_F_BCSR, US_F_ELL, US_F_BDIA };
+enum { US_F_COO = 0, US_F_CSR, US_F_DCSR, US_F_CSC, US_F_DCSC, US_F_DIA, US_F_DIA_VARIANT, US_F_BCSR, US_F_ELL, US_F_BDIA, US_F_CSB };
 /* Fill *out with the encoding of Figure 7 (Figure 3c for BDIA) for `format`; b0,b1 = block
- * height,width (BCSR), b0 = block height (BDIA) or b0 = fixed width (ELL, 0 = longest row).  host pointers. */
+ * height,width (BCSR, CSB), b0 = block height (BDIA) or b0 = fixed width (ELL, 0 = longest row).  host pointers. */
 us_status us_desc_preset(int32_t format, int64_t b0, int64_t b1, us_format_desc *out);
 
 /* Decomposition predicate: the `sum` query of Section 4.1.2 (groupBy map, stored entry -> 1)

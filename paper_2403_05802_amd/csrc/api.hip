@@ -47,6 +47,13 @@ us_status us_desc_preset(int32_t format, int64_t b0, int64_t b1, us_format_desc 
       d.level[2] = mk(US_E_MOD, 1, 0, (int)b0); d.level[3] = mk(US_E_MOD, 0, 1, (int)b1);
       d.trim_s = 1; d.trim_e = 1; d.merge_mask = 3;
       break;
+    case US_F_CSB:
+      if (b0 < 1 || b1 < 1 || b0 > 65536 || b1 > 65536) return US_ERR_UNSUPPORTED_DESC;
+      d.nlevels = 4;
+      d.level[0] = mk(US_E_DIV, 1, 0, (int)b0); d.level[1] = mk(US_E_DIV, 0, 1, (int)b1);
+      d.level[2] = mk(US_E_MOD, 1, 0, (int)b0); d.level[3] = mk(US_E_MOD, 0, 1, (int)b1);
+      d.trim_s = 2; d.trim_e = 3; d.merge_mask = 2;
+      break;
     case US_F_BDIA:
       if (b0 < 1 || b0 > 16) return US_ERR_UNSUPPORTED_DESC;
       d.nlevels = 3;

@@ -91,7 +91,7 @@ struct LaunchScope {  // brackets one kernel launch with events when profiling i
   } while (0)
 
 // ------------------------------------------------------------------ formatted tensor
-enum Pattern { P_COO = 0, P_CSR, P_DCSR, P_DIA, P_BCSR, P_ELL, P_BDIA };
+enum Pattern { P_COO = 0, P_CSR, P_DCSR, P_DIA, P_BCSR, P_ELL, P_BDIA, P_CSB };
 
 struct LevelStore {
   int64_t size = -1;      // extent of a dense level, -1 if none
@@ -111,7 +111,8 @@ struct us_formatted {
   float *val = nullptr; int64_t nval = 0;
   // derived sizes
   int64_t nmajor = 0;   // CSR: rows (cols if swapped); DCSR: stored rows; DIA: ndiag; BCSR/BDIA: block rows; ELL: K
-  int64_t bh = 1, bw = 1, nblk = 0;   // BDIA: bh = block height, bw = 1, nblk = (block row, diagonal) nodes
+  int64_t bh = 1, bw = 1, nblk = 0;   // BDIA: bh = block height, bw = 1, nblk = (block row, diagonal) nodes;
+                                      // CSB: nblk = nmajor = blocks of the dense grid, level[1].size = blocks per block row
   // CSR / DCSR: where every SpMV tile starts on the merge path of row ends and non-zeros
   // (rows consumed before step t * tile), computed once at conversion
   int32_t *mp_split = nullptr; int64_t mp_tiles = 0;

@@ -20,8 +20,8 @@ struct Plan {
 static bool aff(const us_expr &e, int c0, int c1) {
   return e.kind == US_E_AFFINE && e.c0 == c0 && e.c1 == c1 && e.c == 0;
 }
-static bool tile(const us_expr &e, int kind, int dim, int64_t *f) {
-  if (e.kind != kind || e.c != 0 || e.factor < 1 || e.factor > 16) return false;
+static bool tile(const us_expr &e, int kind, int dim, int64_t *f, int64_t max_factor = 16) {
+  if (e.kind != kind || e.c != 0 || e.factor < 1 || e.factor > max_factor) return false;
   if (!(e.c0 == (dim == 0) && e.c1 == (dim == 1))) return false;
   *f = e.factor;
   return true;
@@ -52,6 +52,12 @@ static bool match_desc(const us_format_desc &d, Plan *p) {
         tile(d.level[2], US_E_MOD, 0, &f2) && tile(d.level[3], US_E_MOD, 1, &f3) && f0 == f2 && f1 == f3 &&
         S == 1 && E == 1 && (m == 3 || m == 2)) {
       p->pattern = P_BCSR; p->bh = f0; p->bw = f1;
+      return true;
+    }
+    if (tile(d.level[0], US_E_DIV, 0, &f0, 65536) && tile(d.level[1], US_E_DIV, 1, &f1, 65536) &&
+        tile(d.level[2], US_E_MOD, 0, &f2, 65536) && tile(d.level[3], US_E_MOD, 1, &f3, 65536) && f0 == f2 &&
+        f1 == f3 && S == 2 && E == 3 && m == 2) {
+      p->pattern = P_CSB; p->bh = f0; p->bw = f1;
       return true;
     }
     return false;
@@ -750,6 +756,54 @@ static us_status convert_blocked(Env &env, const us_coo &coo, const Plan &plan, 
   return emit_blocked(env, plan, desc, coo.nrows, coo.ncols, ks, skey, sval, n, flags, out);
 }
 
+// CSB (Section 2.1: a dense collection of blocks stored compressed): the entries in BCSR tuple order, a ptr
+// over all blocks of the dense grid, and the two in-block indices of every entry.
+__global__ __launch_bounds__(256) void csb_unpack_kernel(const uint64_t *key, int64_t n, KeySpec ks, int64_t nbc,
+                                                        int32_t *blk, int32_t *in_row, int32_t *in_col, Flags *flags) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const uint64_t k = key[i];
+  if (i > 0 && key[i - 1] == k) flags->duplicate = 1;
+  const uint64_t bk = k >> (ks.ih_bits + ks.iw_bits);
+  blk[i] = (int32_t)((int64_t)(bk >> ks.b_bits) * nbc + (int64_t)(bk & ((1ull << ks.b_bits) - 1)));
+  in_row[i] = (int32_t)((k >> ks.iw_bits) & ((1ull << ks.ih_bits) - 1));
+  in_col[i] = (int32_t)(k & ((1ull << ks.iw_bits) - 1));
+}
+
+static us_status convert_csb(Env &env, const us_coo &coo, const Plan &plan, const us_format_desc &desc, Flags *flags,
+                             us_formatted **out) {
+  const int64_t n = coo.nnz;
+  const int64_t nbr = ceil_div<int64_t>(coo.nrows, plan.bh), nbc = ceil_div<int64_t>(coo.ncols, plan.bw);
+  if (nbr * nbc + 1 >= (1ll << 31)) return US_ERR_OVERFLOW;
+  Plan pk = plan; pk.pattern = P_BCSR;   // same target tuple as BCSR
+  const KeySpec ks = blocked_keyspec(pk, coo.nrows, coo.ncols);
+  uint64_t *skey = env.temp<uint64_t>(n);
+  int32_t *blk = env.temp<int32_t>(n);
+  us_formatted *f = new us_formatted();
+  f->desc = desc; f->pattern = P_CSB;
+  f->nrows = coo.nrows; f->ncols = coo.ncols; f->nnz = n;
+  f->nlevels = 4;
+  f->level[0].size = nbr; f->level[1].size = nbc;
+  f->level[2].ptr = env.owned<int32_t>(nbr * nbc + 1); f->level[2].nptr = nbr * nbc + 1;
+  f->level[2].idx = env.owned<int32_t>(n); f->level[2].nidx = n;
+  f->level[3].idx = env.owned<int32_t>(n); f->level[3].nidx = n;
+  f->val = env.owned<float>(n); f->nval = n;
+  f->nmajor = nbr * nbc; f->bh = plan.bh; f->bw = plan.bw; f->nblk = nbr * nbc;
+  if (!env.ok()) { free_formatted(env, f); return env.status; }
+  SortOut so{};
+  so.key64 = skey; so.val = f->val;
+  sort_coo(env, coo.row, coo.col, coo.val, n, ks, so, flags);
+  if (n > 0)
+    US_LAUNCH(env, "csb_unpack", 20.0 * n, csb_unpack_kernel, ceil_div<int64_t>(n, 256), 256, (const uint64_t *)skey, n, ks,
+              nbc, blk, f->level[2].idx, f->level[3].idx, flags);
+  lower_bound_ptr(env, blk, n, nbr * nbc, f->level[2].ptr);
+  Flags h{};
+  if (!read_flags(env, flags, &h)) { free_formatted(env, f); return env.status; }
+  if (flag_status(h) != US_OK) { free_formatted(env, f); return flag_status(h); }
+  *out = f;
+  return US_OK;
+}
+
 // ------------------------------------------------------------------ convert
 static us_status validate_coo(const us_coo &coo) {
   if (coo.nrows <= 0 || coo.ncols <= 0 || coo.nnz < 0) return US_ERR_SHAPE;
@@ -770,6 +824,7 @@ static us_status convert_with_plan(Env &env, const us_coo &coo, const Plan &plan
   if (!env.ok()) return env.status;
   if (plan.pattern == P_DIA) return convert_dia(env, coo, plan, desc, flags, out);
   if (plan.pattern == P_BCSR || plan.pattern == P_BDIA) return convert_blocked(env, coo, plan, desc, flags, out);
+  if (plan.pattern == P_CSB) return convert_csb(env, coo, plan, desc, flags, out);
   // COO / CSR / DCSR / ELL: sort by (major, minor), then build
   const int64_t n = coo.nnz;
   int32_t *major = env.owned<int32_t>(n), *minor = env.owned<int32_t>(n);
@@ -829,6 +884,11 @@ __device__ __forceinline__ bool slot_entry(const SrcView &v, int64_t s, int32_t 
       *r = (int32_t)row; *c = (int32_t)col; *x = val;
       return true;
     }
+    case P_CSB: {    // TileUnion: d0 = e0*bh + e2, d1 = e1*bw + e3 with (e0, e1) = block id / and % blocks per block row
+      const int64_t blk = parent_of(v.ptr, v.nmajor, s), nbc = (v.ncols + v.bw - 1) / v.bw;
+      a = (blk / nbc) * v.bh + v.idx0[s]; b = (blk % nbc) * v.bw + v.idx[s];
+      break;
+    }
     case P_BDIA: {   // inverse map of Figure 9: d0 = e0*b + e2, d1 = e1 + d0
       const int64_t node = s / v.bh, ri = s - node * v.bh;
       const int64_t row = parent_of(v.ptr, v.nmajor, node) * v.bh + ri, col = row + v.idx[node];
@@ -880,6 +940,7 @@ us_status convert_formatted_impl(Env &env, const us_formatted &src, const us_for
     case P_BCSR:
     case P_BDIA: v.ptr = src.level[1].ptr; v.idx = src.level[1].idx; break;
     case P_ELL: v.idx = src.level[2].idx; break;
+    case P_CSB: v.ptr = src.level[2].ptr; v.idx0 = src.level[2].idx; v.idx = src.level[3].idx; break;
     default: return US_ERR_FORMAT_MISMATCH;
   }
   const int64_t ns = v.nslots;

@@ -383,6 +383,20 @@ __global__ __launch_bounds__(256) void csc_spmm_atomic_kernel(const int32_t *ptr
   for (int e = ptr[j]; e < ptr[j + 1]; ++e) atomicAdd(&Y[(int64_t)idx[e] * ldy + cc], val[e] * xv);
 }
 
+// CSB: one wavefront per (entry, 64 columns of X), block found in ptr, fp32 atomics into Y
+__global__ __launch_bounds__(256) void csb_spmm_atomic_kernel(const int32_t *ptr, const int32_t *in_row,
+                                                             const int32_t *in_col, const float *val, int64_t n,
+                                                             int64_t nblocks, int64_t nbc, int64_t bh, int64_t bw,
+                                                             const float *X, int64_t N, int64_t ldx, float *Y, int64_t ldy) {
+  const int64_t e = (int64_t)blockIdx.x * 4 + wave_id();
+  if (e >= n) return;
+  const int64_t cc = (int64_t)blockIdx.y * 64 + lane_id();
+  if (cc >= N) return;
+  const int64_t blk = parent_of(ptr, nblocks, e);
+  const int64_t row = (blk / nbc) * bh + in_row[e], col = (blk % nbc) * bw + in_col[e];
+  atomicAdd(&Y[row * ldy + cc], val[e] * X[col * ldx + cc]);
+}
+
 // scatter form for the column-major COO
 __global__ __launch_bounds__(256) void coo_spmm_atomic_kernel(const int32_t *r, const int32_t *c, const float *val,
                                                              int64_t nnz, const float *X, int64_t N, int64_t ldx,
@@ -499,6 +513,17 @@ us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, 
         hipLaunchKernelGGL(dia_spmm_kernel, dim3((unsigned)ceil_div<int64_t>(A.nrows, 4), (unsigned)ncb), dim3(256), 0,
                            env.stream, (const int32_t *)A.level[0].idx, (const float *)A.val, A.nmajor, A.nrows, A.ncols,
                            A.swapped ? 1 : 0, X, N, ldx, Y, ldy, acc);
+        env.check(hipGetLastError());
+      }
+      return env.status;
+    case P_CSB:
+      if (!accumulate) zero_rows(env, Y, A.nrows, N, ldy);
+      if (env.ok() && A.nnz > 0) {
+        LaunchScope ls(env, "spmm_csb_atomic", 12.0 * A.nnz + xy);
+        hipLaunchKernelGGL(csb_spmm_atomic_kernel, dim3((unsigned)ceil_div<int64_t>(A.nnz, 4), (unsigned)ncb), dim3(256),
+                           0, env.stream, (const int32_t *)A.level[2].ptr, (const int32_t *)A.level[2].idx,
+                           (const int32_t *)A.level[3].idx, (const float *)A.val, A.nnz, A.nmajor, A.level[1].size, A.bh,
+                           A.bw, X, N, ldx, Y, ldy);
         env.check(hipGetLastError());
       }
       return env.status;

@@ -264,6 +264,19 @@ __global__ __launch_bounds__(256) void bdia_spmv_kernel(const int32_t *ptr, cons
   y[i] = s;
 }
 
+// CSB: one thread per entry; its block (hence its row and column origin) is found in ptr.  Entries of a
+// block row interleave rows, so sums go through fp32 atomics (like the column-major layouts).
+__global__ __launch_bounds__(256) void csb_spmv_atomic_kernel(const int32_t *ptr, const int32_t *in_row,
+                                                             const int32_t *in_col, const float *val, int64_t n,
+                                                             int64_t nblocks, int64_t nbc, int64_t bh, int64_t bw,
+                                                             const float *x, float *y) {
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (e >= n) return;
+  const int64_t blk = parent_of(ptr, nblocks, e);
+  const int64_t row = (blk / nbc) * bh + in_row[e], col = (blk % nbc) * bw + in_col[e];
+  atomicAdd(&y[row], val[e] * x[col]);
+}
+
 void spmv_prepare(Env &env, us_formatted *f) {
   if (f->swapped || (f->pattern != P_CSR && f->pattern != P_DCSR)) return;
   const int64_t total = f->nmajor + f->nnz;
@@ -308,6 +321,13 @@ us_status spmv_impl(Env &env, const us_formatted &A, const float *x, float *y, b
       US_LAUNCH(env, "spmv_bcsr", 4.0 * A.nval + 4.0 * A.nblk + 8.0 * A.nrows, bcsr_spmv_kernel,
                 ceil_div<int64_t>(A.nmajor, 4), 256, (const int32_t *)A.level[1].ptr, (const int32_t *)A.level[1].idx,
                 (const float *)A.val, A.nmajor, (int)A.bh, (int)A.bw, A.nrows, A.ncols, x, y, accumulate ? 1 : 0);
+      return env.status;
+    case P_CSB:
+      if (!accumulate) fill_u32(env, (uint32_t *)y, A.nrows, 0u);
+      if (A.nnz > 0)
+        US_LAUNCH(env, "spmv_csb_atomic", 20.0 * A.nnz, csb_spmv_atomic_kernel, ceil_div<int64_t>(A.nnz, 256), 256,
+                  (const int32_t *)A.level[2].ptr, (const int32_t *)A.level[2].idx, (const int32_t *)A.level[3].idx,
+                  (const float *)A.val, A.nnz, A.nmajor, A.level[1].size, A.bh, A.bw, x, y);
       return env.status;
     case P_BDIA:
       US_LAUNCH(env, "spmv_bdia", 4.0 * A.nval + 4.0 * A.nblk + 8.0 * A.nrows + 4.0 * A.ncols, bdia_spmv_kernel,

@@ -44,6 +44,8 @@ def test_status_strings_and_presets_need_no_gpu():
     assert b.nlevels == 3 and b.merge_mask == 1 and (b.trim_s, b.trim_e) == (1, 1)
     assert [(b.level[i].kind, b.level[i].c0, b.level[i].c1, b.level[i].factor) for i in range(3)] == \
         [(B.US_E_DIV, 1, 0, 3), (B.US_E_AFFINE, -1, 1, b.level[1].factor), (B.US_E_MOD, 1, 0, 3)]
+    k = B.us_desc_preset(B.US_F_CSB, 512, 256)        # same map as BCSR, merge(1), trim(2,3)
+    assert k.nlevels == 4 and k.merge_mask == 2 and (k.trim_s, k.trim_e) == (2, 3) and k.level[3].factor == 256
     import pytest
     with pytest.raises(B.UnisparseError):
         B.us_desc_preset(B.US_F_BCSR, 0, 4)
@@ -83,7 +85,7 @@ def test_host_side_checks_return_before_any_device_work():
         B.make_desc([E(B.US_E_DIV, 1, 0, 0, 32), E(B.US_E_DIV, 0, 1, 0, 32), E(B.US_E_MOD, 1, 0, 0, 32),
                      E(B.US_E_MOD, 0, 1, 0, 32)], (1, 1), (0, 1)),                              # block too large
         B.make_desc([E(B.US_E_DIV, 1, 0, 0, 2), E(B.US_E_DIV, 0, 1, 0, 2), E(B.US_E_MOD, 1, 0, 0, 2),
-                     E(B.US_E_MOD, 0, 1, 0, 2)], (2, 3), (1,)),                                 # CSB: not on the GPU path
+                     E(B.US_E_MOD, 0, 1, 0, 2)], (2, 3), (0,)),                                 # CSB map and trim, wrong merge
         B.make_desc([E(B.US_E_AFFINE, 1, 0)], (0, 0), (0,)),                                    # one level
     ]
     for d in unsupported:

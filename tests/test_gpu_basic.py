@@ -12,6 +12,7 @@ FORMATS = [
     ("COO", O.COO()), ("CSR", O.CSR()), ("DCSR", O.DCSR()), ("CSC", O.CSC()), ("DCSC", O.DCSC()),
     ("DIA", O.DIA()), ("DIAv", O.DIA_VARIANT()), ("BCSR2", O.BCSR(2)), ("BCSR4", O.BCSR(4)),
     ("BCSR2x3", O.BCSR(2, 3)), ("BCSR8", O.BCSR(8)), ("ELL", O.ELL()), ("BDIA3", O.BDIA(3)), ("BDIA16", O.BDIA(16)),
+    ("CSB2", O.CSB(2)), ("CSB5x3", O.CSB(5, 3)), ("CSB64x128", O.CSB(64, 128)),
 ]
 
 
@@ -107,7 +108,7 @@ def test_error_paths(ctx):
     from paper_2403_05802_amd import binding as B
     from helpers import dev, us_desc_of
     r = np.array([0, 1, 1], np.int32); c = np.array([0, 2, 2], np.int32); v = np.ones(3, np.float32)
-    for d in (O.CSR(), O.COO(), O.DCSR(), O.BCSR(2), O.ELL(), O.DIA(), O.BDIA(3)):
+    for d in (O.CSR(), O.COO(), O.DCSR(), O.BCSR(2), O.ELL(), O.DIA(), O.BDIA(3), O.CSB(2)):
         with pytest.raises(B.UnisparseError) as ei:
             B.us_convert(ctx, 3, 3, dev(r), dev(c), dev(v), us_desc_of(d))
         assert ei.value.code == "US_ERR_DUPLICATE", d

@@ -1,5 +1,5 @@
 """Format -> format conversion through the COO hub (the reversibility / reachability argument
-of Section 5.2, the CSR->CSC, DCSC->BCSR, COO->ELL, COO->DIA cases of Table 5) vs the oracle."""
+of Section 5.2, the CSR->CSC, DCSC->BCSR, CSB->DIA-variant, COO->ELL, COO->DIA cases of Table 5) vs the oracle."""
 import numpy as np
 import pytest
 
@@ -10,7 +10,7 @@ pytestmark = pytest.mark.gpu
 
 FORMATS = [("COO", O.COO()), ("CSR", O.CSR()), ("DCSR", O.DCSR()), ("CSC", O.CSC()), ("DCSC", O.DCSC()),
            ("DIA", O.DIA()), ("DIAv", O.DIA_VARIANT()), ("BCSR4", O.BCSR(4)), ("BCSR2x3", O.BCSR(2, 3)), ("ELL", O.ELL()),
-           ("BDIA3", O.BDIA(3))]
+           ("BDIA3", O.BDIA(3)), ("CSB8x4", O.CSB(8, 4))]
 
 
 @pytest.fixture(scope="module")
@@ -70,3 +70,7 @@ def test_table5_cases_on_scaled_workloads(ctx):
     assert_same_layout(dia, O.convert(b.nrows, b.ncols, b.row, b.col, b.val, O.DIA()), "COO->DIA")
     diav = B.us_convert_formatted(ctx, dia, us_desc_of(O.DIA_VARIANT()))
     assert_same_layout(diav, O.convert(b.nrows, b.ncols, b.row, b.col, b.val, O.DIA_VARIANT()), "DIA->DIA variant")
+    csb = B.us_convert(ctx, b.nrows, b.ncols, *coo_to_dev(b), us_desc_of(O.CSB(512, 256)))
+    assert_same_layout(csb, O.convert(b.nrows, b.ncols, b.row, b.col, b.val, O.CSB(512, 256)), "COO->CSB")
+    diav2 = B.us_convert_formatted(ctx, csb, us_desc_of(O.DIA_VARIANT()))       # CSB -> DIA variant
+    assert_same_layout(diav2, O.convert(b.nrows, b.ncols, b.row, b.col, b.val, O.DIA_VARIANT()), "CSB->DIA variant")
