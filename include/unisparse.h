@@ -150,7 +150,11 @@ us_status us_decompose(const us_ctx *ctx, const us_coo *coo, const us_format_des
 
 /* y = A x (accumulate = 0) or y += A x (accumulate != 0; the generic op of Figure 3c reads Y).
  * x: ncols floats, y: nrows floats, both device.  For a hybrid call it on part A, then on
- * part B with accumulate = 1. */
+ * part B with accumulate = 1.
+ * Row-grouped layouts (COO, CSR, DCSR, DIA and its variant, BCSR, BDIA, ELL) add in a fixed order: two
+ * calls give the same bits.  Layouts whose leaves are not grouped by output row (CSC, DCSC, column-major
+ * COO, CSB) scatter with fp32 atomics, so the last bits may differ from call to call; this holds for
+ * us_spmm as well. */
 us_status us_spmv(const us_ctx *ctx, const us_formatted *A, const float *x, float *y, int32_t accumulate);
 
 /* Y = A X or Y += A X with dense row-major X (ncols x N, leading dimension ldx >= N) and
