@@ -53,9 +53,20 @@ struct Env {
 
   void *alloc_raw(size_t bytes);
   void free_raw(void *p);
+  // Temporaries are carved out of a reserved block while it lasts (256-byte granules): a call into the
+  // caller's allocator costs microseconds of host time during which the GPU may sit idle.
+  char *arena = nullptr; size_t arena_left = 0;
+  static size_t granule(size_t bytes) { return bytes < 256 ? 256 : (bytes + 255) & ~(size_t)255; }
+  void reserve(size_t bytes);   // one allocation for the temp() calls that follow (no error if it fails)
   template <typename T>
   T *temp(size_t count) {  // never returns NULL for count == 0 callers: allocates at least 256 B
-    void *p = alloc_raw(count * sizeof(T) < 256 ? 256 : count * sizeof(T));
+    const size_t need = granule(count * sizeof(T));
+    if (arena_left >= need) {
+      void *p = arena;
+      arena += need; arena_left -= need;
+      return (T *)p;
+    }
+    void *p = alloc_raw(need);
     if (!p) { fail(US_ERR_ALLOC); return nullptr; }
     temps.push_back(p);
     return (T *)p;
@@ -144,6 +155,9 @@ void exclusive_scan_i32(Env &env, const int32_t *in, int32_t *out, int64_t n, in
 // in-place exclusive scan of nb per-tile sums by one workgroup; grand total to *total_dev
 void scan_partials_launch(Env &env, uint32_t *partial, int64_t nb, int32_t *total_dev);
 void lower_bound_ptr(Env &env, const int32_t *sorted_major, int64_t n, int64_t ngroups, int32_t *ptr);
+// the same ptr from one pass over sorted entries, which also flags equal neighbours if `check`
+void group_ptr_unique(Env &env, const int32_t *sorted_major, const int32_t *sorted_minor, int64_t n, int64_t ngroups,
+                      int32_t *ptr, bool check, Flags *flags);
 
 // how the 64/32-bit sort key is built from a COO entry
 struct KeySpec {
@@ -179,7 +193,10 @@ us_status convert_formatted_impl(Env &env, const us_formatted &src, const us_for
 void *ensure_workspace(Env &env, const us_formatted &A, size_t bytes);
 
 // spmv.hip / spmm.hip
-void spmv_prepare(Env &env, us_formatted *f);  // fills mp_split for row-major CSR / DCSR
+// fills mp_split for row-major CSR / DCSR.  With nmajor_dev the number of stored rows is still on the device
+// (at most nmajor_cap): mp_split is sized for the cap and the caller sets nmajor and mp_tiles once it knows.
+void spmv_prepare(Env &env, us_formatted *f, const int32_t *nmajor_dev = nullptr, int64_t nmajor_cap = 0);
+int64_t spmv_tiles(int64_t nmajor, int64_t nnz);
 us_status spmv_impl(Env &env, const us_formatted &A, const float *x, float *y, bool accumulate);
 us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, int64_t ldx, float *Y,
                     int64_t ldy, bool accumulate);

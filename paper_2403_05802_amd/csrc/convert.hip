@@ -91,14 +91,22 @@ __global__ __launch_bounds__(256) void nonempty_flag_kernel(const int32_t *ptr, 
   if (g < n) flag[g] = ptr[g + 1] > ptr[g] ? 1 : 0;
 }
 
+// *nnr_dev = number of non-empty groups (the total of the scan that made pos); the arrays hold `cap` of
+// them, which a valid input never exceeds
 __global__ __launch_bounds__(256) void dcsr_compact_kernel(const int32_t *ptr, const int32_t *pos, int64_t n,
-                                                          int64_t nnr, int32_t nnz, int32_t *idx0, int32_t *ptr1) {
+                                                          const int32_t *nnr_dev, int64_t cap, int32_t nnz,
+                                                          int32_t *idx0, int32_t *ptr1) {
   int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (g == 0) ptr1[nnr] = nnz;
+  if (g == 0) {
+    const int64_t nnr = *nnr_dev;
+    ptr1[nnr >= 0 && nnr < cap ? nnr : cap] = nnz;
+  }
   if (g < n && ptr[g + 1] > ptr[g]) {
     int32_t k = pos[g];
-    idx0[k] = (int32_t)g;
-    ptr1[k] = ptr[g];
+    if (k >= 0 && k < cap) {
+      idx0[k] = (int32_t)g;
+      ptr1[k] = ptr[g];
+    }
   }
 }
 
@@ -216,11 +224,11 @@ static us_status build_from_sorted(Env &env, const Plan &plan, const us_format_d
     return flag_status(*h);
   };
   Flags h{};
-  if (check_dups && nnz > 1)
-    US_LAUNCH(env, "check_unique", 8.0 * nnz, check_unique_unpacked_kernel, ceil_div<int64_t>(nnz, 256), 256,
-              (const int32_t *)major, (const int32_t *)minor, nnz, flags);
 
   if (plan.pattern == P_COO) {
+    if (check_dups && nnz > 1)
+      US_LAUNCH(env, "check_unique", 8.0 * nnz, check_unique_unpacked_kernel, ceil_div<int64_t>(nnz, 256), 256,
+                (const int32_t *)major, (const int32_t *)minor, nnz, flags);
     f->nlevels = 2;
     f->level[0].idx = major; f->level[0].nidx = nnz;
     f->level[1].idx = minor; f->level[1].nidx = nnz;
@@ -238,7 +246,8 @@ static us_status build_from_sorted(Env &env, const Plan &plan, const us_format_d
     ptr = env.temp<int32_t>(nmaj + 1);
   }
   if (!env.ok()) return finish(env.status);
-  lower_bound_ptr(env, major, nnz, nmaj, ptr);
+  if (check_dups) group_ptr_unique(env, major, minor, nnz, nmaj, ptr, true, flags);
+  else lower_bound_ptr(env, major, nnz, nmaj, ptr);
 
   if (plan.pattern == P_CSR) {
     f->nlevels = 2;
@@ -251,28 +260,32 @@ static us_status build_from_sorted(Env &env, const Plan &plan, const us_format_d
   }
 
   if (plan.pattern == P_DCSR) {
-    // Trim(0): keep only the major indices that have children
+    // Trim(0): keep only the major indices that have children.  How many there are (nnr) stays on the
+    // device until the one read of the flags that ends the call: idx and ptr are allocated for the most
+    // there can be, min(nmaj, nnz), and the kernels in between take nnr from device memory.
+    const int64_t cap = nmaj < nnz ? nmaj : nnz;
     int32_t *flag = env.temp<int32_t>(nmaj), *pos = env.temp<int32_t>(nmaj);
+    int32_t *idx0 = env.owned<int32_t>(cap), *ptr1 = env.owned<int32_t>(cap + 1);
+    f->nlevels = 2;
+    f->level[0].idx = idx0; f->level[0].nidx = 0;
+    f->level[1].ptr = ptr1; f->level[1].nptr = 1;
+    f->level[1].idx = minor; f->level[1].nidx = nnz;
+    f->val = val; f->nval = nnz; f->nmajor = 0;
+    minor_loose = val_loose = false;
     if (!env.ok()) return finish(env.status);
     US_LAUNCH(env, "nonempty_flag", 8.0 * nmaj, nonempty_flag_kernel, ceil_div<int64_t>(nmaj, 256), 256,
               (const int32_t *)ptr, nmaj, flag);
     exclusive_scan_i32(env, flag, pos, nmaj, &flags->scalar[0]);
+    US_LAUNCH(env, "dcsr_compact", 12.0 * nmaj + 8.0 * cap, dcsr_compact_kernel, ceil_div<int64_t>(nmaj, 256), 256,
+              (const int32_t *)ptr, (const int32_t *)pos, nmaj, (const int32_t *)&flags->scalar[0], cap,
+              (int32_t)nnz, idx0, ptr1);
+    spmv_prepare(env, f, &flags->scalar[0], cap);
     us_status s = flags_ok(&h);
     if (s != US_OK) return finish(s);
     const int64_t nnr = h.scalar[0];
-    int32_t *idx0 = env.owned<int32_t>(nnr), *ptr1 = env.owned<int32_t>(nnr + 1);
-    f->nlevels = 2;
-    f->level[0].idx = idx0; f->level[0].nidx = nnr;
-    f->level[1].ptr = ptr1; f->level[1].nptr = nnr + 1;
-    f->level[1].idx = minor; f->level[1].nidx = nnz;
-    f->val = val; f->nval = nnz; f->nmajor = nnr;
-    minor_loose = val_loose = false;
-    if (!env.ok()) return finish(env.status);
-    US_LAUNCH(env, "dcsr_compact", 12.0 * nmaj + 8.0 * nnr, dcsr_compact_kernel, ceil_div<int64_t>(nmaj, 256), 256,
-              (const int32_t *)ptr, (const int32_t *)pos, nmaj, nnr, (int32_t)nnz, idx0, ptr1);
-    spmv_prepare(env, f);
-    env.sync();
-    return finish(env.status);
+    f->level[0].nidx = nnr; f->level[1].nptr = nnr + 1; f->nmajor = nnr;
+    f->mp_tiles = f->mp_split ? spmv_tiles(nnr, nnz) : 0;
+    return finish(US_OK);
   }
 
   if (plan.pattern == P_ELL) {

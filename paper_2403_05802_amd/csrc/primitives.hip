@@ -19,7 +19,16 @@ void Env::free_raw(void *p) {
 }
 int g_lds_finish = -1;
 
+void Env::reserve(size_t bytes) {
+  if (arena_left >= bytes || bytes == 0) return;
+  void *p = alloc_raw(granule(bytes));
+  if (!p) return;   // temp() falls back to one allocation per array
+  temps.push_back(p);
+  arena = (char *)p; arena_left = granule(bytes);
+}
+
 void Env::release_temps() {
+  arena = nullptr; arena_left = 0;
   if (temps.empty()) return;
   (void)hipStreamSynchronize(stream);  // kernels may still read the temporaries
   for (void *p : temps) free_raw(p);
@@ -143,6 +152,88 @@ __global__ __launch_bounds__(256) void lower_bound_ptr_kernel(const int32_t *maj
 void lower_bound_ptr(Env &env, const int32_t *sorted_major, int64_t n, int64_t ngroups, int32_t *ptr) {
   US_LAUNCH(env, "ptr_lower_bound", 4.0 * n + 4.0 * (ngroups + 1), lower_bound_ptr_kernel,
             ceil_div<int64_t>(ngroups + 1, 256), 256, sorted_major, n, ngroups, ptr);
+}
+
+// ------------------------------------------------------------------ the same pointers from one pass over the entries
+// Entries sorted by (major, minor): wherever the major index steps from p to r, ptr[p+1..r] is that
+// position; behind the last entry everything is n.  The same pass compares neighbours (check != 0:
+// Flags::duplicate).  Short steps are written by the thread that finds them, long ones (runs of empty
+// groups) by the whole workgroup afterwards.  Index arrays that failed validation may hold anything:
+// every write stays inside ptr[0..ngroups], whatever they hold (entries of ptr may then stay unwritten;
+// the call ends in US_ERR_INDEX_RANGE and ptr is only ever read as numbers before that).
+constexpr int GP_IPT = 4, GP_SHORT = 16, GP_LIST = 256;
+
+__global__ __launch_bounds__(256) void group_ptr_unique_kernel(const int32_t *major, const int32_t *minor, int64_t n,
+                                                               int64_t ngroups, int32_t *ptr, int check,
+                                                               Flags *flags) {
+  __shared__ int32_t s_lo[GP_LIST], s_hi[GP_LIST], s_v[GP_LIST];
+  __shared__ uint32_t s_n;
+  if (threadIdx.x == 0) s_n = 0;
+  __syncthreads();
+  auto emit = [&](int64_t lo, int64_t hi, int64_t v) {   // ptr[lo..hi] = v
+    if (hi - lo < GP_SHORT) {
+      for (int64_t q = lo; q <= hi; ++q) ptr[q] = (int32_t)v;
+      return;
+    }
+    const uint32_t k = atomicAdd(&s_n, 1u);
+    if (k < GP_LIST) {
+      s_lo[k] = (int32_t)lo; s_hi[k] = (int32_t)hi; s_v[k] = (int32_t)v;
+    } else {
+      for (int64_t q = lo; q <= hi; ++q) ptr[q] = (int32_t)v;
+    }
+  };
+  auto clampg = [&](int32_t m) { return (int64_t)((uint32_t)m < (uint64_t)ngroups ? m : ngroups - 1); };
+  const int64_t i0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * GP_IPT;
+  if (i0 < n) {
+    int32_t m[GP_IPT], c[GP_IPT];
+    const bool vec = i0 + GP_IPT <= n && (((uintptr_t)major | (uintptr_t)minor) & 15) == 0;
+    if (vec) {
+      const int4 mv = *reinterpret_cast<const int4 *>(major + i0);
+      m[0] = mv.x; m[1] = mv.y; m[2] = mv.z; m[3] = mv.w;
+      if (check) {
+        const int4 cv = *reinterpret_cast<const int4 *>(minor + i0);
+        c[0] = cv.x; c[1] = cv.y; c[2] = cv.z; c[3] = cv.w;
+      } else {
+        c[0] = c[1] = c[2] = c[3] = 0;
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < GP_IPT; ++k) {
+        const int64_t i = i0 + k < n ? i0 + k : n - 1;
+        m[k] = major[i];
+        c[k] = check ? minor[i] : 0;
+      }
+    }
+    int64_t pm = i0 > 0 ? clampg(major[i0 - 1]) : -1;
+    int32_t pm_raw = i0 > 0 ? major[i0 - 1] : -1, pc = i0 > 0 && check ? minor[i0 - 1] : -1;
+    bool dup = false;
+#pragma unroll
+    for (int k = 0; k < GP_IPT; ++k) {
+      if (i0 + k < n) {
+        const int64_t r = clampg(m[k]);
+        if (r > pm) emit(pm + 1, r, i0 + k);
+        if (check && i0 + k > 0 && m[k] == pm_raw && c[k] == pc) dup = true;
+        if (r > pm) pm = r;
+        pm_raw = m[k]; pc = c[k];
+      }
+    }
+    if (i0 + GP_IPT >= n) emit(pm + 1, ngroups, n);
+    if (dup) flags->duplicate = 1;
+  }
+  __syncthreads();
+  const uint32_t cnt = s_n < (uint32_t)GP_LIST ? s_n : (uint32_t)GP_LIST;
+  for (uint32_t k = 0; k < cnt; ++k)
+    for (int64_t q = (int64_t)s_lo[k] + threadIdx.x; q <= (int64_t)s_hi[k]; q += 256) ptr[q] = s_v[k];
+}
+
+void group_ptr_unique(Env &env, const int32_t *sorted_major, const int32_t *sorted_minor, int64_t n, int64_t ngroups,
+                      int32_t *ptr, bool check, Flags *flags) {
+  if (n <= 0) {
+    fill_u32(env, (uint32_t *)ptr, (uint64_t)ngroups + 1, 0u);
+    return;
+  }
+  US_LAUNCH(env, "ptr_unique", (check ? 8.0 : 4.0) * n + 4.0 * (ngroups + 1), group_ptr_unique_kernel,
+            ceil_div<int64_t>(n, 256 * GP_IPT), 256, sorted_major, sorted_minor, n, ngroups, ptr, check ? 1 : 0, flags);
 }
 
 }  // namespace us

@@ -28,6 +28,7 @@ namespace us {
 
 constexpr int RS_T = 512, RS_IPT = 8, RS_TILE = RS_T * RS_IPT, RS_NW = RS_T / 64, RS_MAXBITS = 8, RS_BINS = 1 << RS_MAXBITS;
 constexpr int RS_CHUNK = 32;  // tiles per workgroup of the chunk scan
+constexpr int RS_HC = 16;     // histogram kernel: counters per digit
 
 typedef uint64_t Key;  // keys live in registers and LDS as 64-bit words whatever their storage
 
@@ -93,10 +94,14 @@ __device__ __forceinline__ uint32_t xcd_tile(uint32_t i, uint32_t per_xcd) { ret
 
 template <int IN>
 __global__ __launch_bounds__(RS_T) void radix_hist_kernel(PassArgs a) {
-  __shared__ uint32_t s_hist[RS_BINS];
-  for (int i = threadIdx.x; i < RS_BINS; i += RS_T) s_hist[i] = 0;
+  // RS_HC counters per digit, picked by lane: neighbouring items often share a digit (within a group of
+  // rows that share their low bits, one heavy row owns most entries), and LDS adds to one address
+  // take their turns one lane at a time.
+  __shared__ uint32_t s_hist[RS_BINS * RS_HC];
+  for (int i = threadIdx.x; i < RS_BINS * RS_HC; i += RS_T) s_hist[i] = 0;
   __syncthreads();
   const uint32_t base = blockIdx.x * RS_TILE;
+  const uint32_t copy = threadIdx.x & (RS_HC - 1);
   uint32_t digit[RS_IPT];
   if (IN == IN_SPLIT && a.digit_in) {
     // the previous pass left this pass's digits as bytes: 8 per thread in one 8-byte load
@@ -140,9 +145,14 @@ __global__ __launch_bounds__(RS_T) void radix_hist_kernel(PassArgs a) {
   }
 #pragma unroll
   for (int k = 0; k < RS_IPT; ++k)
-    if (digit[k] != 0xFFFFFFFFu) atomicAdd(&s_hist[digit[k]], 1u);
+    if (digit[k] != 0xFFFFFFFFu) atomicAdd(&s_hist[digit[k] * RS_HC + copy], 1u);
   __syncthreads();
-  for (uint32_t d = threadIdx.x; d < RS_BINS; d += RS_T) a.hist[(size_t)blockIdx.x * RS_BINS + d] = s_hist[d];
+  for (uint32_t d = threadIdx.x; d < RS_BINS; d += RS_T) {
+    uint32_t sum = 0;
+#pragma unroll
+    for (uint32_t c = 0; c < RS_HC; ++c) sum += s_hist[d * RS_HC + ((c + d) & (RS_HC - 1))];
+    a.hist[(size_t)blockIdx.x * RS_BINS + d] = sum;
+  }
 }
 
 // Offsets of every (tile, digit) run without a single atomic:
@@ -652,6 +662,21 @@ static bool sort_generic(Env &env, int in_mode, const int32_t *row, const int32_
   const int nrec = finish_local ? npass : npass - 1;   // passes that write records
   Rec *rbuf[2] = {nullptr, nullptr};
   uint8_t *dbuf[2] = {nullptr, nullptr};
+  const uint32_t nbuckets = finish_local ? 1u << high_bits : 0u;
+  LocalArgs la{};
+  la.big_cap = (uint32_t)(nnz / LS_CAP) + 1;                 // a big bucket holds more than LS_CAP items
+  la.tile_cap = (uint32_t)(nnz / RS_TILE) + la.big_cap;      // each has at most size/RS_TILE + 1 tiles
+  la.work_cap = (uint32_t)(nnz / LS_GROUP) + la.big_cap;     // ... and at most size/LS_GROUP + 1 groups
+  {  // everything below in one allocation
+    auto g = [](size_t b) { return Env::granule(b); };
+    size_t need = (nrec < 2 ? nrec : 2) * g(sizeof(Rec) * nnz) + (npass - 1 < 2 ? npass - 1 : 2) * g(nnz + 16) +
+                  g(4ull * RS_BINS * nblocks) + g(4ull * RS_BINS * nchunks) + g(4ull * RS_BINS);
+    if (finish_local)
+      need += g(4ull * (nbuckets + 1)) + (npass >= 2 ? 0 : g(sizeof(Rec) * nnz)) + g(16) +
+              g(sizeof(BigBucket) * la.big_cap) + g(4ull * la.tile_cap) + g(4ull * la.tile_cap * RS_BINS) +
+              g(4ull * la.big_cap * RS_BINS) + g(sizeof(WorkItem) * la.work_cap);
+    env.reserve(need);
+  }
   for (int i = 0; i < 2 && i < nrec; ++i) rbuf[i] = env.temp<Rec>(nnz);
   for (int i = 0; i < 2 && i < npass - 1; ++i) dbuf[i] = env.temp<uint8_t>(nnz + 16);
   uint32_t *hist = env.temp<uint32_t>((size_t)RS_BINS * nblocks);
@@ -706,12 +731,7 @@ static bool sort_generic(Env &env, int in_mode, const int32_t *row, const int32_
   }
   if (!finish_local) return false;
 
-  const uint32_t nbuckets = 1u << high_bits;
-  LocalArgs la{};
   la.nbuckets = nbuckets; la.n = (uint32_t)nnz; la.low_bits = low_bits; la.b_bits = ks.b_bits;
-  la.big_cap = (uint32_t)(nnz / LS_CAP) + 1;                 // a big bucket holds more than LS_CAP items
-  la.tile_cap = (uint32_t)(nnz / RS_TILE) + la.big_cap;      // each has at most size/RS_TILE + 1 tiles
-  la.work_cap = (uint32_t)(nnz / LS_GROUP) + la.big_cap;     // ... and at most size/LS_GROUP + 1 groups
   uint32_t *off = env.temp<uint32_t>((size_t)nbuckets + 1);
   la.rec_in = rbuf[(npass - 1) & 1];
   la.rec_split = npass >= 2 ? rbuf[npass & 1] : env.temp<Rec>(nnz);

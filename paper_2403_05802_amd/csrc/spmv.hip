@@ -26,9 +26,16 @@ __device__ __forceinline__ int64_t merge_path_rows(const int32_t *row_end, int64
 struct SegPair { int32_t key; float val; };
 
 // split[t] = row ends consumed before merge step t * MP_TILE (t = 0..ntiles)
+// nrows_dev != null: the row count is *nrows_dev (at most nrows) and the tile count follows from it
 __global__ __launch_bounds__(256) void merge_path_split_kernel(const int32_t *ptr, int64_t nrows, int64_t nnz,
-                                                              int64_t ntiles, int32_t *split) {
+                                                              int64_t ntiles, const int32_t *nrows_dev,
+                                                              int32_t *split) {
   int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (nrows_dev) {
+    const int64_t r = *nrows_dev;
+    nrows = r >= 0 && r < nrows ? r : nrows;
+    ntiles = (nrows + nnz + MP_TILE - 1) / MP_TILE;
+  }
   if (t > ntiles) return;
   int64_t d = t * MP_TILE;
   if (d > nrows + nnz) d = nrows + nnz;
@@ -277,16 +284,19 @@ __global__ __launch_bounds__(256) void csb_spmv_atomic_kernel(const int32_t *ptr
   atomicAdd(&y[row], val[e] * x[col]);
 }
 
-void spmv_prepare(Env &env, us_formatted *f) {
+int64_t spmv_tiles(int64_t nmajor, int64_t nnz) { return ceil_div<int64_t>(nmajor + nnz, MP_TILE); }
+
+void spmv_prepare(Env &env, us_formatted *f, const int32_t *nmajor_dev, int64_t nmajor_cap) {
   if (f->swapped || (f->pattern != P_CSR && f->pattern != P_DCSR)) return;
-  const int64_t total = f->nmajor + f->nnz;
+  const int64_t nmajor = nmajor_dev ? nmajor_cap : f->nmajor;
+  const int64_t total = nmajor + f->nnz;
   if (total == 0) return;
-  const int64_t nb = ceil_div<int64_t>(total, MP_TILE);
+  const int64_t nb = spmv_tiles(nmajor, f->nnz);
   f->mp_split = env.owned<int32_t>(nb + 1);
   f->mp_tiles = nb;
   if (!env.ok()) return;
   US_LAUNCH(env, "spmv_split", 4.0 * (nb + 1), merge_path_split_kernel, ceil_div<int64_t>(nb + 1, 256), 256,
-            (const int32_t *)f->level[1].ptr, f->nmajor, f->nnz, nb, f->mp_split);
+            (const int32_t *)f->level[1].ptr, nmajor, f->nnz, nb, nmajor_dev, f->mp_split);
 }
 
 us_status spmv_impl(Env &env, const us_formatted &A, const float *x, float *y, bool accumulate) {
