@@ -180,6 +180,8 @@ struct SortOut {
 };
 bool sort_coo(Env &env, const int32_t *row, const int32_t *col, const float *val, int64_t nnz,
               const KeySpec &ks, const SortOut &out, Flags *flags_dev);
+// what a whole-array sort of nnz entries takes from Env::temp (for Env::reserve by a caller with temporaries of its own)
+size_t sort_temp_bytes(int64_t nnz);
 // ascending sort of 32-bit keys
 void sort_u32(Env &env, const uint32_t *key, int64_t n, int bits, uint32_t *out, Flags *flags_dev);
 // convert.hip

@@ -833,6 +833,8 @@ static Flags *new_flags(Env &env) {
 
 static us_status convert_with_plan(Env &env, const us_coo &coo, const Plan &plan, const us_format_desc &desc,
                                    us_formatted **out) {
+  const bool by_sort = plan.pattern == P_COO || plan.pattern == P_CSR || plan.pattern == P_DCSR || plan.pattern == P_ELL;
+  if (by_sort) env.reserve(sort_temp_bytes(coo.nnz) + 4 * Env::granule(sizeof(Flags)));   // flags and the sort's buffers together
   Flags *flags = new_flags(env);
   if (!env.ok()) return env.status;
   if (plan.pattern == P_DIA) return convert_dia(env, coo, plan, desc, flags, out);

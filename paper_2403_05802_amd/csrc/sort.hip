@@ -69,13 +69,20 @@ struct PassArgs {
   uint32_t *dtotal;                // [RS_BINS] digit totals of the whole input
   uint32_t nchunks;
   KeySpec ks;
+  int hist_minor_only;             // IN_COO: this pass's digit lies inside the minor index of a (major, minor) key
   Flags *flags;
 };
 
+__device__ __forceinline__ bool coo_out_of_range(const KeySpec &ks, uint32_t r, uint32_t c) {
+  return ((ks.swap ? c : r) >= ks.a_extent) | ((ks.swap ? r : c) >= ks.b_extent);
+}
+
 template <int IN>
-__device__ __forceinline__ void load_item(const PassArgs &a, uint32_t i, Key *key, uint32_t *val) {
+__device__ __forceinline__ void load_item(const PassArgs &a, uint32_t i, Key *key, uint32_t *val, bool *bad) {
   if (IN == IN_COO) {
-    *key = build_key(a.ks, (uint32_t)a.row[i], (uint32_t)a.col[i]);
+    const uint32_t r = (uint32_t)a.row[i], c = (uint32_t)a.col[i];
+    *bad |= coo_out_of_range(a.ks, r, c);
+    *key = build_key(a.ks, r, c);
     *val = a.val_in[i];
   } else if (IN == IN_KEY32) {
     *key = a.lo_in[i];
@@ -117,6 +124,15 @@ __global__ __launch_bounds__(RS_T) void radix_hist_kernel(PassArgs a) {
 #pragma unroll
       for (int k = 0; k < RS_IPT; ++k) digit[k] = i + k < a.n ? a.digit_in[i + k] : 0xFFFFFFFFu;
     }
+  } else if (IN == IN_COO && a.hist_minor_only) {
+    // the digit is a bit field of the minor index alone: read that array only (the scatter of this pass
+    // reads both and validates them; bits of an out-of-range minor index land in the key just the same)
+    const int32_t *minor = a.ks.swap ? a.row : a.col;
+#pragma unroll
+    for (int k = 0; k < RS_IPT; ++k) {
+      uint32_t i = base + k * RS_T + threadIdx.x;
+      digit[k] = i < a.n ? (((uint32_t)minor[i] >> a.shift) & a.mask) : 0xFFFFFFFFu;
+    }
   } else {
     bool bad = false;
     Key key[RS_IPT];
@@ -125,15 +141,8 @@ __global__ __launch_bounds__(RS_T) void radix_hist_kernel(PassArgs a) {
       uint32_t i = base + k * RS_T + threadIdx.x;
       key[k] = 0;
       if (i < a.n) {
-        if (IN == IN_COO) {
-          uint32_t r = (uint32_t)a.row[i], c = (uint32_t)a.col[i];
-          uint32_t ra = a.ks.swap ? c : r, cb = a.ks.swap ? r : c;
-          bad |= (ra >= a.ks.a_extent) | (cb >= a.ks.b_extent);
-          key[k] = build_key(a.ks, r, c);
-        } else {
-          uint32_t unused;
-          load_item<IN>(a, i, &key[k], &unused);
-        }
+        uint32_t unused;
+        load_item<IN>(a, i, &key[k], &unused, &bad);
       }
     }
 #pragma unroll
@@ -160,6 +169,8 @@ __global__ __launch_bounds__(RS_T) void radix_hist_kernel(PassArgs a) {
 //                 them (coalesced rows), leaving prefixes inside the chunk and the chunk total;
 //   top kernel:   one wavefront per digit scans the chunk totals and leaves the digit total;
 //   the scatter kernel adds the start of the digit (a 256-entry scan it does itself).
+// Letting one workgroup of the histogram kernel count 8 tiles in a row and leave the prefixes itself (no chunk
+// kernel) was no faster: 25 + 8.5 us a pass for the two kernels left, against 19 + 7 + 6.5 for these three.
 __global__ __launch_bounds__(RS_BINS) void radix_scan_chunk_kernel(uint32_t *hist, uint32_t *chunk, uint32_t nblocks) {
   const uint32_t d = threadIdx.x;
   const uint32_t t0 = blockIdx.x * RS_CHUNK, t1 = min(t0 + RS_CHUNK, nblocks);
@@ -208,13 +219,15 @@ __global__ __launch_bounds__(RS_T) void radix_scatter_kernel(PassArgs a) {
   const uint32_t in_tile = min((uint32_t)RS_TILE, a.n - base);
   Key key[RS_IPT];
   uint32_t val[RS_IPT], pos[RS_IPT];
+  bool bad = false;
   // wave w owns the contiguous slice [w*64*IPT, (w+1)*64*IPT) of the tile, lanes striped
 #pragma unroll
   for (int j = 0; j < RS_IPT; ++j) {
     uint32_t t = w * (64 * RS_IPT) + j * 64 + lane;
     key[j] = 0; val[j] = 0;
-    if (t < in_tile) load_item<IN>(a, base + t, &key[j], &val[j]);
+    if (t < in_tile) load_item<IN>(a, base + t, &key[j], &val[j], &bad);
   }
+  if (IN == IN_COO && bad) a.flags->index_range = 1;
   __syncthreads();
 
   // stable rank of every item among the items of its wave with the same digit.
@@ -712,12 +725,13 @@ static bool sort_generic(Env &env, int in_mode, const int32_t *row, const int32_
     a.next_mask = last_pass ? 0u : (1u << widths[p + 1]) - 1u;
     a.tiles_per_xcd = ceil_div<uint32_t>(nblocks, 8u);
     a.hist = hist; a.chunk = chunk; a.dtotal = dtotal; a.nchunks = nchunks; a.ks = ks; a.flags = flags;
+    a.hist_minor_only = first && in_mode == IN_COO && ks.mode == 0 && shifts[p] + widths[p] <= ks.b_bits && ks.b_bits <= 32;
 
     const int in = first ? in_mode : IN_SPLIT;
     const int om = last ? final_mode : OUT_SPLIT;
     const double in_key = in == IN_COO ? 8.0 : (in == IN_KEY32 ? 4.0 : kb);
     const double out_key = om == OUT_UNPACK ? 8.0 : (om == OUT_KEY64 ? 8.0 : (om == OUT_KEY32 ? 4.0 : kb + 1.0));
-    if (in == IN_COO) launch_hist<IN_COO>(env, a, 8.0 * nnz);
+    if (in == IN_COO) launch_hist<IN_COO>(env, a, (a.hist_minor_only ? 4.0 : 8.0) * nnz);
     else if (in == IN_KEY32) launch_hist<IN_KEY32>(env, a, 4.0 * nnz);
     else launch_hist<IN_SPLIT>(env, a, 1.0 * nnz);
     US_LAUNCH(env, "radix_scan_chunk", 8.0 * RS_BINS * nblocks, radix_scan_chunk_kernel, nchunks, RS_BINS, hist, chunk,
@@ -760,6 +774,13 @@ static bool sort_generic(Env &env, int in_mode, const int32_t *row, const int32_
   else
     US_LAUNCH(env, "local_sort", 24.0 * nnz, (local_sort_kernel<OUT_KEY64>), nbuckets + la.work_cap, LS_T, la);
   return true;
+}
+
+size_t sort_temp_bytes(int64_t nnz) {
+  if (nnz <= 0) return 0;
+  const size_t nblocks = (size_t)ceil_div<int64_t>(nnz, RS_TILE), nchunks = ceil_div<size_t>(nblocks, RS_CHUNK);
+  return 2 * Env::granule(sizeof(Rec) * nnz) + 2 * Env::granule(nnz + 16) + Env::granule(4ull * RS_BINS * nblocks) +
+         Env::granule(4ull * RS_BINS * nchunks) + Env::granule(4ull * RS_BINS);
 }
 
 bool sort_coo(Env &env, const int32_t *row, const int32_t *col, const float *val, int64_t nnz,
