@@ -246,8 +246,16 @@ static us_status build_from_sorted(Env &env, const Plan &plan, const us_format_d
     ptr = env.temp<int32_t>(nmaj + 1);
   }
   if (!env.ok()) return finish(env.status);
-  if (check_dups) group_ptr_unique(env, major, minor, nnz, nmaj, ptr, true, flags);
-  else lower_bound_ptr(env, major, nnz, nmaj, ptr);
+  // one pass over the entries gives both ptr and the duplicate check; with fewer entries than groups the
+  // runs of empty groups are long and a binary search per group is the quicker way to ptr
+  if (check_dups && nnz >= nmaj) {
+    group_ptr_unique(env, major, minor, nnz, nmaj, ptr, true, flags);
+  } else {
+    if (check_dups && nnz > 1)
+      US_LAUNCH(env, "check_unique", 8.0 * nnz, check_unique_unpacked_kernel, ceil_div<int64_t>(nnz, 256), 256,
+                (const int32_t *)major, (const int32_t *)minor, nnz, flags);
+    lower_bound_ptr(env, major, nnz, nmaj, ptr);
+  }
 
   if (plan.pattern == P_CSR) {
     f->nlevels = 2;

@@ -203,3 +203,59 @@ def test_duplicate_cut_in_two_by_a_rank_split(ctx):
         with pytest.raises(B.UnisparseError) as ei:
             B.us_decompose(ctx, n, n, dev(r), dev(c), dev(v), us_desc_of(da), us_desc_of(db), pred)
         assert ei.value.code == "US_ERR_DUPLICATE", (da, db)
+
+
+def test_row_pointers_over_runs_of_empty_rows(ctx):
+    """The pointer pass walks the sorted entries and fills ptr wherever the row index steps: steps of every
+    length (inside one thread, listed for the workgroup, more of them than the list holds) and the tail
+    behind the last entry, with entries >= rows (one pass) and entries < rows (binary search per row)."""
+    from paper_2403_05802_amd import binding as B
+    from helpers import dev, us_desc_of
+    rng = np.random.default_rng(11)
+    # (a) 1024 consecutive entries each in a row of its own, 40 rows apart: > 256 long steps in one workgroup
+    far = np.arange(1500, dtype=np.int64) * 40 + 7
+    # (b) a dense head so that entries >= rows, with steps of 1..17 rows around the in-thread limit
+    steps = np.concatenate([np.arange(1, 18), rng.integers(1, 18, 300)])
+    mid = far[-1] + 1 + np.cumsum(steps)
+    nrows = int(mid[-1]) + 5000                      # a long tail of empty rows behind the last entry
+    head_r = np.repeat(np.arange(3, dtype=np.int64), nrows // 3 + 2)[: nrows + 10]
+    head_c = np.concatenate([rng.permutation(nrows)[: (head_r == k).sum()] for k in range(3)])
+    r = np.concatenate([head_r, far, mid]).astype(np.int32)
+    c = np.concatenate([head_c, rng.integers(0, nrows, far.size + mid.size)]).astype(np.int32)
+    keep = np.unique(r.astype(np.int64) * nrows + c, return_index=True)[1]
+    r, c = r[keep], c[keep]
+    p = rng.permutation(r.size); r, c = r[p], c[p]
+    v = rng.uniform(0.5, 1, r.size).astype(np.float32)
+    assert r.size >= nrows
+    roundtrip(ctx, nrows, nrows, r, c, v, [O.CSR(), O.DCSR(), O.ELL(), O.CSC()])
+    # the same rows with few entries: fewer entries than rows
+    sel = r >= 3
+    roundtrip(ctx, nrows, nrows, r[sel], c[sel], v[sel], [O.CSR(), O.DCSR(), O.CSC(), O.DCSC()])
+    # equal neighbours that fall into different threads / workgroups of the pass
+    for cut in (4, 1024, 4096 + 3):
+        order = np.lexsort((c, r))
+        a, b = order[cut - 1], order[cut]             # neighbours in sorted order: make them equal
+        rr2, cc2 = r.copy(), c.copy()
+        rr2[b], cc2[b] = rr2[a], cc2[a]
+        with pytest.raises(B.UnisparseError) as ei:
+            B.us_convert(ctx, nrows, nrows, dev(rr2), dev(cc2), dev(v), us_desc_of(O.CSR()))
+        assert ei.value.code == "US_ERR_DUPLICATE"
+
+
+def test_hypersparse_dcsr_array_counts(ctx):
+    """Stored-row arrays are allocated before their count is known; what the handle reports is the count."""
+    from paper_2403_05802_amd import binding as B
+    from helpers import dev, us_desc_of
+    n = 3_000_000
+    r = np.array([5, 5, 2_999_999, 17, 17, 17], np.int32)
+    c = np.array([1, 0, 2_999_999, 9, 3, 4], np.int32)
+    v = np.arange(1, 7, dtype=np.float32)
+    g = B.us_convert(ctx, n, n, dev(r), dev(c), dev(v), us_desc_of(O.DCSR()))
+    assert g.idx(0).cpu().tolist() == [5, 17, 2_999_999]
+    assert g.ptr(1).cpu().tolist() == [0, 2, 5, 6]
+    assert g.idx(1).cpu().tolist() == [0, 1, 3, 4, 9, 2_999_999]
+    x = torch.ones(n, device="cuda"); y = torch.empty(n, device="cuda")
+    B.us_spmv(ctx, g, x, y)
+    assert float(y[5]) == 3.0 and float(y[17]) == 15.0 and float(y[2_999_999]) == 3.0 and float(y.sum()) == 21.0
+    g.free()
+    roundtrip(ctx, n, n, r, c, v, [O.DCSR(), O.CSR(), O.DCSC()])
