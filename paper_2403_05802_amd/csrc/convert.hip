@@ -205,8 +205,9 @@ static KeySpec rowcol_keyspec(const us_coo &coo, bool swapped) {
 // that move into the result (or are released when the format re-lays them out: ELL).
 static us_status build_from_sorted(Env &env, const Plan &plan, const us_format_desc &desc, int64_t nrows,
                                    int64_t ncols, int64_t nnz, int32_t *major, int32_t *minor, float *val,
-                                   Flags *flags, bool check_dups, us_formatted **out) {
+                                   Flags *flags, bool check_dups, us_formatted **out, bool validated = false) {
   // Takes ownership of major, minor and val (arrays of nnz entries from Env::owned).
+  // validated: the caller has already read the flags after the sort (indices are in range).
   us_formatted *f = new us_formatted();
   f->desc = desc; f->pattern = plan.pattern; f->swapped = plan.swapped;
   f->nrows = nrows; f->ncols = ncols; f->nnz = nnz;
@@ -301,9 +302,11 @@ static us_status build_from_sorted(Env &env, const Plan &plan, const us_format_d
     if (K == 0)
       US_LAUNCH(env, "max_row_len", 4.0 * nmaj, max_len_kernel, one_counter_grid(nmaj, 256), 256,
                 (const int32_t *)ptr, nmaj, &flags->scalar[0]);
-    us_status s = flags_ok(&h);
-    if (s != US_OK) return finish(s);
-    if (K == 0) K = h.scalar[0];
+    if (K == 0 || !validated) {   // the scatter below indexes by the major index: it must be known to be in range
+      us_status s = flags_ok(&h);
+      if (s != US_OK) return finish(s);
+      if (K == 0) K = h.scalar[0];
+    }
     if (K * nrows >= (1ll << 31)) return finish(US_ERR_OVERFLOW);
     const int64_t slots = K * nrows;
     int32_t *ecol = env.owned<int32_t>(slots);
@@ -1000,8 +1003,11 @@ __global__ __launch_bounds__(256) void row_len_kernel(const int32_t *ptr, int64_
 }
 __global__ void pick_kernel(const uint32_t *sorted, int64_t at, int32_t *out) { *out = (int32_t)sorted[at]; }
 
-__global__ __launch_bounds__(256) void clipped_len_kernel(const int32_t *ptr, int64_t n, int64_t K, int32_t *out) {
+// K_dev != null: the cut is still on the device (the percentile picked just before)
+__global__ __launch_bounds__(256) void clipped_len_kernel(const int32_t *ptr, int64_t n, int64_t K, const int32_t *K_dev,
+                                                         int32_t *out) {
   int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (K_dev) K = *K_dev;
   if (g < n) { int64_t l = ptr[g + 1] - ptr[g]; out[g] = (int32_t)(l < K ? l : K); }
 }
 
@@ -1104,15 +1110,18 @@ static us_status decompose_rank(Env &env, const us_coo &coo, const Plan &pa, con
     if (k < 1) k = 1;
     if (k > nrows) k = nrows;
     US_LAUNCH(env, "pick", 8.0, pick_kernel, 1, 1, (const uint32_t *)slen, k - 1, &flags->scalar[2]);
-    if (!read_flags(env, flags, &h)) return env.status;
-    if (flag_status(h) != US_OK) return flag_status(h);
-    K = h.scalar[2];
   }
+  // the cut K (if picked above), the size of part A and the longest row all come back in one read of the flags
+  const bool by_percentile = pred.kind == US_P_RANK_LT_PERCENTILE;
   US_LAUNCH(env, "clipped_len", 8.0 * nrows, clipped_len_kernel, ceil_div<int64_t>(nrows, 256), 256,
-            (const int32_t *)ptr, nrows, K, clip);
+            (const int32_t *)ptr, nrows, K, (const int32_t *)(by_percentile ? &flags->scalar[2] : nullptr), clip);
   exclusive_scan_i32(env, clip, ptr_a, nrows, &flags->scalar[1]);
+  US_LAUNCH(env, "max_row_len", 4.0 * nrows, max_len_kernel, one_counter_grid(nrows, 256), 256, (const int32_t *)ptr,
+            nrows, &flags->scalar[3]);
   if (!read_flags(env, flags, &h)) return env.status;
   if (flag_status(h) != US_OK) return flag_status(h);
+  if (by_percentile) K = h.scalar[2];
+  const int64_t longest = h.scalar[3];
   const int64_t na = h.scalar[1], nb = n - na;
   CooLists la = alloc_lists(env, na), lb = alloc_lists(env, nb);
   us_status st = env.status;
@@ -1127,7 +1136,10 @@ static us_status decompose_rank(Env &env, const us_coo &coo, const Plan &pa, con
       // the same flag block goes on (its duplicate flag may have been set by the split); sizes start from zero
       fill_u32(env, (uint32_t *)&flags->scalar[0], 4, 0u);
       if (!env.ok()) return env.status;
-      us_status s = build_from_sorted(env, p, d, coo.nrows, coo.ncols, cnt, l.r, l.c, l.v, flags, false, o);
+      Plan q = p;
+      // part A as ELL of automatic width: its rows hold min(length, K) entries, so the width is known here
+      if (&l == &la && q.pattern == P_ELL && q.ell_width == 0) q.ell_width = longest < K ? longest : K;
+      us_status s = build_from_sorted(env, q, d, coo.nrows, coo.ncols, cnt, l.r, l.c, l.v, flags, false, o, true);
       l = CooLists();  // ownership moved
       return s;
     }

@@ -90,15 +90,26 @@ __global__ __launch_bounds__(SCAN_T) void scan_reduce_kernel(const int32_t *in, 
   if (threadIdx.x == 0) partial[blockIdx.x] = total;
 }
 
-// single workgroup: exclusive scan of the per-tile sums in place, grand total to *total_dev
+// single workgroup: exclusive scan of the per-tile sums in place, grand total to *total_dev.
+// Every thread takes SP_IPT consecutive sums per round, so 24,000 of them are three rounds.
+constexpr int SP_IPT = 8;
 __global__ __launch_bounds__(1024) void scan_partials_kernel(uint32_t *partial, int64_t nb, int32_t *total_dev) {
   __shared__ uint32_t s_wave[1024 / 64 + 1];
   uint32_t carry = 0;
-  for (int64_t base = 0; base < nb; base += 1024) {
-    int64_t i = base + threadIdx.x;
-    uint32_t v = i < nb ? partial[i] : 0u, total;
-    uint32_t ex = block_exclusive_sum<1024>(v, s_wave, &total);
-    if (i < nb) partial[i] = ex + carry;
+  for (int64_t base = 0; base < nb; base += 1024 * SP_IPT) {
+    const int64_t i0 = base + (int64_t)threadIdx.x * SP_IPT;
+    uint32_t v[SP_IPT], s = 0, total;
+#pragma unroll
+    for (int k = 0; k < SP_IPT; ++k) {
+      v[k] = i0 + k < nb ? partial[i0 + k] : 0u;
+      s += v[k];
+    }
+    uint32_t ex = block_exclusive_sum<1024>(s, s_wave, &total) + carry;
+#pragma unroll
+    for (int k = 0; k < SP_IPT; ++k) {
+      if (i0 + k < nb) partial[i0 + k] = ex;
+      ex += v[k];
+    }
     carry += total;
   }
   if (threadIdx.x == 0 && total_dev) *total_dev = (int32_t)carry;
