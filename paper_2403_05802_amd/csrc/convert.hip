@@ -200,6 +200,30 @@ static KeySpec rowcol_keyspec(const us_coo &coo, bool swapped) {
   return ks;
 }
 
+// Gives f (shape already set) the levels of an ELL tensor of width K with every slot empty: column -1, value 0.
+static bool ell_shell(Env &env, us_formatted *f, int64_t K) {
+  const int64_t slots = K * f->nrows;
+  int32_t *ecol = env.owned<int32_t>(slots);
+  float *ev = env.owned<float>(slots);
+  f->nlevels = 3;
+  f->level[0].size = K; f->level[1].size = f->nrows;
+  f->level[2].idx = ecol; f->level[2].nidx = slots;
+  f->val = ev; f->nval = slots; f->nmajor = K;
+  if (!env.ok()) return false;
+  fill_u32(env, (uint32_t *)ecol, slots, 0xFFFFFFFFu);
+  fill_u32(env, (uint32_t *)ev, slots, 0u);
+  return true;
+}
+
+static us_formatted *new_empty_ell(Env &env, const us_format_desc &desc, int64_t nrows, int64_t ncols, int64_t nnz,
+                                   int64_t K) {
+  us_formatted *f = new us_formatted();
+  f->desc = desc; f->pattern = P_ELL; f->swapped = false;
+  f->nrows = nrows; f->ncols = ncols; f->nnz = nnz;
+  if (!ell_shell(env, f, K)) { free_formatted(env, f); return nullptr; }
+  return f;
+}
+
 // Build COO / CSR / DCSR / ELL from entries already sorted by (major, minor).  `major` is a
 // temporary unless the format keeps it (COO); `minor` and `val` are owned arrays of nnz entries
 // that move into the result (or are released when the format re-lays them out: ELL).
@@ -249,8 +273,8 @@ static us_status build_from_sorted(Env &env, const Plan &plan, const us_format_d
   if (!env.ok()) return finish(env.status);
   // one pass over the entries gives both ptr and the duplicate check; with fewer entries than groups the
   // runs of empty groups are long and a binary search per group is the quicker way to ptr
-  if (check_dups && nnz >= nmaj) {
-    group_ptr_unique(env, major, minor, nnz, nmaj, ptr, true, flags);
+  if (nnz >= nmaj) {
+    group_ptr_unique(env, major, minor, nnz, nmaj, ptr, check_dups, flags);
   } else {
     if (check_dups && nnz > 1)
       US_LAUNCH(env, "check_unique", 8.0 * nnz, check_unique_unpacked_kernel, ceil_div<int64_t>(nnz, 256), 256,
@@ -308,16 +332,9 @@ static us_status build_from_sorted(Env &env, const Plan &plan, const us_format_d
       if (K == 0) K = h.scalar[0];
     }
     if (K * nrows >= (1ll << 31)) return finish(US_ERR_OVERFLOW);
-    const int64_t slots = K * nrows;
-    int32_t *ecol = env.owned<int32_t>(slots);
-    float *ev = env.owned<float>(slots);
-    f->nlevels = 3;
-    f->level[0].size = K; f->level[1].size = nrows;
-    f->level[2].idx = ecol; f->level[2].nidx = slots;
-    f->val = ev; f->nval = slots; f->nmajor = K;
-    if (!env.ok()) return finish(env.status);
-    fill_u32(env, (uint32_t *)ecol, slots, 0xFFFFFFFFu);
-    fill_u32(env, (uint32_t *)ev, slots, 0u);
+    if (!ell_shell(env, f, K)) return finish(env.status);
+    int32_t *ecol = f->level[2].idx;
+    float *ev = f->val;
     if (nnz > 0)
       US_LAUNCH(env, "ell_scatter", 16.0 * nnz + 8.0 * nnz, ell_scatter_kernel, ceil_div<int64_t>(nnz, 256), 256,
                 (const int32_t *)major, (const int32_t *)minor, (const float *)val, (const int32_t *)ptr, nnz,
@@ -1011,21 +1028,28 @@ __global__ __launch_bounds__(256) void clipped_len_kernel(const int32_t *ptr, in
   if (g < n) { int64_t l = ptr[g + 1] - ptr[g]; out[g] = (int32_t)(l < K ? l : K); }
 }
 
-// stable split of the sorted list by rank-in-row: rank < K -> part A, else part B; on the way, equal
-// neighbours are flagged as duplicates if the sort has not looked for them (the two copies of a
-// coordinate may end up in different parts, so this is the last place that sees them side by side)
+// stable split of the sorted list by rank-in-row: rank < K -> part A, else part B.  (Equal neighbours have
+// been looked for before: the two copies of a coordinate may end up in different parts.)
+// ell_col != null: part A is an ELL slab of width ell_width over nrows rows and takes its entries directly
+// (slot rank * nrows + row) instead of the list (ar, ac, av).
 __global__ __launch_bounds__(256) void rank_split_kernel(const int32_t *major, const int32_t *minor, const float *val,
                                                         const int32_t *ptr, const int32_t *ptr_a, int64_t n,
                                                         int64_t K, int32_t *ar, int32_t *ac, float *av, int32_t *br,
-                                                        int32_t *bc, float *bv, int check_dups, Flags *flags) {
+                                                        int32_t *bc, float *bv, int32_t *ell_col, float *ell_val,
+                                                        int64_t ell_width, int64_t nrows, Flags *flags) {
   int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= n) return;
   const int32_t r = major[i], c = minor[i];
-  if (check_dups && i > 0 && major[i - 1] == r && minor[i - 1] == c) flags->duplicate = 1;
   int64_t rank = i - ptr[r];
   if (rank < K) {
-    int64_t p = ptr_a[r] + rank;
-    ar[p] = r; ac[p] = c; av[p] = val[i];
+    if (ell_col) {
+      if (rank >= ell_width) { flags->ell_overflow = 1; return; }
+      const int64_t slot = rank * nrows + r;
+      ell_col[slot] = c; ell_val[slot] = val[i];
+    } else {
+      int64_t p = ptr_a[r] + rank;
+      ar[p] = r; ac[p] = c; av[p] = val[i];
+    }
   } else {
     int64_t p = (int64_t)(ptr[r] - ptr_a[r]) + (rank - K);
     br[p] = r; bc[p] = c; bv[p] = val[i];
@@ -1095,7 +1119,14 @@ static us_status decompose_rank(Env &env, const us_coo &coo, const Plan &pa, con
   SortOut so{};
   so.major = major; so.minor = minor; so.val = val;
   const bool checked = sort_coo(env, coo.row, coo.col, coo.val, n, rowcol_keyspec(coo, false), so, flags);
-  lower_bound_ptr(env, major, n, nrows, ptr);
+  if (n >= nrows) {
+    group_ptr_unique(env, major, minor, n, nrows, ptr, !checked, flags);
+  } else {
+    if (!checked && n > 1)
+      US_LAUNCH(env, "check_unique", 8.0 * n, check_unique_unpacked_kernel, ceil_div<int64_t>(n, 256), 256,
+                (const int32_t *)major, (const int32_t *)minor, n, flags);
+    lower_bound_ptr(env, major, n, nrows, ptr);
+  }
   Flags h{};
   int64_t K = pred.abs;
   if (pred.kind == US_P_RANK_LT_PERCENTILE) {
@@ -1123,12 +1154,23 @@ static us_status decompose_rank(Env &env, const us_coo &coo, const Plan &pa, con
   if (by_percentile) K = h.scalar[2];
   const int64_t longest = h.scalar[3];
   const int64_t na = h.scalar[1], nb = n - na;
-  CooLists la = alloc_lists(env, na), lb = alloc_lists(env, nb);
+  // part A as row-major ELL: the split writes its slab directly (its rows hold min(length, K) entries, which
+  // gives the automatic width); any other format gets a sorted list first
+  us_formatted *ell = nullptr;
+  int64_t ell_width = 0;
+  if (pa.pattern == P_ELL && !pa.swapped) {
+    ell_width = pa.ell_width > 0 ? pa.ell_width : (longest < K ? longest : K);
+    if (ell_width * nrows >= (1ll << 31)) return US_ERR_OVERFLOW;
+    ell = new_empty_ell(env, da, nrows, coo.ncols, na, ell_width);
+    if (!ell) return env.status;
+  }
+  CooLists la = ell ? CooLists() : alloc_lists(env, na), lb = alloc_lists(env, nb);
   us_status st = env.status;
   if (st == US_OK && n > 0) {
     US_LAUNCH(env, "rank_split", 16.0 * n + 12.0 * n, rank_split_kernel, ceil_div<int64_t>(n, 256), 256,
               (const int32_t *)major, (const int32_t *)minor, (const float *)val, (const int32_t *)ptr,
-              (const int32_t *)ptr_a, n, K, la.r, la.c, la.v, lb.r, lb.c, lb.v, checked ? 0 : 1, flags);
+              (const int32_t *)ptr_a, n, K, la.r, la.c, la.v, lb.r, lb.c, lb.v,
+              ell ? ell->level[2].idx : (int32_t *)nullptr, ell ? ell->val : (float *)nullptr, ell_width, nrows, flags);
     st = env.status;
   }
   auto finish_part = [&](const Plan &p, const us_format_desc &d, CooLists &l, int64_t cnt, us_formatted **o) {
@@ -1149,8 +1191,11 @@ static us_status decompose_rank(Env &env, const us_coo &coo, const Plan &pa, con
     us_coo c{coo.nrows, coo.ncols, cnt, l.r, l.c, l.v};
     return convert_with_plan(env, c, p, d, o);
   };
-  if (st == US_OK) st = finish_part(pa, da, la, na, oa);
-  if (st == US_OK) st = finish_part(pb, db, lb, nb, ob);
+  if (st == US_OK && !ell) st = finish_part(pa, da, la, na, oa);
+  if (st == US_OK) st = finish_part(pb, db, lb, nb, ob);   // ends with a read of the flags: covers the slab's overflow flag too
+  if (ell) {
+    if (st == US_OK) *oa = ell; else free_formatted(env, ell);
+  }
   env.sync();
   free_lists(env, la);
   free_lists(env, lb);
