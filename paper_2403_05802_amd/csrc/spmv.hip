@@ -58,7 +58,9 @@ __global__ __launch_bounds__(MP_T) void csr_spmv_kernel(const int32_t *ptr, cons
   const int64_t r0 = split[blockIdx.x], r1 = split[blockIdx.x + 1];
   const int64_t z0 = diag0 - r0, z1 = diag1 - r1;
   const int nr = (int)(r1 - r0), nz = (int)(z1 - z0);
-  {  // all index/value loads first, then all gathers of x: two round trips instead of sixteen
+  {  // all index/value loads first, then all gathers of x: two round trips instead of sixteen.
+     // (Non-temporal loads of the streamed arrays were measured: 7 % faster right after a conversion, 16 %
+     // slower when the product is repeated and the matrix would otherwise stay in the memory-side cache.)
     int32_t ci[MP_IPT];
     float vv[MP_IPT], xv[MP_IPT];
     int32_t re[MP_IPT];
