@@ -25,7 +25,8 @@
 // What the counters say about the scatter kernel (16.8 M entries, 100 us): ~810 VALU instructions per
 // wavefront = 42 % of the VALU issue slots, waves waiting twice as long as they issue, 6 waves per SIMD
 // (74 VGPRs, 43 KB of LDS per workgroup).  Forcing 8 waves per SIMD (16-bit wave counters for the LDS,
-// 64 VGPRs) spilled 24 registers and took 157 us.
+// 64 VGPRs) spilled 24 registers and took 157 us; 8192-entry tiles (16 entries per thread, runs twice as
+// long, 4 waves per SIMD) took 123 us.
 #include "common.h"
 #include "device.h"
 
