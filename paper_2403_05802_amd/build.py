@@ -40,5 +40,24 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
+def build_c_example(verbose: bool = True) -> str:
+    """tests/c_abi/abi_example: a plain C program (gcc, no PyTorch) that drives the library through
+    include/unisparse.h; the GPU tests run it."""
+    src = os.path.join(ROOT, "tests", "c_abi", "abi_example.c")
+    exe = os.path.join(ROOT, "tests", "c_abi", "abi_example")
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c11", "-Wall", "-Werror", "-O1", "-I", os.path.join(rocm, "include"),
+           "-I", os.path.join(ROOT, "include"), src, "-o", exe, "-L", HERE, "-lunisparse_hip",
+           "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/../../paper_2403_05802_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("gcc failed for abi_example.c:\n" + r.stderr)
+    if verbose:
+        print("built", exe)
+    return exe
+
+
 if __name__ == "__main__":
     build()
+    build_c_example()
