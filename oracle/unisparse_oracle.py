@@ -32,9 +32,15 @@ listed in the design notes of the repository):
     (the enum query of Figure 7), exposed as a size K (K = longest row unless a width is
     fixed); the column level that follows holds one index per (slot,row) with pad = -1
     and pad value +0.0;
-  * parity unpinned by the paper: the pad column (-1), percentile-based ELL width, and
-    the "fraction of the in-bounds diagonal length" predicate are this repository's
-    readings, pinned only by brute-force tests.
+  * CISR-plus (Section 7.2.4, its printed encoding): the indirect level is built from three
+    queries -- sum (entries per row), reorder (rows with the most entries first; equal rows in
+    ascending row order) and schedule into N partitions; "in a balanced manner" is all the text
+    says about schedule, and it is read here as dealing: the k-th row of that order goes to
+    partition k mod N.  The level is untouched by trim(1,2), hence a size N; rows and columns
+    below it are compressed levels (a row level with a ptr over the N partitions);
+  * parity unpinned by the paper: the pad column (-1), percentile-based ELL width, the
+    "fraction of the in-bounds diagonal length" predicate and the dealing rule of schedule
+    are this repository's readings, pinned only by brute-force tests.
 """
 from __future__ import annotations
 
@@ -45,7 +51,7 @@ import numpy as np
 
 # --------------------------------------------------------------------------- descriptors
 
-AFFINE, DIV, MOD, ENUM = "affine", "div", "mod", "enum"
+AFFINE, DIV, MOD, ENUM, SCHED = "affine", "div", "mod", "enum", "sched"
 
 
 @dataclass(frozen=True)
@@ -57,6 +63,9 @@ class Expr:
     mod   : (c0*d0 + c1*d1 + c) % factor       (non-negative)
     enum  : indirect level: rank of the entry inside its group (group key = the affine
             part, e.g. d0) when the group is traversed by ascending `traverse` dim
+    sched : indirect level: the partition (0..factor-1) that the entry's group (key = the
+            affine part, e.g. d0) is scheduled to: groups ordered by size, largest first
+            (sum + reorder queries), then dealt to `factor` partitions (schedule query)
     """
     kind: str
     c0: int = 0
@@ -72,6 +81,7 @@ def diag() -> Expr: return Expr(AFFINE, -1, 1)          # d1 - d0
 def div(dim: int, f: int) -> Expr: return Expr(DIV, 1 - dim, dim, 0, f)
 def mod(dim: int, f: int) -> Expr: return Expr(MOD, 1 - dim, dim, 0, f)
 def enum_by_row() -> Expr: return Expr(ENUM, 1, 0, 0, 1, traverse=1)
+def sched_rows(n: int) -> Expr: return Expr(SCHED, 1, 0, 0, n)
 
 
 @dataclass(frozen=True)
@@ -100,6 +110,9 @@ def BDIA(b: int) -> FormatDesc:
     return FormatDesc((div(0, b), diag(), mod(0, b)), (1, 1), (0,))
 def ELL(width: int = 0) -> FormatDesc:
     return FormatDesc((enum_by_row(), d0(), d1()), (0, 0), (0,), ell_width=width)
+def CISR_PLUS(n: int) -> FormatDesc:
+    """Section 7.2.4: (indirect(d0), d0, d1), merge(0,1), trim(1,2), n partitions."""
+    return FormatDesc((sched_rows(n), d0(), d1()), (1, 2), (0, 1))
 
 
 class OracleError(Exception):
@@ -154,6 +167,21 @@ def _group_rank(group: np.ndarray, order_key: np.ndarray) -> Tuple[np.ndarray, n
     return rank, size
 
 
+def _scheduled_partition(group: np.ndarray, nparts: int) -> np.ndarray:
+    """The three queries behind the indirect level of CISR-plus, one after the other.
+    sum:      entries per group (only groups that hold an entry exist);
+    reorder:  groups by descending size, equal sizes by ascending group index;
+    schedule: the k-th group of that order is dealt to partition k mod nparts.
+    Returns the partition of every entry."""
+    if nparts < 1:
+        raise OracleError("US_ERR_UNSUPPORTED_DESC", "number of partitions")
+    ids, inv, size = np.unique(group, return_inverse=True, return_counts=True)   # sum
+    order = np.lexsort((ids, -size))                                             # reorder
+    part_of_group = np.empty(ids.shape[0], dtype=np.int64)
+    part_of_group[order] = np.arange(ids.shape[0], dtype=np.int64) % nparts      # schedule
+    return part_of_group[inv.reshape(-1)]
+
+
 def eval_index_map(desc: FormatDesc, nrows: int, ncols: int, row: np.ndarray, col: np.ndarray
                    ) -> List[np.ndarray]:
     """Target tuple e = M(d0, d1) of every entry (Section 4.1.1), one int64 array per level."""
@@ -171,6 +199,8 @@ def eval_index_map(desc: FormatDesc, nrows: int, ncols: int, row: np.ndarray, co
         elif e.kind == ENUM:
             rank, _ = _group_rank(a, c if e.traverse == 1 else r)
             out.append(rank)
+        elif e.kind == SCHED:
+            out.append(_scheduled_partition(a, e.factor))
         else:
             raise OracleError("US_ERR_UNSUPPORTED_DESC", e.kind)
     return out
@@ -183,6 +213,8 @@ def _level_extent(desc: FormatDesc, L: int, nrows: int, ncols: int, eL: np.ndarr
         if desc.ell_width > 0:
             return 0, int(desc.ell_width)
         return 0, int(eL.max()) + 1 if eL.size else 0
+    if e.kind == SCHED:
+        return 0, int(e.factor)
     lo, hi = _affine_range(e, nrows, ncols)
     if e.kind == AFFINE:
         return lo, hi - lo + 1

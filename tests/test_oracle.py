@@ -12,6 +12,7 @@ ALL_FORMATS = [
     ("COO", O.COO()), ("CSR", O.CSR()), ("DCSR", O.DCSR()), ("CSC", O.CSC()), ("DCSC", O.DCSC()),
     ("DIA", O.DIA()), ("DIAv", O.DIA_VARIANT()), ("BCSR2", O.BCSR(2)), ("BCSR4", O.BCSR(4)),
     ("BCSR2x3", O.BCSR(2, 3)), ("CSB2", O.CSB(2)), ("ELL", O.ELL()), ("BDIA3", O.BDIA(3)),
+    ("CISRplus3", O.CISR_PLUS(3)),
 ]
 
 
@@ -378,3 +379,77 @@ def test_decompose_blocked_groups_brute_force(seed):
         assert bool(m[t]) == (cnt >= thld)
     assert np.array_equal(O.to_dense(qa) + O.to_dense(qb), A)
     assert qa.val.size % (bh * bw) == 0 and qa.nnz + qb.nnz == r.size
+
+
+# ------------------------------------------------------------------ CISR-plus (Section 7.2.4): sum, reorder, schedule
+def brute_cisr_plus(nr, A, nparts):
+    """Plain loops: rows with entries, most entries first (ties: lower row first), dealt to the partitions
+    in turn; inside a partition rows ascending, inside a row columns ascending."""
+    lens = [(int(np.count_nonzero(A[i])), i) for i in range(nr)]
+    order = sorted([t for t in lens if t[0] > 0], key=lambda t: (-t[0], t[1]))
+    parts = [[] for _ in range(nparts)]
+    for k, (_, i) in enumerate(order):
+        parts[k % nparts].append(i)
+    ptr1, rows, ptr2, cols, vals = [0], [], [0], [], []
+    for p in parts:
+        for i in sorted(p):
+            rows.append(i)
+            for j in np.flatnonzero(A[i]):
+                cols.append(int(j)); vals.append(A[i, j])
+            ptr2.append(len(cols))
+        ptr1.append(len(rows))
+    return ptr1, rows, ptr2, cols, vals, parts
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_cisr_plus_brute_force(seed):
+    rng = np.random.default_rng(100 + seed)
+    nr, nc = int(rng.integers(1, 40)), int(rng.integers(1, 30))
+    row, col, val = random_coo(rng, nr, nc, int(rng.integers(0, nr * nc // 2 + 1)))
+    if seed % 2 == 0 and row.size:   # skew: pile extra entries into two rows
+        extra = [(int(r0), j) for r0 in rng.choice(nr, size=min(2, nr), replace=False) for j in range(nc)]
+        have = set(zip(row.tolist(), col.tolist()))
+        extra = [e for e in extra if e not in have]
+        row = np.concatenate([row, np.array([e[0] for e in extra], np.int32)])
+        col = np.concatenate([col, np.array([e[1] for e in extra], np.int32)])
+        val = np.concatenate([val, rng.uniform(0.5, 1, len(extra)).astype(np.float32)])
+    A = dense_of(nr, nc, row, col, val)
+    for nparts in (1, 2, 3, 7, 64):
+        f = O.convert(nr, nc, row, col, val, O.CISR_PLUS(nparts))
+        ptr1, rows, ptr2, cols, vals, parts = brute_cisr_plus(nr, A, nparts)
+        assert [l.kind for l in f.levels] == ["dense", "compressed", "compressed"]
+        assert f.levels[0].size == nparts
+        assert f.levels[1].ptr.tolist() == ptr1 and f.levels[1].idx.tolist() == rows
+        assert f.levels[2].ptr.tolist() == ptr2 and f.levels[2].idx.tolist() == cols
+        assert np.array_equal(f.val, np.array(vals, np.float32))
+        # what dealing a descending order guarantees: partition sizes differ by at most one row, and an
+        # earlier partition never holds fewer entries than a later one
+        nrows_p = [len(p) for p in parts]
+        loads = [sum(int(np.count_nonzero(A[i])) for i in p) for p in parts]
+        assert max(nrows_p) - min(nrows_p) <= 1
+        assert all(loads[j] >= loads[j + 1] for j in range(nparts - 1))
+        assert np.allclose(O.to_dense(f), A)
+        x = rng.uniform(-1, 1, nc)
+        assert np.allclose(O.spmv(f, x), A @ x)
+
+
+def test_cisr_plus_with_one_partition_is_dcsr_under_a_root():
+    rng = np.random.default_rng(5)
+    row, col, val = random_coo(rng, 30, 20, 90)
+    f = O.convert(30, 20, row, col, val, O.CISR_PLUS(1))
+    d = O.convert(30, 20, row, col, val, O.DCSR())
+    assert f.levels[1].ptr.tolist() == [0, d.levels[0].idx.size]
+    assert np.array_equal(f.levels[1].idx, d.levels[0].idx)
+    assert np.array_equal(f.levels[2].ptr, d.levels[1].ptr) and np.array_equal(f.levels[2].idx, d.levels[1].idx)
+    assert np.array_equal(f.val, d.val)
+
+
+def test_cisr_plus_on_the_example(example_A):
+    """Matrix A with two partitions, by hand: rows by entries 2 (3 entries), then 0, 1, 4 (one each) ->
+    partitions {2, 1} and {0, 4}; stored by ascending row inside a partition."""
+    nr, nc, r, c, v = shuffled_A(example_A, 3)
+    f = O.convert(nr, nc, r, c, v, O.CISR_PLUS(2))
+    assert f.levels[0].size == 2
+    assert f.levels[1].ptr.tolist() == [0, 2, 4] and f.levels[1].idx.tolist() == [1, 2, 0, 4]
+    assert f.levels[2].ptr.tolist() == [0, 1, 4, 5, 6] and f.levels[2].idx.tolist() == [1, 1, 2, 3, 0, 3]
+    assert f.val.tolist() == [2, 3, 4, 5, 1, 6]
