@@ -281,6 +281,12 @@ def other_workloads(B, W, torch, ctx, up, K, Wm):
     x = up(W.dense_operand(1, m.ncols)); y = torch.empty(m.nrows, device=dev)
     run("config1_csr_spmv", m, lambda r, c, v: [B.us_convert(ctx, m.nrows, m.ncols, r, c, v, CSR)],
         lambda p: B.us_spmv(ctx, p[0], x, y), 2.0 * m.nnz, lambda p: 20.0 * m.nnz + 4.0 * m.nrows)
+    # config 2 once more, into the scheduled layout of Section 7.2.4 (1024 partitions, its core count) + SpMV
+    m = W.cfg2_powerlaw()
+    x = up(W.dense_operand(2, m.ncols)); y = torch.empty(m.nrows, device=dev)
+    CP = B.us_desc_preset(B.US_F_CISR_PLUS, 1024)
+    run("config2_cisr_plus_spmv", m, lambda r, c, v: [B.us_convert(ctx, m.nrows, m.ncols, r, c, v, CP)],
+        lambda p: B.us_spmv(ctx, p[0], x, y), 2.0 * m.nnz, lambda p: 20.0 * m.nnz + 8.0 * m.nrows)
     # config 3
     m = W.cfg3_banded()
     x = up(W.dense_operand(3, m.ncols)); y = torch.empty(m.nrows, device=dev)

@@ -64,8 +64,10 @@ typedef struct us_coo {
 
 /* One destination expression of an index map (Figure 5a): e = c0*d0 + c1*d1 + c, optionally
  * followed by "/ factor" (floor) or "% factor", or the indirect function of ELL (Figure 7:
- * sum + enum grouped by the affine part, traversed by the other dimension). */
-enum { US_E_AFFINE = 0, US_E_DIV = 1, US_E_MOD = 2, US_E_INDIRECT_ENUM = 3 };
+ * sum + enum grouped by the affine part, traversed by the other dimension), or the indirect function
+ * of CISR-plus (Section 7.2.4: sum + reorder + schedule of the groups of the affine part into `factor`
+ * partitions). */
+enum { US_E_AFFINE = 0, US_E_DIV = 1, US_E_MOD = 2, US_E_INDIRECT_ENUM = 3, US_E_INDIRECT_SCHEDULE = 4 };
 typedef struct us_expr {
   int32_t kind;
   int32_t c0, c1, c;
@@ -81,7 +83,12 @@ typedef struct us_expr {
  *   ELL  (indirect(d1),d0,d1) merge(0) trim(0,0)
  *   BDIA (d0/b,d1-d0,d0%b) merge(0) trim(1,1), 1 <= b <= 16 (the blocked DIA of Figure 3c)
  *   CSB  (d0/bh,d1/bw,d0%bh,d1%bw) merge(1) trim(2,3), 1 <= bh,bw <= 65536 and fewer than 2^31 blocks:
- *        a dense grid of blocks (two sizes), one ptr over the blocks, (d0%bh, d1%bw) per entry        */
+ *        a dense grid of blocks (two sizes), one ptr over the blocks, (d0%bh, d1%bw) per entry
+ *   CISR-plus (schedule(d0),d0,d1) merge(0,1) trim(1,2), 1 <= partitions <= 65536 (Section 7.2.4): rows that
+ *        hold entries are ordered by their number of entries, most first (equal ones by ascending row), and
+ *        dealt to the partitions in turn (the k-th goes to partition k mod P: this library's reading of
+ *        "schedule ... in a balanced manner"); stored as a size P, a row level (ptr over the partitions, row
+ *        indices ascending inside a partition) and a column level (ptr over the stored rows, column indices) */
 typedef struct us_format_desc {
   int32_t nlevels;
   us_expr level[4];
@@ -90,9 +97,10 @@ typedef struct us_format_desc {
   int64_t ell_width;      /* ELL only: 0 = longest row, >0 = fixed number of slots */
 } us_format_desc;
 
-enum { US_F_COO = 0, US_F_CSR, US_F_DCSR, US_F_CSC, US_F_DCSC, US_F_DIA, US_F_DIA_VARIANT, US_F_BCSR, US_F_ELL, US_F_BDIA, US_F_CSB };
+enum { US_F_COO = 0, US_F_CSR, US_F_DCSR, US_F_CSC, US_F_DCSC, US_F_DIA, US_F_DIA_VARIANT, US_F_BCSR, US_F_ELL, US_F_BDIA, US_F_CSB, US_F_CISR_PLUS };
 /* Fill *out with the encoding of Figure 7 (Figure 3c for BDIA) for `format`; b0,b1 = block
- * height,width (BCSR, CSB), b0 = block height (BDIA) or b0 = fixed width (ELL, 0 = longest row).  host pointers. */
+ * height,width (BCSR, CSB), b0 = block height (BDIA), b0 = fixed width (ELL, 0 = longest row) or b0 = number of
+ * partitions (CISR-plus).  host pointers. */
 us_status us_desc_preset(int32_t format, int64_t b0, int64_t b1, us_format_desc *out);
 
 /* Decomposition predicate: the `sum` query of Section 4.1.2 (groupBy map, stored entry -> 1)

@@ -20,9 +20,9 @@ US_OK = 0
 STATUS_NAMES = {0: "US_OK", -1: "US_ERR_NULL", -2: "US_ERR_SHAPE", -3: "US_ERR_INDEX_RANGE",
                 -4: "US_ERR_UNSUPPORTED_DESC", -5: "US_ERR_DUPLICATE", -6: "US_ERR_ALLOC",
                 -7: "US_ERR_OVERFLOW", -8: "US_ERR_HIP", -9: "US_ERR_FORMAT_MISMATCH"}
-US_E_AFFINE, US_E_DIV, US_E_MOD, US_E_INDIRECT_ENUM = 0, 1, 2, 3
+US_E_AFFINE, US_E_DIV, US_E_MOD, US_E_INDIRECT_ENUM, US_E_INDIRECT_SCHEDULE = 0, 1, 2, 3, 4
 (US_F_COO, US_F_CSR, US_F_DCSR, US_F_CSC, US_F_DCSC, US_F_DIA, US_F_DIA_VARIANT, US_F_BCSR, US_F_ELL,
- US_F_BDIA, US_F_CSB) = range(11)
+ US_F_BDIA, US_F_CSB, US_F_CISR_PLUS) = range(12)
 US_P_SUM_GE_ABS, US_P_SUM_GE_FRAC_OF_CAPACITY, US_P_RANK_LT_ABS, US_P_RANK_LT_PERCENTILE = range(4)
 US_A_SIZE, US_A_PTR, US_A_IDX, US_A_VAL = range(4)
 

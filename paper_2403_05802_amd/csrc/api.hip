@@ -66,6 +66,12 @@ us_status us_desc_preset(int32_t format, int64_t b0, int64_t b1, us_format_desc 
       d.level[0] = mk(US_E_INDIRECT_ENUM, 1, 0, 1); d.level[1] = r; d.level[2] = c;
       d.trim_s = 0; d.trim_e = 0; d.merge_mask = 1; d.ell_width = b0;
       break;
+    case US_F_CISR_PLUS:
+      if (b0 < 1 || b0 > 65536) return US_ERR_UNSUPPORTED_DESC;
+      d.nlevels = 3;
+      d.level[0] = mk(US_E_INDIRECT_SCHEDULE, 1, 0, (int)b0); d.level[1] = r; d.level[2] = c;
+      d.trim_s = 1; d.trim_e = 2; d.merge_mask = 3;
+      break;
     default: return US_ERR_UNSUPPORTED_DESC;
   }
   *out = d;

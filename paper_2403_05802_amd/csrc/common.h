@@ -102,7 +102,7 @@ struct LaunchScope {  // brackets one kernel launch with events when profiling i
   } while (0)
 
 // ------------------------------------------------------------------ formatted tensor
-enum Pattern { P_COO = 0, P_CSR, P_DCSR, P_DIA, P_BCSR, P_ELL, P_BDIA, P_CSB };
+enum Pattern { P_COO = 0, P_CSR, P_DCSR, P_DIA, P_BCSR, P_ELL, P_BDIA, P_CSB, P_CISR };
 
 struct LevelStore {
   int64_t size = -1;      // extent of a dense level, -1 if none
@@ -121,7 +121,7 @@ struct us_formatted {
   us::LevelStore level[4];
   float *val = nullptr; int64_t nval = 0;
   // derived sizes
-  int64_t nmajor = 0;   // CSR: rows (cols if swapped); DCSR: stored rows; DIA: ndiag; BCSR/BDIA: block rows; ELL: K
+  int64_t nmajor = 0;   // CSR: rows (cols if swapped); DCSR, CISR-plus: stored rows; DIA: ndiag; BCSR/BDIA: block rows; ELL: K
   int64_t bh = 1, bw = 1, nblk = 0;   // BDIA: bh = block height, bw = 1, nblk = (block row, diagonal) nodes;
                                       // CSB: nblk = nmajor = blocks of the dense grid, level[1].size = blocks per block row
   // CSR / DCSR: where every SpMV tile starts on the merge path of row ends and non-zeros
@@ -133,6 +133,14 @@ struct us_formatted {
 };
 
 namespace us {
+
+// Compressed rows as the product kernels see them: CSR (every row), DCSR and CISR-plus (a list of stored rows).
+struct StoredRows { const int32_t *ptr, *idx, *row_ids; };
+inline StoredRows stored_rows(const us_formatted &A) {
+  if (A.pattern == P_CISR) return {A.level[2].ptr, A.level[2].idx, A.level[1].idx};
+  if (A.pattern == P_DCSR) return {A.level[1].ptr, A.level[1].idx, A.level[0].idx};
+  return {A.level[1].ptr, A.level[1].idx, nullptr};
+}
 
 // internal status: a fast path met an input it cannot take (Flags::retry): a bucket too large for the
 // in-LDS finish of the sort, or a value carrying the bit pattern that marks empty DIA slots.  The entry
@@ -184,6 +192,9 @@ bool sort_coo(Env &env, const int32_t *row, const int32_t *col, const float *val
 size_t sort_temp_bytes(int64_t nnz);
 // ascending sort of 32-bit keys
 void sort_u32(Env &env, const uint32_t *key, int64_t n, int bits, uint32_t *out, Flags *flags_dev);
+// the same, stable, with a 32-bit payload that travels with its key
+void sort_u32_payload(Env &env, const uint32_t *key, const uint32_t *payload, int64_t n, int bits, uint32_t *key_out,
+                      uint32_t *payload_out, Flags *flags_dev);
 // convert.hip
 us_status convert_impl(Env &env, const us_coo &coo, const us_format_desc &desc, us_formatted **out);
 us_status decompose_impl(Env &env, const us_coo &coo, const us_format_desc &da, const us_format_desc &db,

@@ -806,4 +806,14 @@ void sort_u32(Env &env, const uint32_t *key, int64_t n, int bits, uint32_t *out,
   sort_generic(env, IN_KEY32, nullptr, nullptr, key, dummy_in, n, ks, so, flags_dev);
 }
 
+void sort_u32_payload(Env &env, const uint32_t *key, const uint32_t *payload, int64_t n, int bits, uint32_t *key_out,
+                      uint32_t *payload_out, Flags *flags_dev) {
+  if (n <= 0) return;
+  KeySpec ks{};
+  ks.total_bits = bits;
+  SortOut so{};
+  so.key32 = key_out; so.val = (float *)payload_out;   // the value slot carries 32 bits untouched
+  sort_generic(env, IN_KEY32, nullptr, nullptr, key, (const float *)payload, n, ks, so, flags_dev);
+}
+
 }  // namespace us

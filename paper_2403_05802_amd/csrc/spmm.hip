@@ -486,24 +486,24 @@ us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, 
       }
       return env.status;
     case P_CSR:
-    case P_DCSR: {
-      const bool d = A.pattern == P_DCSR;
+    case P_DCSR:
+    case P_CISR: {
+      const StoredRows sr = stored_rows(A);
       if (A.swapped) {
         if (!accumulate) zero_rows(env, Y, A.nrows, N, ldy);
         if (env.ok() && A.nmajor > 0) {
           LaunchScope ls(env, "spmm_csc", 8.0 * A.nnz + xy);
           hipLaunchKernelGGL(csc_spmm_atomic_kernel, dim3((unsigned)ceil_div<int64_t>(A.nmajor, 4), (unsigned)ncb),
-                             dim3(256), 0, env.stream, (const int32_t *)A.level[1].ptr,
-                             (const int32_t *)A.level[1].idx, (const float *)A.val,
-                             (const int32_t *)(d ? A.level[0].idx : nullptr), A.nmajor, X, N, ldx, Y, ldy);
+                             dim3(256), 0, env.stream, sr.ptr, sr.idx, (const float *)A.val, sr.row_ids, A.nmajor, X, N,
+                             ldx, Y, ldy);
           env.check(hipGetLastError());
         }
         return env.status;
       }
       if (!accumulate) zero_rows(env, Y, A.nrows, N, ldy);
       if (A.nnz > 0) {
-        RowSrc rs{nullptr, A.level[1].ptr, d ? A.level[0].idx : nullptr, A.nmajor};
-        entry_balanced_spmm(env, A, rs, A.level[1].idx, "spmm_csr", vec, X, N, ldx, Y, ldy);
+        RowSrc rs{nullptr, sr.ptr, sr.row_ids, A.nmajor};
+        entry_balanced_spmm(env, A, rs, sr.idx, "spmm_csr", vec, X, N, ldx, Y, ldy);
       }
       return env.status;
     }

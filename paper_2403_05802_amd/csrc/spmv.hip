@@ -289,7 +289,7 @@ __global__ __launch_bounds__(256) void csb_spmv_atomic_kernel(const int32_t *ptr
 int64_t spmv_tiles(int64_t nmajor, int64_t nnz) { return ceil_div<int64_t>(nmajor + nnz, MP_TILE); }
 
 void spmv_prepare(Env &env, us_formatted *f, const int32_t *nmajor_dev, int64_t nmajor_cap) {
-  if (f->swapped || (f->pattern != P_CSR && f->pattern != P_DCSR)) return;
+  if (f->swapped || (f->pattern != P_CSR && f->pattern != P_DCSR && f->pattern != P_CISR)) return;
   const int64_t nmajor = nmajor_dev ? nmajor_cap : f->nmajor;
   const int64_t total = nmajor + f->nnz;
   if (total == 0) return;
@@ -298,28 +298,30 @@ void spmv_prepare(Env &env, us_formatted *f, const int32_t *nmajor_dev, int64_t 
   f->mp_tiles = nb;
   if (!env.ok()) return;
   US_LAUNCH(env, "spmv_split", 4.0 * (nb + 1), merge_path_split_kernel, ceil_div<int64_t>(nb + 1, 256), 256,
-            (const int32_t *)f->level[1].ptr, nmajor, f->nnz, nb, nmajor_dev, f->mp_split);
+            stored_rows(*f).ptr, nmajor, f->nnz, nb, nmajor_dev, f->mp_split);
 }
 
 us_status spmv_impl(Env &env, const us_formatted &A, const float *x, float *y, bool accumulate) {
   switch (A.pattern) {
     case P_CSR:
     case P_DCSR:
+    case P_CISR: {
+      const StoredRows sr = stored_rows(A);
       if (A.swapped) {
         if (!accumulate) fill_u32(env, (uint32_t *)y, A.nrows, 0u);
         if (A.nmajor > 0)
           US_LAUNCH(env, "spmv_csc", 16.0 * A.nnz, csc_spmv_atomic_kernel, ceil_div<int64_t>(A.nmajor, 256), 256,
-                    (const int32_t *)A.level[1].ptr, (const int32_t *)A.level[1].idx, (const float *)A.val,
-                    (const int32_t *)(A.pattern == P_DCSR ? A.level[0].idx : nullptr), A.nmajor, x, y);
+                    sr.ptr, sr.idx, (const float *)A.val, sr.row_ids, A.nmajor, x, y);
         return env.status;
       }
-      if (A.pattern == P_DCSR) {
+      if (sr.row_ids) {   // a list of stored rows: the others are zero
         if (!accumulate) fill_u32(env, (uint32_t *)y, A.nrows, 0u);
-        spmv_compressed(env, A, A.level[1].ptr, A.level[1].idx, A.val, A.level[0].idx, A.nmajor, A.nnz, x, y, true);
+        spmv_compressed(env, A, sr.ptr, sr.idx, A.val, sr.row_ids, A.nmajor, A.nnz, x, y, true);
         return env.status;
       }
-      spmv_compressed(env, A, A.level[1].ptr, A.level[1].idx, A.val, nullptr, A.nrows, A.nnz, x, y, accumulate);
+      spmv_compressed(env, A, sr.ptr, sr.idx, A.val, nullptr, A.nrows, A.nnz, x, y, accumulate);
       return env.status;
+    }
     case P_DIA:
       US_LAUNCH(env, "spmv_dia", 4.0 * A.nval + 8.0 * A.nrows + 4.0 * A.ncols, dia_spmv_kernel,
                 ceil_div<int64_t>(A.nrows, 256), 256, (const int32_t *)A.level[0].idx, (const float *)A.val,

@@ -5,7 +5,8 @@ import torch
 from oracle import unisparse_oracle as O
 from paper_2403_05802_amd import binding as B
 
-KIND = {O.AFFINE: B.US_E_AFFINE, O.DIV: B.US_E_DIV, O.MOD: B.US_E_MOD, O.ENUM: B.US_E_INDIRECT_ENUM}
+KIND = {O.AFFINE: B.US_E_AFFINE, O.DIV: B.US_E_DIV, O.MOD: B.US_E_MOD, O.ENUM: B.US_E_INDIRECT_ENUM,
+        O.SCHED: B.US_E_INDIRECT_SCHEDULE}
 PRED = {O.SUM_GE_ABS: B.US_P_SUM_GE_ABS, O.SUM_GE_FRAC_OF_CAPACITY: B.US_P_SUM_GE_FRAC_OF_CAPACITY,
         O.RANK_LT_ABS: B.US_P_RANK_LT_ABS, O.RANK_LT_PERCENTILE: B.US_P_RANK_LT_PERCENTILE}
 

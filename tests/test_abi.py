@@ -46,7 +46,12 @@ def test_status_strings_and_presets_need_no_gpu():
         [(B.US_E_DIV, 1, 0, 3), (B.US_E_AFFINE, -1, 1, b.level[1].factor), (B.US_E_MOD, 1, 0, 3)]
     k = B.us_desc_preset(B.US_F_CSB, 512, 256)        # same map as BCSR, merge(1), trim(2,3)
     assert k.nlevels == 4 and k.merge_mask == 2 and (k.trim_s, k.trim_e) == (2, 3) and k.level[3].factor == 256
+    z = B.us_desc_preset(B.US_F_CISR_PLUS, 1024, 0)   # Section 7.2.4: (schedule(d0), d0, d1), merge(0,1), trim(1,2)
+    assert z.nlevels == 3 and z.merge_mask == 3 and (z.trim_s, z.trim_e) == (1, 2)
+    assert (z.level[0].kind, z.level[0].c0, z.level[0].c1, z.level[0].factor) == (B.US_E_INDIRECT_SCHEDULE, 1, 0, 1024)
     import pytest
+    with pytest.raises(B.UnisparseError):
+        B.us_desc_preset(B.US_F_CISR_PLUS, 0, 0)
     with pytest.raises(B.UnisparseError):
         B.us_desc_preset(B.US_F_BCSR, 0, 4)
     with pytest.raises(B.UnisparseError):

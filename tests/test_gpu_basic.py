@@ -13,6 +13,7 @@ FORMATS = [
     ("DIA", O.DIA()), ("DIAv", O.DIA_VARIANT()), ("BCSR2", O.BCSR(2)), ("BCSR4", O.BCSR(4)),
     ("BCSR2x3", O.BCSR(2, 3)), ("BCSR8", O.BCSR(8)), ("ELL", O.ELL()), ("BDIA3", O.BDIA(3)), ("BDIA16", O.BDIA(16)),
     ("CSB2", O.CSB(2)), ("CSB5x3", O.CSB(5, 3)), ("CSB64x128", O.CSB(64, 128)),
+    ("CISRplus1", O.CISR_PLUS(1)), ("CISRplus3", O.CISR_PLUS(3)), ("CISRplus256", O.CISR_PLUS(256)),
 ]
 
 

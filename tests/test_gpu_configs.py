@@ -67,7 +67,7 @@ def test_cfg2_small_csr_dcsr(ctx):
         m = W.cfg2_powerlaw(n=1 << 14, target_nnz=1 << 18, max_len=3000, empty_frac=empty)
         d = coo_to_dev(m)
         x = W.dense_operand(2, m.ncols)
-        for desc in (O.CSR(), O.DCSR()):
+        for desc in (O.CSR(), O.DCSR(), O.CISR_PLUS(64)):
             o = O.convert(m.nrows, m.ncols, m.row, m.col, m.val, desc)
             g = B.us_convert(ctx, m.nrows, m.ncols, *d, us_desc_of(desc))
             assert_same_layout(g, o, f"cfg2s empty={empty}")
@@ -163,6 +163,13 @@ def test_cfg2_full(ctx):
         B.us_set_sort_lds_finish(None)
     assert torch.equal(g3.ptr(1), g.ptr(1)) and torch.equal(g3.idx(1), g.idx(1))
     assert torch.equal(g3.val().view(torch.int32), g.val().view(torch.int32))
+    # CISR-plus with 1024 partitions (the core count of Section 7.2.4) against the full oracle output
+    o4 = O.convert(m.nrows, m.ncols, m.row, m.col, m.val, O.CISR_PLUS(1024))
+    g4 = B.us_convert(ctx, m.nrows, m.ncols, *d, us_desc_of(O.CISR_PLUS(1024)))
+    assert_same_layout(g4, o4, "cfg2 CISR-plus")
+    rows_per_part = np.diff(o4.levels[1].ptr)
+    assert rows_per_part.max() - rows_per_part.min() <= 1
+    check_spmv(ctx, [g4], m, x)
 
 
 def test_cfg3_full(ctx):

@@ -28,7 +28,7 @@ def draw_case(seed):
         nr, nc = int(rng.integers(50, 5000)), int(rng.integers(50, 5000))
     cap = nr * nc
     nnz = int(min(cap, rng.choice([0, 1, 7, 300, 5000, 12000, 40000])))
-    fmt_kind = int(rng.integers(0, 10))
+    fmt_kind = int(rng.integers(0, 11))
     if fmt_kind in (5, 6) and nnz > 3000:     # dense diagonal slabs: keep the slab small by banding the entries
         offs = rng.choice(np.arange(-(nr - 1), nc), size=min(6, nr + nc - 1), replace=False)
         rows, cols = [], []
@@ -49,7 +49,8 @@ def draw_case(seed):
     v = rng.uniform(-1, 1, r.size).astype(np.float32); v[v == 0] = 0.25
     desc = [O.COO(), O.CSR(), O.DCSR(), O.CSC(), O.DCSC(), O.DIA(), O.DIA_VARIANT(),
             O.BCSR(int(rng.integers(1, 17)), int(rng.integers(1, 17))), O.BDIA(int(rng.integers(1, 17))),
-            O.CSB(int(rng.integers(1, 300)), int(rng.integers(1, 300)))][fmt_kind]
+            O.CSB(int(rng.integers(1, 300)), int(rng.integers(1, 300))),
+            O.CISR_PLUS(int(rng.choice([1, 2, 7, 64, 1000, 65536])))][fmt_kind]
     if fmt_kind == 8 and r.size > 3000 and nr * 1.0 * r.size > 2 ** 27:
         desc = O.CSR()                         # a scattered matrix in BDIA: nodes x block would be huge
     mode = [None, True, False][seed % 3]
