@@ -10,7 +10,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libunisparse_hip.so")
-SOURCES = ["primitives.hip", "sort.hip", "convert.hip", "spmv.hip", "spmm.hip", "api.hip"]
+SOURCES = ["primitives.hip", "sort.hip", "convert.hip", "sum_query.hip", "blocked.hip", "cisr.hip", "decompose.hip",
+           "spmv.hip", "spmm.hip", "api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=default",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
