@@ -207,6 +207,31 @@ __global__ __launch_bounds__(256) void radix_scan_top_kernel(uint32_t *chunk, ui
   if (lane == 0) dtotal[d] = carry;
 }
 
+// Both scans in one workgroup for inputs of at most RS_SMALL tiles (one launch less per digit pass, which is
+// what a conversion of a few hundred thousand entries spends its time on): thread d holds digit d of every tile.
+constexpr int RS_SMALL = 64;
+__global__ __launch_bounds__(RS_BINS) void radix_scan_small_kernel(uint32_t *hist, uint32_t *chunk, uint32_t *dtotal,
+                                                                  uint32_t nblocks, uint32_t nchunks) {
+  const uint32_t d = threadIdx.x;
+  uint32_t v[RS_SMALL];
+#pragma unroll
+  for (int t = 0; t < RS_SMALL; ++t) v[t] = (uint32_t)t < nblocks ? hist[(size_t)t * RS_BINS + d] : 0u;
+  uint32_t before_chunk = 0, run = 0;
+#pragma unroll
+  for (int t = 0; t < RS_SMALL; ++t) {
+    if ((uint32_t)t < nblocks) {
+      if (t % RS_CHUNK == 0) {
+        before_chunk += run;
+        run = 0;
+        chunk[(size_t)d * nchunks + t / RS_CHUNK] = before_chunk;
+      }
+      hist[(size_t)t * RS_BINS + d] = run;
+      run += v[t];
+    }
+  }
+  dtotal[d] = before_chunk + run;
+}
+
 template <int IN, int OUT>
 __global__ __launch_bounds__(RS_T) void radix_scatter_kernel(PassArgs a) {
   __shared__ uint32_t s_cnt[RS_NW][RS_BINS];  // per-wave digit counts, then per-wave bases
@@ -740,10 +765,15 @@ static bool sort_generic(Env &env, int in_mode, const int32_t *row, const int32_
     if (in == IN_COO) launch_hist<IN_COO>(env, a, (a.hist_minor_only ? 4.0 : 8.0) * nnz);
     else if (in == IN_KEY32) launch_hist<IN_KEY32>(env, a, 4.0 * nnz);
     else launch_hist<IN_SPLIT>(env, a, 1.0 * nnz);
-    US_LAUNCH(env, "radix_scan_chunk", 8.0 * RS_BINS * nblocks, radix_scan_chunk_kernel, nchunks, RS_BINS, hist, chunk,
-              nblocks);
-    US_LAUNCH(env, "radix_scan_top", 8.0 * RS_BINS * nchunks, radix_scan_top_kernel, RS_BINS / 4, 256, chunk, nchunks,
-              dtotal);
+    if (nblocks <= (uint32_t)RS_SMALL) {
+      US_LAUNCH(env, "radix_scan_small", 8.0 * RS_BINS * nblocks, radix_scan_small_kernel, 1, RS_BINS, hist, chunk, dtotal,
+                nblocks, nchunks);
+    } else {
+      US_LAUNCH(env, "radix_scan_chunk", 8.0 * RS_BINS * nblocks, radix_scan_chunk_kernel, nchunks, RS_BINS, hist, chunk,
+                nblocks);
+      US_LAUNCH(env, "radix_scan_top", 8.0 * RS_BINS * nchunks, radix_scan_top_kernel, RS_BINS / 4, 256, chunk, nchunks,
+                dtotal);
+    }
     const double bytes = (in_key + 4.0 + out_key + 4.0) * nnz;
     if (in == IN_COO) launch_scatter_out<IN_COO>(env, a, om, bytes);
     else if (in == IN_KEY32) launch_scatter_out<IN_KEY32>(env, a, om, bytes);
