@@ -170,6 +170,35 @@ __global__ __launch_bounds__(256) void node_keep_kernel(const int32_t *head, con
   keep[i] = (int64_t)(start[g + 1] - start[g]) >= thld ? 1 : 0;
 }
 
+// The same decision without the run tables when a node cannot hold more than `width` entries (a blocked
+// diagonal piece holds at most b, a bh x bw block bh*bw): every entry counts its run by looking at most
+// width - 1 neighbours to either side (cached reads), and equal neighbours are flagged on the way.
+constexpr int NK_T = 256, NK_IPT = 4, NK_TILE = NK_T * NK_IPT, NK_HALO = 15;
+__global__ __launch_bounds__(NK_T) void node_keep_window_kernel(const uint64_t *key, int64_t n, int ih_bits, int width,
+                                                               int64_t thld, int32_t *keep, Flags *flags) {
+  __shared__ uint64_t s_key[NK_TILE + 2 * NK_HALO];   // the tile's keys with width - 1 <= NK_HALO neighbours either side
+  const int64_t i0 = (int64_t)blockIdx.x * NK_TILE - NK_HALO;
+  for (int t = threadIdx.x; t < NK_TILE + 2 * NK_HALO; t += NK_T) {
+    const int64_t i = i0 + t;
+    s_key[t] = (i >= 0 && i < n) ? key[i] : 0ull;
+  }
+  __syncthreads();
+  bool dup = false;
+#pragma unroll
+  for (int k = 0; k < NK_IPT; ++k) {
+    const int t = NK_HALO + k * NK_T + threadIdx.x;
+    const int64_t i = i0 + t;
+    if (i >= n) continue;
+    const uint64_t cur = s_key[t], node = cur >> ih_bits;
+    dup |= i > 0 && s_key[t - 1] == cur;
+    int count = 1;
+    for (int d = 1; d < width && i - d >= 0 && (s_key[t - d] >> ih_bits) == node; ++d) ++count;
+    for (int d = 1; d < width && i + d < n && (s_key[t + d] >> ih_bits) == node; ++d) ++count;
+    keep[i] = count >= thld ? 1 : 0;
+  }
+  if (dup) flags->duplicate = 1;
+}
+
 __global__ __launch_bounds__(256) void node_split_kernel(const uint64_t *key, const float *val, const int32_t *keep,
                                                         const int32_t *pos_a, int64_t n, KeySpec ks, uint64_t *key_a,
                                                         float *val_a, CooLists la, CooLists lb) {
@@ -201,7 +230,6 @@ static us_status decompose_blocked(Env &env, const us_coo &coo, const Plan &pa, 
   const bool direct = pa.pattern == pg.pattern && pa.bh == pg.bh && pa.bw == pg.bw;
   uint64_t *skey = env.temp<uint64_t>(n);
   float *sval = env.temp<float>(n);
-  int32_t *head = env.temp<int32_t>(n), *pos = env.temp<int32_t>(n), *start = env.temp<int32_t>(n + 1);
   int32_t *keep = env.temp<int32_t>(n), *pos_a = env.temp<int32_t>(n);
   if (!env.ok()) return env.status;
   int64_t na = 0;
@@ -210,12 +238,20 @@ static us_status decompose_blocked(Env &env, const us_coo &coo, const Plan &pa, 
     so.key64 = skey; so.val = sval;
     sort_coo(env, coo.row, coo.col, coo.val, n, ks, so, flags);
     const int64_t g = ceil_div<int64_t>(n, 256);
-    US_LAUNCH(env, "node_head", 12.0 * n, node_head_kernel, g, 256, (const uint64_t *)skey, n, inner_bits, head, flags);
-    exclusive_scan_i32(env, head, pos, n, &flags->scalar[0]);
-    US_LAUNCH(env, "node_start", 12.0 * n, node_start_kernel, g, 256, (const int32_t *)head, (const int32_t *)pos, n,
-              start);
-    US_LAUNCH(env, "node_keep", 16.0 * n, node_keep_kernel, g, 256, (const int32_t *)head, (const int32_t *)pos,
-              (const int32_t *)start, n, thld, keep);
+    const int64_t width = pg.bh * pg.bw;   // the most entries a node can hold
+    if (width <= 16) {
+      US_LAUNCH(env, "node_keep", 12.0 * n, node_keep_window_kernel, ceil_div<int64_t>(n, NK_TILE), NK_T,
+                (const uint64_t *)skey, n, inner_bits, (int)width, thld, keep, flags);
+    } else {
+      int32_t *head = env.temp<int32_t>(n), *pos = env.temp<int32_t>(n), *start = env.temp<int32_t>(n + 1);
+      if (!env.ok()) return env.status;
+      US_LAUNCH(env, "node_head", 12.0 * n, node_head_kernel, g, 256, (const uint64_t *)skey, n, inner_bits, head, flags);
+      exclusive_scan_i32(env, head, pos, n, &flags->scalar[0]);
+      US_LAUNCH(env, "node_start", 12.0 * n, node_start_kernel, g, 256, (const int32_t *)head, (const int32_t *)pos, n,
+                start);
+      US_LAUNCH(env, "node_keep", 16.0 * n, node_keep_kernel, g, 256, (const int32_t *)head, (const int32_t *)pos,
+                (const int32_t *)start, n, thld, keep);
+    }
     exclusive_scan_i32(env, keep, pos_a, n, &flags->scalar[1]);
     Flags h{};
     if (!read_flags(env, flags, &h)) return env.status;
