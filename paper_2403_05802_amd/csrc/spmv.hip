@@ -314,9 +314,10 @@ us_status spmv_impl(Env &env, const us_formatted &A, const float *x, float *y, b
                     sr.ptr, sr.idx, (const float *)A.val, sr.row_ids, A.nmajor, x, y);
         return env.status;
       }
-      if (sr.row_ids) {   // a list of stored rows: the others are zero
-        if (!accumulate) fill_u32(env, (uint32_t *)y, A.nrows, 0u);
-        spmv_compressed(env, A, sr.ptr, sr.idx, A.val, sr.row_ids, A.nmajor, A.nnz, x, y, true);
+      if (sr.row_ids) {   // a list of stored rows: the others are zero (unless every row is stored)
+        const bool every_row = A.nmajor == A.nrows;
+        if (!accumulate && !every_row) fill_u32(env, (uint32_t *)y, A.nrows, 0u);
+        spmv_compressed(env, A, sr.ptr, sr.idx, A.val, sr.row_ids, A.nmajor, A.nnz, x, y, accumulate || !every_row);
         return env.status;
       }
       spmv_compressed(env, A, sr.ptr, sr.idx, A.val, nullptr, A.nrows, A.nnz, x, y, accumulate);
