@@ -26,7 +26,9 @@
 // wavefront = 42 % of the VALU issue slots, waves waiting twice as long as they issue, 6 waves per SIMD
 // (74 VGPRs, 43 KB of LDS per workgroup).  Forcing 8 waves per SIMD (16-bit wave counters for the LDS,
 // 64 VGPRs) spilled 24 registers and took 157 us; 8192-entry tiles (16 entries per thread, runs twice as
-// long, 4 waves per SIMD) took 123 us.
+// long, 4 waves per SIMD) took 123 us; 1024 threads x 4 entries (same tile, 48 VGPRs, 8 waves per SIMD) took
+// 105 us, no different from the 106 us of this shape: occupancy is not what holds the kernel back, the
+// scattered 200-byte pieces it writes are (7-bit digits, pieces twice as long: 96 us).
 #include "common.h"
 #include "device.h"
 
