@@ -87,7 +87,7 @@ typedef struct us_expr {
  *   CISR-plus (schedule(d0),d0,d1) merge(0,1) trim(1,2), 1 <= partitions <= 65536 (Section 7.2.4): rows that
  *        hold entries are ordered by their number of entries, most first (equal ones by ascending row), and
  *        dealt to the partitions in turn (the k-th goes to partition k mod P: this library's reading of
- *        "schedule ... in a balanced manner"); stored as a size P, a row level (ptr over the partitions, row
+ *        the schedule query, of which the paper only requires balance); stored as a size P, a row level (ptr over the partitions, row
  *        indices ascending inside a partition) and a column level (ptr over the stored rows, column indices) */
 typedef struct us_format_desc {
   int32_t nlevels;

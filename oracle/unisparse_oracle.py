@@ -34,8 +34,8 @@ listed in the design notes of the repository):
     and pad value +0.0;
   * CISR-plus (Section 7.2.4, its printed encoding): the indirect level is built from three
     queries -- sum (entries per row), reorder (rows with the most entries first; equal rows in
-    ascending row order) and schedule into N partitions; "in a balanced manner" is all the text
-    says about schedule, and it is read here as dealing: the k-th row of that order goes to
+    ascending row order) and schedule into N partitions; the text asks only that the assignment be balanced,
+    and that is read here as dealing: the k-th row of that order goes to
     partition k mod N.  The level is untouched by trim(1,2), hence a size N; rows and columns
     below it are compressed levels (a row level with a ptr over the N partitions);
   * parity unpinned by the paper: the pad column (-1), percentile-based ELL width, the

@@ -6,7 +6,7 @@ namespace us {
 
 // ------------------------------------------------------------------ CISR-plus (Section 7.2.4)
 // The indirect level of its encoding is three queries over the rows: sum (entries per row), reorder (most
-// entries first, equal rows by ascending index) and schedule (the paper says only "in a balanced manner"; read
+// entries first, equal rows by ascending index) and schedule (the paper asks only that the assignment be balanced; read
 // here as dealing: the k-th row of that order goes to partition k mod P).  After the (row, col) sort these are row-level steps: the stored rows are compacted in row order,
 // one stable key sort by (longest possible - length) gives the order, a second one by partition (from row order
 // again, so rows stay ascending inside a partition) gives the storage order; then the entries of every row move
