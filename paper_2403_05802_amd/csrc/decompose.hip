@@ -297,7 +297,7 @@ us_status decompose_impl(Env &env, const us_coo &coo, const us_format_desc &da, 
   if ((pa.pattern == P_ELL && pa.swapped) || (pb.pattern == P_ELL && pb.swapped)) return US_ERR_UNSUPPORTED_DESC;
   if (pred.ngroup == 2) {
     // groups that are the nodes of a blocked layout: (d0/b, d1-d0) of Figure 3c, or the blocks (d0/bh, d1/bw)
-    // of the BELL/COO case study (Section 7.2.2: "non-zero threshold within each block")
+    // of the BELL/COO case study (Section 7.2.2: a threshold on the entries of each block)
     Plan pg;
     int64_t bh, bw;
     if (pred.kind != US_P_SUM_GE_ABS || !tile(pred.group[0], US_E_DIV, 0, &bh)) return US_ERR_UNSUPPORTED_DESC;

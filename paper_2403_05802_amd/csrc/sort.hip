@@ -1,4 +1,4 @@
-// The Sort operator of the conversion algorithm (Figure 8: "apply Sort to T_format";
+// The Sort operator of the conversion algorithm (Figure 8: the step that orders T_format by its target tuple;
 // Section 7.2.1 reports it as 65 % of COO->BDIA conversion time, Section 7.2.3 as 84 % for
 // Serpens) as a least-significant-digit radix sort over packed target tuples.
 //
