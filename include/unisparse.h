@@ -14,8 +14,11 @@
  *   - The library never takes ownership of caller memory.  Arrays of a us_formatted are
  *     obtained through us_ctx.alloc and released by us_free through us_ctx.free.
  *   - Work is enqueued on us_ctx.hip_stream.  us_convert / us_decompose synchronise that
- *     stream once before returning (output sizes and the validation flags are data
- *     dependent); us_spmv / us_spmm only enqueue.
+ *     stream before returning (output sizes and the validation flags are data dependent:
+ *     one read-back for most conversions, up to three for a decomposition); us_spmv /
+ *     us_spmm only enqueue.
+ *   - An array of a us_formatted may be allocated larger than the count us_formatted_array
+ *     reports (the stored-row arrays of DCSR are sized before their count is known).
  *   - Every call returns a us_status; on error no output object is produced (*out = NULL)
  *     and nothing is leaked.  The library never aborts, throws or prints.
  *   - Indices are int32, values fp32 (fp32 accumulate), element counts must stay below 2^31.
@@ -159,7 +162,7 @@ us_status us_decompose(const us_ctx *ctx, const us_coo *coo, const us_format_des
 /* y = A x (accumulate = 0) or y += A x (accumulate != 0; the generic op of Figure 3c reads Y).
  * x: ncols floats, y: nrows floats, both device.  For a hybrid call it on part A, then on
  * part B with accumulate = 1.
- * Row-grouped layouts (COO, CSR, DCSR, DIA and its variant, BCSR, BDIA, ELL) add in a fixed order: two
+ * Row-grouped layouts (COO, CSR, DCSR, CISR-plus, DIA and its variant, BCSR, BDIA, ELL) add in a fixed order: two
  * calls give the same bits.  Layouts whose leaves are not grouped by output row (CSC, DCSC, column-major
  * COO, CSB) scatter with fp32 atomics, so the last bits may differ from call to call; this holds for
  * us_spmm as well. */
