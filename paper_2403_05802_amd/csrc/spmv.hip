@@ -205,6 +205,29 @@ __global__ __launch_bounds__(256) void dia_spmv_kernel(const int32_t *off, const
   y[i] = s;
 }
 
+// Row-indexed slab, nrows a multiple of 4: four rows per thread, the slab read as 16-byte vectors (the summation
+// order per row is the same as above: diagonals in ascending order of offset)
+__global__ __launch_bounds__(256) void dia_spmv4_kernel(const int32_t *off, const float *val, int64_t ndiag, int64_t nrows,
+                                                       int64_t ncols, const float *x, float *y, int accumulate) {
+  const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i >= nrows) return;
+  float4 s = accumulate ? *reinterpret_cast<const float4 *>(y + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int64_t k = 0; k < ndiag; ++k) {
+    const int64_t j = i + off[k];
+    if (j + 3 < 0 || j >= ncols) continue;
+    const float4 v = *reinterpret_cast<const float4 *>(val + k * nrows + i);
+    if (j >= 0 && j + 3 < ncols) {
+      s.x += v.x * x[j]; s.y += v.y * x[j + 1]; s.z += v.z * x[j + 2]; s.w += v.w * x[j + 3];
+    } else {
+      if (j >= 0 && j < ncols) s.x += v.x * x[j];
+      if (j + 1 >= 0 && j + 1 < ncols) s.y += v.y * x[j + 1];
+      if (j + 2 >= 0 && j + 2 < ncols) s.z += v.z * x[j + 2];
+      if (j + 3 >= 0 && j + 3 < ncols) s.w += v.w * x[j + 3];
+    }
+  }
+  *reinterpret_cast<float4 *>(y + i) = s;
+}
+
 // column-major compressed layouts (CSC / DCSC): scatter form, one thread per stored column
 __global__ __launch_bounds__(256) void csc_spmv_atomic_kernel(const int32_t *ptr, const int32_t *idx, const float *val,
                                                              const int32_t *col_ids, int64_t ncols_stored,
@@ -324,9 +347,14 @@ us_status spmv_impl(Env &env, const us_formatted &A, const float *x, float *y, b
       return env.status;
     }
     case P_DIA:
-      US_LAUNCH(env, "spmv_dia", 4.0 * A.nval + 8.0 * A.nrows + 4.0 * A.ncols, dia_spmv_kernel,
-                ceil_div<int64_t>(A.nrows, 256), 256, (const int32_t *)A.level[0].idx, (const float *)A.val,
-                A.nmajor, A.nrows, A.ncols, A.swapped ? 1 : 0, x, y, accumulate ? 1 : 0);
+      if (!A.swapped && A.nrows % 4 == 0 && (((uintptr_t)A.val | (uintptr_t)y) & 15) == 0)
+        US_LAUNCH(env, "spmv_dia", 4.0 * A.nval + 8.0 * A.nrows + 4.0 * A.ncols, dia_spmv4_kernel,
+                  ceil_div<int64_t>(A.nrows / 4, 256), 256, (const int32_t *)A.level[0].idx, (const float *)A.val,
+                  A.nmajor, A.nrows, A.ncols, x, y, accumulate ? 1 : 0);
+      else
+        US_LAUNCH(env, "spmv_dia", 4.0 * A.nval + 8.0 * A.nrows + 4.0 * A.ncols, dia_spmv_kernel,
+                  ceil_div<int64_t>(A.nrows, 256), 256, (const int32_t *)A.level[0].idx, (const float *)A.val,
+                  A.nmajor, A.nrows, A.ncols, A.swapped ? 1 : 0, x, y, accumulate ? 1 : 0);
       return env.status;
     case P_ELL:
       US_LAUNCH(env, "spmv_ell", 8.0 * A.nval + 8.0 * A.nrows, ell_spmv_kernel, ceil_div<int64_t>(A.nrows, 256), 256,
