@@ -334,7 +334,30 @@ def other_workloads(B, W, torch, ctx, up, K, Wm):
         lambda r, c, v: list(B.us_decompose(ctx, m.nrows, m.ncols, r, c, v, ELL, COO, pr)), prod5,
         2.0 * m.nnz * 128, lambda p: 12.0 * m.nnz + 8.0 * p[0].val().numel() + 12.0 * p[1].nnz)
     res["label_propagation"] = label_propagation(B, W, torch, ctx, up)
+    res["format_to_format"] = format_to_format(B, W, torch, ctx, up, K, Wm)
     return res
+
+
+def format_to_format(B, W, torch, ctx, up, K, Wm):
+    """Conversions between formats through the COO hub, the cases of Table 5 on the benchmark matrices:
+    CSR -> CSC (config 2), DCSC -> BCSR 4x4 (config 4), CSB -> DIA variant (config 3's diagonals)."""
+    out = {}
+
+    def one(name, m, src_desc, dst_desc):
+        r, c, v = up(m.row), up(m.col), up(m.val)
+        src = B.us_convert(ctx, m.nrows, m.ncols, r, c, v, src_desc)
+        del r, c, v
+        ms = timed(torch, lambda: B.us_convert_formatted(ctx, src, dst_desc).free(), K, Wm)
+        out[name] = {"nnz": m.nnz, "convert_ms": round(ms, 4), "convert_mnnz_s": round(m.nnz / ms / 1e3, 1)}
+        src.free()
+        torch.cuda.empty_cache()
+
+    P = B.us_desc_preset
+    one("config2_csr_to_csc", W.cfg2_powerlaw(), P(B.US_F_CSR), P(B.US_F_CSC))
+    one("config4_dcsc_to_bcsr", W.cfg4_blockfem(), P(B.US_F_DCSC), P(B.US_F_BCSR, 4, 4))
+    one("config3_diagonals_csb_to_dia_variant", W.cfg3_banded(extra_frac=0.0), P(B.US_F_CSB, 512, 512),
+        P(B.US_F_DIA_VARIANT))
+    return out
 
 
 def label_propagation(B, W, torch, ctx, up, iters=20, N=1000):

@@ -124,7 +124,7 @@ struct us_formatted {
   int64_t nmajor = 0;   // CSR: rows (cols if swapped); DCSR, CISR-plus: stored rows; DIA: ndiag; BCSR/BDIA: block rows; ELL: K
   int64_t bh = 1, bw = 1, nblk = 0;   // BDIA: bh = block height, bw = 1, nblk = (block row, diagonal) nodes;
                                       // CSB: nblk = nmajor = blocks of the dense grid, level[1].size = blocks per block row
-  // CSR / DCSR: where every SpMV tile starts on the merge path of row ends and non-zeros
+  // CSR / DCSR / CISR-plus (and CSC / DCSC by columns): where every tile starts on the merge path of row ends and non-zeros
   // (rows consumed before step t * tile), computed once at conversion
   int32_t *mp_split = nullptr; int64_t mp_tiles = 0;
   // scratch for the compute kernels (partial sums of rows cut by a tile boundary); grown on
@@ -133,6 +133,10 @@ struct us_formatted {
 };
 
 namespace us {
+
+// Steps of the merged sequence {row ends} U {non-zeros} per workgroup of the compressed-row kernels
+// (us_formatted::mp_split holds where every such tile starts)
+constexpr int MP_TILE = 2048;
 
 // Compressed rows as the product kernels see them: CSR (every row), DCSR and CISR-plus (a list of stored rows).
 struct StoredRows { const int32_t *ptr, *idx, *row_ids; };

@@ -472,6 +472,42 @@ __global__ __launch_bounds__(256) void expand_write_kernel(SrcView v, const int3
   row[pos[s]] = r; col[pos[s]] = c; val[pos[s]] = x;
 }
 
+// Compressed layouts (CSR, DCSR, CISR-plus, and CSC / DCSC with columns in the role of rows): Split(ptr) = one
+// major index per entry, found with the
+// tile starts on the merge path that the conversion left for the product kernels: a workgroup stages the row ends
+// that fall into its tile and every entry searches them in LDS.  Columns and values are used where they are.
+__global__ __launch_bounds__(256) void expand_rows_kernel(const int32_t *ptr, const int32_t *row_ids, const int32_t *split,
+                                                         int64_t nrows, int64_t nnz, int32_t *row_out) {
+  __shared__ int32_t s_end[MP_TILE];
+  const int32_t *row_end = ptr + 1;
+  const int64_t total = nrows + nnz;
+  const int64_t diag0 = (int64_t)blockIdx.x * MP_TILE, diag1 = min(diag0 + (int64_t)MP_TILE, total);
+  const int64_t r0 = split[blockIdx.x], r1 = split[blockIdx.x + 1];
+  const int64_t z0 = diag0 - r0, z1 = diag1 - r1;
+  const int nr = (int)(r1 - r0), nz = (int)(z1 - z0);
+  for (int i = threadIdx.x; i < nr; i += 256) s_end[i] = (int32_t)(row_end[r0 + i] - z0);
+  __syncthreads();
+  for (int i = threadIdx.x; i < nz; i += 256) {
+    int lo = 0, hi = nr;   // first staged row whose end lies behind entry i; none: the row that runs on past the tile
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (s_end[mid] <= i) lo = mid + 1; else hi = mid;
+    }
+    int64_t row = r0 + lo;
+    if (row > nrows - 1) row = nrows - 1;
+    row_out[z0 + i] = row_ids ? row_ids[row] : (int32_t)row;
+  }
+}
+
+// layouts without padding: every slot is an entry, so only its coordinates have to be rebuilt
+__global__ __launch_bounds__(256) void expand_coords_kernel(SrcView v, int32_t *row, int32_t *col) {
+  int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (s >= v.nslots) return;
+  int32_t r, c; float x;
+  slot_entry(v, s, &r, &c, &x);
+  row[s] = r; col[s] = c;
+}
+
 us_status convert_formatted_impl(Env &env, const us_formatted &src, const us_format_desc &desc, us_formatted **out) {
   *out = nullptr;
   Plan plan;
@@ -495,6 +531,36 @@ us_status convert_formatted_impl(Env &env, const us_formatted &src, const us_for
     default: return US_ERR_FORMAT_MISMATCH;
   }
   const int64_t ns = v.nslots;
+  if ((src.pattern == P_CSR || src.pattern == P_DCSR || src.pattern == P_CISR) && src.mp_split && ns > 0 &&
+      src.mp_tiles == ceil_div<int64_t>(src.nmajor + ns, MP_TILE)) {
+    const StoredRows sr = stored_rows(src);
+    int32_t *r = env.temp<int32_t>(ns);
+    if (!env.ok()) return env.status;
+    US_LAUNCH(env, "expand_rows", 4.0 * ns + 4.0 * src.nmajor, expand_rows_kernel, src.mp_tiles, 256, sr.ptr, sr.row_ids,
+              (const int32_t *)src.mp_split, src.nmajor, ns, r);
+    us_coo coo{src.nrows, src.ncols, ns, src.swapped ? sr.idx : r, src.swapped ? r : sr.idx, src.val};   // CSC: the major index is d1
+    us_status st = env.status;
+    if (st == US_OK) st = convert_with_plan(env, coo, plan, desc, out);
+    env.sync();
+    if (st == US_OK && !env.ok()) st = env.status;
+    if (st != US_OK && *out) { free_formatted(env, *out); *out = nullptr; }
+    return st;
+  }
+  if (src.pattern == P_COO || src.pattern == P_CSR || src.pattern == P_DCSR || src.pattern == P_CSB ||
+      src.pattern == P_CISR) {
+    // no padding anywhere: the values are used where they are, the coordinates are written out once
+    int32_t *r = env.temp<int32_t>(ns), *c = env.temp<int32_t>(ns);
+    if (!env.ok()) return env.status;
+    if (ns > 0)
+      US_LAUNCH(env, "expand_coords", 12.0 * ns, expand_coords_kernel, ceil_div<int64_t>(ns, 256), 256, v, r, c);
+    us_coo coo{src.nrows, src.ncols, ns, r, c, src.val};
+    us_status st = env.status;
+    if (st == US_OK) st = convert_with_plan(env, coo, plan, desc, out);
+    env.sync();
+    if (st == US_OK && !env.ok()) st = env.status;
+    if (st != US_OK && *out) { free_formatted(env, *out); *out = nullptr; }
+    return st;
+  }
   Flags *flags = new_flags(env);
   int32_t *flag = env.temp<int32_t>(ns), *pos = env.temp<int32_t>(ns);
   if (!env.ok()) return env.status;

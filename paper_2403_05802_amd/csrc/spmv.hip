@@ -11,7 +11,8 @@ namespace us {
 // row and 20,000 one-entry rows cost the same.  Each workgroup takes MP_TILE consecutive steps of
 // that sequence, stages the products in LDS, every thread walks MP_IPT steps, and partial row
 // sums are stitched together with a segmented scan (fixed order: bitwise reproducible).
-constexpr int MP_T = 256, MP_IPT = 8, MP_TILE = MP_T * MP_IPT;
+constexpr int MP_T = 256, MP_IPT = 8;
+static_assert(MP_TILE == MP_T * MP_IPT, "tile of the merge path = threads x steps per thread");
 
 // number of row ends consumed before step `diag`: largest r with ptr_end[r-1] <= diag - r ...
 __device__ __forceinline__ int64_t merge_path_rows(const int32_t *row_end, int64_t nrows, int64_t nnz, int64_t diag) {
@@ -312,7 +313,9 @@ __global__ __launch_bounds__(256) void csb_spmv_atomic_kernel(const int32_t *ptr
 int64_t spmv_tiles(int64_t nmajor, int64_t nnz) { return ceil_div<int64_t>(nmajor + nnz, MP_TILE); }
 
 void spmv_prepare(Env &env, us_formatted *f, const int32_t *nmajor_dev, int64_t nmajor_cap) {
-  if (f->swapped || (f->pattern != P_CSR && f->pattern != P_DCSR && f->pattern != P_CISR)) return;
+  // (column-major CSC / DCSC get the tile starts too: their products scatter and do not use them, but the way
+  // back to COO does)
+  if (f->pattern != P_CSR && f->pattern != P_DCSR && f->pattern != P_CISR) return;
   const int64_t nmajor = nmajor_dev ? nmajor_cap : f->nmajor;
   const int64_t total = nmajor + f->nnz;
   if (total == 0) return;
