@@ -339,8 +339,9 @@ def other_workloads(B, W, torch, ctx, up, K, Wm):
 
 
 def format_to_format(B, W, torch, ctx, up, K, Wm):
-    """Conversions between formats through the COO hub, the cases of Table 5 on the benchmark matrices:
-    CSR -> CSC (config 2), DCSC -> BCSR 4x4 (config 4), CSB -> DIA variant (config 3's diagonals)."""
+    """The conversion cases of Table 5 on the benchmark matrices: COO -> ELL (config 4), COO -> DIA (config 3's
+    diagonals), and through the COO hub CSR -> CSC (config 2), DCSC -> BCSR 4x4 (config 4), CSB -> DIA variant
+    (config 3's diagonals)."""
     out = {}
 
     def one(name, m, src_desc, dst_desc):
@@ -352,7 +353,16 @@ def format_to_format(B, W, torch, ctx, up, K, Wm):
         src.free()
         torch.cuda.empty_cache()
 
+    def from_coo(name, m, dst_desc):
+        r, c, v = up(m.row), up(m.col), up(m.val)
+        ms = timed(torch, lambda: B.us_convert(ctx, m.nrows, m.ncols, r, c, v, dst_desc).free(), K, Wm)
+        out[name] = {"nnz": m.nnz, "convert_ms": round(ms, 4), "convert_mnnz_s": round(m.nnz / ms / 1e3, 1)}
+        del r, c, v
+        torch.cuda.empty_cache()
+
     P = B.us_desc_preset
+    from_coo("config4_coo_to_ell", W.cfg4_blockfem(), P(B.US_F_ELL))                       # 96 entries in every row
+    from_coo("config3_diagonals_coo_to_dia", W.cfg3_banded(extra_frac=0.0), P(B.US_F_DIA))
     one("config2_csr_to_csc", W.cfg2_powerlaw(), P(B.US_F_CSR), P(B.US_F_CSC))
     one("config4_dcsc_to_bcsr", W.cfg4_blockfem(), P(B.US_F_DCSC), P(B.US_F_BCSR, 4, 4))
     one("config3_diagonals_csb_to_dia_variant", W.cfg3_banded(extra_frac=0.0), P(B.US_F_CSB, 512, 512),

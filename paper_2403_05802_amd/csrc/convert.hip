@@ -127,19 +127,39 @@ __global__ __launch_bounds__(256) void max_len_kernel(const int32_t *ptr, int64_
   }
 }
 
-// ELL: entry i of the sorted list sits in slot rank = i - ptr[row] of its row (the enum query)
-__global__ __launch_bounds__(256) void ell_scatter_kernel(const int32_t *major, const int32_t *minor,
-                                                         const float *val, const int32_t *ptr, int64_t n,
-                                                         int64_t nrows, int64_t K, int32_t *ecol, float *eval,
-                                                         Flags *flags) {
-  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= n) return;
-  int32_t r = major[i];
-  int64_t rank = i - ptr[r];
-  if (rank >= K) { flags->ell_overflow = 1; return; }
-  int64_t slot = rank * nrows + r;
-  ecol[slot] = minor[i];
-  eval[slot] = val[i];
+// ELL: entry i of the sorted list sits in slot rank = i - ptr[row] of its row (the enum query).  The slab is
+// slot-major (col/val[slot * nrows + row]) while the list is row-major: a wavefront takes 64 rows and moves them
+// EF_SLOTS slots at a time through LDS -- in, EF_RPL rows per load instruction (EF_SLOTS consecutive entries of a
+// row each); out, a lane per row, 256 contiguous bytes per slot and array, pads included (no separate fill).
+constexpr int EF_ROWS = 64, EF_SLOTS = 16, EF_PITCH = EF_SLOTS + 1, EF_RPL = 64 / EF_SLOTS;   // rows per load instruction
+__global__ __launch_bounds__(64) void ell_fill_kernel(const int32_t *minor, const float *val, const int32_t *ptr,
+                                                     int64_t nrows, int64_t K, int32_t *ecol, float *eval,
+                                                     Flags *flags) {
+  __shared__ int32_t s_col[EF_ROWS * EF_PITCH];
+  __shared__ float s_val[EF_ROWS * EF_PITCH];
+  const int lane = threadIdx.x;
+  const int64_t r = (int64_t)blockIdx.x * EF_ROWS + lane;
+  const int64_t start = r < nrows ? ptr[r] : 0, len = r < nrows ? ptr[r + 1] - start : 0;
+  if (len > K) flags->ell_overflow = 1;
+  for (int64_t k0 = 0; k0 < K; k0 += EF_SLOTS) {
+#pragma unroll 4
+    for (int j = 0; j < EF_ROWS; j += EF_RPL) {
+      const int row = j + lane / EF_SLOTS, kk = lane % EF_SLOTS;
+      const int64_t st = __shfl(start, row), ln = __shfl(len, row);
+      const bool has = k0 + kk < ln;
+      s_col[row * EF_PITCH + kk] = has ? minor[st + k0 + kk] : -1;
+      s_val[row * EF_PITCH + kk] = has ? val[st + k0 + kk] : 0.f;
+    }
+    __syncthreads();
+    if (r < nrows) {
+      const int nk = (int)min<int64_t>(EF_SLOTS, K - k0);
+      for (int kk = 0; kk < nk; ++kk) {
+        ecol[(k0 + kk) * nrows + r] = s_col[lane * EF_PITCH + kk];
+        eval[(k0 + kk) * nrows + r] = s_val[lane * EF_PITCH + kk];
+      }
+    }
+    __syncthreads();
+  }
 }
 
 // ------------------------------------------------------------------ launches shared with the other conversion files
@@ -218,8 +238,8 @@ KeySpec rowcol_keyspec(const us_coo &coo, bool swapped) {
   return ks;
 }
 
-// Gives f (shape already set) the levels of an ELL tensor of width K with every slot empty: column -1, value 0.
-static bool ell_shell(Env &env, us_formatted *f, int64_t K) {
+// Gives f (shape already set) the levels of an ELL tensor of width K, every slot empty (column -1, value 0) if `fill`.
+static bool ell_shell(Env &env, us_formatted *f, int64_t K, bool fill = true) {
   const int64_t slots = K * f->nrows;
   int32_t *ecol = env.owned<int32_t>(slots);
   float *ev = env.owned<float>(slots);
@@ -228,8 +248,10 @@ static bool ell_shell(Env &env, us_formatted *f, int64_t K) {
   f->level[2].idx = ecol; f->level[2].nidx = slots;
   f->val = ev; f->nval = slots; f->nmajor = K;
   if (!env.ok()) return false;
-  fill_u32(env, (uint32_t *)ecol, slots, 0xFFFFFFFFu);
-  fill_u32(env, (uint32_t *)ev, slots, 0u);
+  if (fill) {
+    fill_u32(env, (uint32_t *)ecol, slots, 0xFFFFFFFFu);
+    fill_u32(env, (uint32_t *)ev, slots, 0u);
+  }
   return true;
 }
 
@@ -337,13 +359,11 @@ us_status build_from_sorted(Env &env, const Plan &plan, const us_format_desc &de
       if (K == 0) K = h.scalar[0];
     }
     if (K * nrows >= (1ll << 31)) return finish(US_ERR_OVERFLOW);
-    if (!ell_shell(env, f, K)) return finish(env.status);
-    int32_t *ecol = f->level[2].idx;
-    float *ev = f->val;
-    if (nnz > 0)
-      US_LAUNCH(env, "ell_scatter", 16.0 * nnz + 8.0 * nnz, ell_scatter_kernel, ceil_div<int64_t>(nnz, 256), 256,
-                (const int32_t *)major, (const int32_t *)minor, (const float *)val, (const int32_t *)ptr, nnz,
-                nrows, K, ecol, ev, flags);
+    if (!ell_shell(env, f, K, false)) return finish(env.status);
+    if (K > 0)
+      US_LAUNCH(env, "ell_fill", 8.0 * nnz + 8.0 * K * nrows, ell_fill_kernel, ceil_div<int64_t>(nrows, EF_ROWS), EF_ROWS,
+                (const int32_t *)minor, (const float *)val, (const int32_t *)ptr, nrows, K, f->level[2].idx, f->val,
+                flags);
     return finish(flags_ok(&h));
   }
   return finish(US_ERR_UNSUPPORTED_DESC);
