@@ -43,12 +43,15 @@ typedef uint64_t Key;  // keys live in registers and LDS as 64-bit words whateve
 __device__ __forceinline__ Key build_key(const KeySpec &ks, uint32_t r, uint32_t c) {
   uint32_t a = ks.swap ? c : r, b = ks.swap ? r : c;
   if (ks.mode == 0) return ((Key)a << ks.b_bits) | (Key)b;
+  // (a coordinate out of range is reported, not sorted; its second field is still cut to b_bits so that it cannot
+  // leak into the leading field, whose digits the first histogram may take from a / bh alone)
+  const Key field = ((Key)1 << ks.b_bits) - 1;
   if (ks.mode == 2) {   // Skew(0,1,-1) then TileSplit(0,bh): (a/bh, b-a, a%bh), the diagonal biased to be >= 0
     uint32_t ab = a / ks.bh, ai = a - ab * ks.bh, dg = b - a + (ks.a_extent - 1);
-    return ((((Key)ab << ks.b_bits) | (Key)dg) << ks.ih_bits) | (Key)ai;
+    return ((((Key)ab << ks.b_bits) | ((Key)dg & field)) << ks.ih_bits) | (Key)ai;
   }
   uint32_t ab = a / ks.bh, ai = a - ab * ks.bh, bb = b / ks.bw, bi = b - bb * ks.bw;
-  return (((((Key)ab << ks.b_bits) | (Key)bb) << ks.ih_bits | (Key)ai) << ks.iw_bits) | (Key)bi;
+  return (((((Key)ab << ks.b_bits) | ((Key)bb & field)) << ks.ih_bits | (Key)ai) << ks.iw_bits) | (Key)bi;
 }
 
 enum { IN_COO = 0, IN_SPLIT = 1, IN_KEY32 = 2 };
@@ -78,6 +81,8 @@ struct PassArgs {
   uint32_t nchunks;
   KeySpec ks;
   int hist_minor_only;             // IN_COO: this pass's digit lies inside the minor index of a (major, minor) key
+  int hist_major_shift;            // IN_COO, blocked keys: >= 0 when this pass's digit lies inside the leading field
+                                   // a / bh of the key: digit = ((a / bh) >> hist_major_shift) & mask
   Flags *flags;
 };
 
@@ -131,6 +136,15 @@ __global__ __launch_bounds__(RS_T) void radix_hist_kernel(PassArgs a) {
     } else {
 #pragma unroll
       for (int k = 0; k < RS_IPT; ++k) digit[k] = i + k < a.n ? a.digit_in[i + k] : 0xFFFFFFFFu;
+    }
+  } else if (IN == IN_COO && a.hist_major_shift >= 0) {
+    // the digit is a bit field of the block row alone: read the row indices only (the scatter of this pass reads
+    // and validates both coordinates)
+    const int32_t *major = a.ks.swap ? a.col : a.row;
+#pragma unroll
+    for (int k = 0; k < RS_IPT; ++k) {
+      uint32_t i = base + k * RS_T + threadIdx.x;
+      digit[k] = i < a.n ? ((((uint32_t)major[i] / a.ks.bh) >> a.hist_major_shift) & a.mask) : 0xFFFFFFFFu;
     }
   } else if (IN == IN_COO && a.hist_minor_only) {
     // the digit is a bit field of the minor index alone: read that array only (the scatter of this pass
@@ -759,12 +773,14 @@ static bool sort_generic(Env &env, int in_mode, const int32_t *row, const int32_
     a.tiles_per_xcd = ceil_div<uint32_t>(nblocks, 8u);
     a.hist = hist; a.chunk = chunk; a.dtotal = dtotal; a.nchunks = nchunks; a.ks = ks; a.flags = flags;
     a.hist_minor_only = first && in_mode == IN_COO && ks.mode == 0 && shifts[p] + widths[p] <= ks.b_bits && ks.b_bits <= 32;
+    const int lead_at = ks.b_bits + ks.ih_bits + ks.iw_bits;   // blocked keys: where the field a / bh starts
+    a.hist_major_shift = (first && in_mode == IN_COO && ks.mode != 0 && shifts[p] >= lead_at) ? shifts[p] - lead_at : -1;
 
     const int in = first ? in_mode : IN_SPLIT;
     const int om = last ? final_mode : OUT_SPLIT;
     const double in_key = in == IN_COO ? 8.0 : (in == IN_KEY32 ? 4.0 : kb);
     const double out_key = om == OUT_UNPACK ? 8.0 : (om == OUT_KEY64 ? 8.0 : (om == OUT_KEY32 ? 4.0 : kb + 1.0));
-    if (in == IN_COO) launch_hist<IN_COO>(env, a, (a.hist_minor_only ? 4.0 : 8.0) * nnz);
+    if (in == IN_COO) launch_hist<IN_COO>(env, a, (a.hist_minor_only || a.hist_major_shift >= 0 ? 4.0 : 8.0) * nnz);
     else if (in == IN_KEY32) launch_hist<IN_KEY32>(env, a, 4.0 * nnz);
     else launch_hist<IN_SPLIT>(env, a, 1.0 * nnz);
     if (nblocks <= (uint32_t)RS_SMALL) {
