@@ -91,22 +91,23 @@ __global__ __launch_bounds__(SCAN_T) void scan_reduce_kernel(const int32_t *in, 
 }
 
 // single workgroup: exclusive scan of the per-tile sums in place, grand total to *total_dev.
-// Every thread takes SP_IPT consecutive sums per round, so 24,000 of them are three rounds.
-constexpr int SP_IPT = 8;
+// Every thread takes IPT consecutive sums per round (all its loads in flight together), so 24,000 of them are
+// one round of 1024 x 32 instead of three of 1024 x 8: the kernel is one workgroup waiting on memory.
+template <int IPT>
 __global__ __launch_bounds__(1024) void scan_partials_kernel(uint32_t *partial, int64_t nb, int32_t *total_dev) {
   __shared__ uint32_t s_wave[1024 / 64 + 1];
   uint32_t carry = 0;
-  for (int64_t base = 0; base < nb; base += 1024 * SP_IPT) {
-    const int64_t i0 = base + (int64_t)threadIdx.x * SP_IPT;
-    uint32_t v[SP_IPT], s = 0, total;
+  for (int64_t base = 0; base < nb; base += 1024 * IPT) {
+    const int64_t i0 = base + (int64_t)threadIdx.x * IPT;
+    uint32_t v[IPT], s = 0, total;
 #pragma unroll
-    for (int k = 0; k < SP_IPT; ++k) {
+    for (int k = 0; k < IPT; ++k) {
       v[k] = i0 + k < nb ? partial[i0 + k] : 0u;
       s += v[k];
     }
     uint32_t ex = block_exclusive_sum<1024>(s, s_wave, &total) + carry;
 #pragma unroll
-    for (int k = 0; k < SP_IPT; ++k) {
+    for (int k = 0; k < IPT; ++k) {
       if (i0 + k < nb) partial[i0 + k] = ex;
       ex += v[k];
     }
@@ -152,7 +153,8 @@ __global__ __launch_bounds__(SCAN_T) void scan_apply_kernel(const int32_t *in, i
 }
 
 void scan_partials_launch(Env &env, uint32_t *partial, int64_t nb, int32_t *total_dev) {
-  US_LAUNCH(env, "scan_partials", 8.0 * nb, scan_partials_kernel, 1, 1024, partial, nb, total_dev);
+  if (nb > 1024 * 8) US_LAUNCH(env, "scan_partials", 8.0 * nb, scan_partials_kernel<32>, 1, 1024, partial, nb, total_dev);
+  else US_LAUNCH(env, "scan_partials", 8.0 * nb, scan_partials_kernel<8>, 1, 1024, partial, nb, total_dev);
 }
 
 void exclusive_scan_i32(Env &env, const int32_t *in, int32_t *out, int64_t n, int32_t *total_dev) {
