@@ -64,3 +64,41 @@ def test_csr_beyond_the_benchmark_sizes(n, finish):
     g.free()
     del row, col, val, ref, x, y, ptr, idx, v, counts
     torch.cuda.empty_cache()
+
+
+def test_every_layout_and_back_at_2_to_27():
+    """2^27 entries: every layout that can hold a scattered matrix of this size, converted back to CSR through the
+    COO hub, gives the bytes of the direct COO -> CSR conversion (two different code paths that must agree), and the
+    rank decomposition into ELL + COO keeps every entry: its two products add up to the exact row sums."""
+    from paper_2403_05802_amd import binding as B
+    dim, n, row, col, val, _ = generate(1 << 27)
+    ctx = B.Context("cuda:0")
+    P = B.us_desc_preset
+    csr = B.us_convert(ctx, dim, dim, row, col, val, P(B.US_F_CSR))
+    ref_ptr, ref_idx, ref_val = csr.ptr(1), csr.idx(1), csr.val()
+    for name, desc in (("DCSR", P(B.US_F_DCSR)), ("CSC", P(B.US_F_CSC)), ("COO", P(B.US_F_COO)),
+                       ("BCSR2", P(B.US_F_BCSR, 2, 2)), ("CSB1024", P(B.US_F_CSB, 1024, 1024)),
+                       ("CISR-plus1024", P(B.US_F_CISR_PLUS, 1024)), ("ELL", P(B.US_F_ELL))):
+        g = B.us_convert(ctx, dim, dim, row, col, val, desc)
+        back = B.us_convert_formatted(ctx, g, P(B.US_F_CSR))
+        assert torch.equal(back.ptr(1), ref_ptr) and torch.equal(back.idx(1), ref_idx), name
+        assert torch.equal(back.val().view(torch.int32), ref_val.view(torch.int32)), name
+        back.free(); g.free()
+        torch.cuda.empty_cache()
+    # scattered entries in 4x4 blocks: nearly one block per entry, 16 value slots each = 2^31 slots: reported, not built
+    import pytest as _pytest
+    with _pytest.raises(B.UnisparseError) as ei:
+        B.us_convert(ctx, dim, dim, row, col, val, P(B.US_F_BCSR, 4, 4))
+    assert ei.value.code == "US_ERR_OVERFLOW"
+    x = torch.ones(dim, device="cuda"); y = torch.empty(dim, device="cuda")
+    ref = torch.zeros(dim, dtype=torch.float64, device="cuda").index_add_(0, row.to(torch.int64), val.to(torch.float64))
+    pred = B.make_predicate([B.expr(B.US_E_AFFINE, 1, 0)], B.US_P_RANK_LT_PERCENTILE, 9, 10)
+    ga, gb = B.us_decompose(ctx, dim, dim, row, col, val, P(B.US_F_ELL), P(B.US_F_COO), pred)
+    assert ga.nnz + gb.nnz == n and gb.nnz > 0
+    counts = (ref_ptr[1:] - ref_ptr[:-1])
+    K = ga.size(0)
+    assert K == int(torch.sort(counts).values[-(-9 * dim // 10) - 1])        # nearest-rank 90th percentile of the row lengths
+    assert ga.nnz == int(torch.clamp(counts, max=K).sum())
+    B.us_spmv(ctx, ga, x, y); B.us_spmv(ctx, gb, x, y, accumulate=True)
+    assert bool((y.to(torch.float64) == ref).all())
+    ga.free(); gb.free(); csr.free()
