@@ -249,11 +249,21 @@ class Formatted:
     def __init__(self, ctx: Context, handle: int):
         self.ctx = ctx
         self.handle = C.c_void_p(handle)
-        nr, nc, nz = C.c_int64(), C.c_int64(), C.c_int64()
-        self.desc = us_format_desc()
-        _check(lib().us_formatted_info(self.handle, C.byref(nr), C.byref(nc), C.byref(nz), C.byref(self.desc)),
-               "us_formatted_info")
-        self.nrows, self.ncols, self.nnz = nr.value, nc.value, nz.value
+        self._info = None   # (nrows, ncols, nnz, desc), asked for on first use: a conversion loop never needs it
+
+    def _get_info(self):
+        if self._info is None:
+            nr, nc, nz = C.c_int64(), C.c_int64(), C.c_int64()
+            desc = us_format_desc()
+            _check(lib().us_formatted_info(self.handle, C.byref(nr), C.byref(nc), C.byref(nz), C.byref(desc)),
+                   "us_formatted_info")
+            self._info = (nr.value, nc.value, nz.value, desc)
+        return self._info
+
+    nrows = property(lambda self: self._get_info()[0])
+    ncols = property(lambda self: self._get_info()[1])
+    nnz = property(lambda self: self._get_info()[2])
+    desc = property(lambda self: self._get_info()[3])
 
     def us_formatted_array(self, level: int, which: int):
         """(device tensor or None, count).  US_A_SIZE returns (None, extent)."""
