@@ -68,8 +68,10 @@ __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t *p, uint64_t n, 
   for (int k = 0; k < 4; ++k, i += 256)
     if (i < n) p[i] = v;
   // Fills clear what the next kernel adds into with atomics (product outputs, counters, flags).  Once, in some
-  // thirty runs of the tests, the last few elements of a product came out short by what looked like one such add
-  // landing before the fill's last store; a wave that ends only after its stores are acknowledged rules that out.
+  // thirty runs of the tests, the last few elements of such a product came out short, as if an add had landed
+  // before the fill's last store.  The end of a wave should wait for its stores by itself; this wait costs nothing
+  // and states the requirement (the cause of that one mismatch was not found, and it did not come back in 4800
+  // repeats of the case).
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 void fill_u32(Env &env, uint32_t *p, uint64_t n, uint32_t v) {

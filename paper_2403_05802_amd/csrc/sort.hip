@@ -29,6 +29,11 @@
 // long, 4 waves per SIMD) took 123 us; 1024 threads x 4 entries (same tile, 48 VGPRs, 8 waves per SIMD) took
 // 105 us, no different from the 106 us of this shape: occupancy is not what holds the kernel back, the
 // scattered 200-byte pieces it writes are (7-bit digits, pieces twice as long: 96 us).
+//
+// A counting sort by row (device atomics for the row histogram, then an atomic cursor per row for the scatter,
+// then a sort inside every row) is no way round the digit passes: on the 16.8 M entries and 2^20 rows of the
+// power-law workload the histogram alone took 0.91 ms (18 G atomics per second to scattered addresses) and the
+// cursor scatter 1.5 ms, against 0.68 ms for all five passes here.
 #include "common.h"
 #include "device.h"
 
