@@ -155,10 +155,26 @@ __global__ __launch_bounds__(RS_T) void radix_hist_kernel(PassArgs a) {
     // the digit is a bit field of the minor index alone: read that array only (the scatter of this pass
     // reads both and validates them; bits of an out-of-range minor index land in the key just the same)
     const int32_t *minor = a.ks.swap ? a.row : a.col;
+    if (base + RS_TILE <= a.n && (reinterpret_cast<uintptr_t>(minor) & 15u) == 0) {
+      // a full tile of a 16-byte aligned array: four indices per load (which thread counts which item is free)
+      static_assert(RS_IPT % 4 == 0, "indices are read four at a time");
+      const uint4 *m4 = reinterpret_cast<const uint4 *>(minor + base);
+      uint4 v[RS_IPT / 4];
 #pragma unroll
-    for (int k = 0; k < RS_IPT; ++k) {
-      uint32_t i = base + k * RS_T + threadIdx.x;
-      digit[k] = i < a.n ? (((uint32_t)minor[i] >> a.shift) & a.mask) : 0xFFFFFFFFu;
+      for (int q = 0; q < RS_IPT / 4; ++q) v[q] = m4[q * RS_T + threadIdx.x];
+#pragma unroll
+      for (int q = 0; q < RS_IPT / 4; ++q) {
+        digit[4 * q + 0] = (v[q].x >> a.shift) & a.mask;
+        digit[4 * q + 1] = (v[q].y >> a.shift) & a.mask;
+        digit[4 * q + 2] = (v[q].z >> a.shift) & a.mask;
+        digit[4 * q + 3] = (v[q].w >> a.shift) & a.mask;
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < RS_IPT; ++k) {
+        uint32_t i = base + k * RS_T + threadIdx.x;
+        digit[k] = i < a.n ? (((uint32_t)minor[i] >> a.shift) & a.mask) : 0xFFFFFFFFu;
+      }
     }
   } else {
     bool bad = false;
