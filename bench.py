@@ -287,6 +287,12 @@ def other_workloads(B, W, torch, ctx, up, K, Wm):
     CP = B.us_desc_preset(B.US_F_CISR_PLUS, 1024)
     run("config2_cisr_plus_spmv", m, lambda r, c, v: [B.us_convert(ctx, m.nrows, m.ncols, r, c, v, CP)],
         lambda p: B.us_spmv(ctx, p[0], x, y), 2.0 * m.nnz, lambda p: 20.0 * m.nnz + 8.0 * m.nrows)
+    # config 2 with half of its rows emptied, so that the doubly compressed layout has rows to drop
+    m = W.cfg2_powerlaw(empty_frac=0.5)
+    x = up(W.dense_operand(2, m.ncols)); y = torch.empty(m.nrows, device=dev)
+    DCSR = B.us_desc_preset(B.US_F_DCSR)
+    run("config2_half_empty_rows_dcsr_spmv", m, lambda r, c, v: [B.us_convert(ctx, m.nrows, m.ncols, r, c, v, DCSR)],
+        lambda p: B.us_spmv(ctx, p[0], x, y), 2.0 * m.nnz, lambda p: 20.0 * m.nnz + 8.0 * p[0].idx(0).numel())
     # config 3
     m = W.cfg3_banded()
     x = up(W.dense_operand(3, m.ncols)); y = torch.empty(m.nrows, device=dev)
