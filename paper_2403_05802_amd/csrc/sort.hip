@@ -86,6 +86,7 @@ struct PassArgs {
   uint32_t nchunks;
   KeySpec ks;
   int hist_minor_only;             // IN_COO: this pass's digit lies inside the minor index of a (major, minor) key
+  int coo_vec;                     // IN_COO: row, col and val are 16-byte aligned (full tiles are read four entries a load)
   int hist_major_shift;            // IN_COO, blocked keys: >= 0 when this pass's digit lies inside the leading field
                                    // a / bh of the key: digit = ((a / bh) >> hist_major_shift) & mask
   Flags *flags;
@@ -146,10 +147,24 @@ __global__ __launch_bounds__(RS_T) void radix_hist_kernel(PassArgs a) {
     // the digit is a bit field of the block row alone: read the row indices only (the scatter of this pass reads
     // and validates both coordinates)
     const int32_t *major = a.ks.swap ? a.col : a.row;
+    if (base + RS_TILE <= a.n && (reinterpret_cast<uintptr_t>(major) & 15u) == 0) {
+      const uint4 *m4 = reinterpret_cast<const uint4 *>(major + base);   // full, aligned tile: four indices per load
+      uint4 v[RS_IPT / 4];
 #pragma unroll
-    for (int k = 0; k < RS_IPT; ++k) {
-      uint32_t i = base + k * RS_T + threadIdx.x;
-      digit[k] = i < a.n ? ((((uint32_t)major[i] / a.ks.bh) >> a.hist_major_shift) & a.mask) : 0xFFFFFFFFu;
+      for (int q = 0; q < RS_IPT / 4; ++q) v[q] = m4[q * RS_T + threadIdx.x];
+#pragma unroll
+      for (int q = 0; q < RS_IPT / 4; ++q) {
+        digit[4 * q + 0] = ((v[q].x / a.ks.bh) >> a.hist_major_shift) & a.mask;
+        digit[4 * q + 1] = ((v[q].y / a.ks.bh) >> a.hist_major_shift) & a.mask;
+        digit[4 * q + 2] = ((v[q].z / a.ks.bh) >> a.hist_major_shift) & a.mask;
+        digit[4 * q + 3] = ((v[q].w / a.ks.bh) >> a.hist_major_shift) & a.mask;
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < RS_IPT; ++k) {
+        uint32_t i = base + k * RS_T + threadIdx.x;
+        digit[k] = i < a.n ? ((((uint32_t)major[i] / a.ks.bh) >> a.hist_major_shift) & a.mask) : 0xFFFFFFFFu;
+      }
     }
   } else if (IN == IN_COO && a.hist_minor_only) {
     // the digit is a bit field of the minor index alone: read that array only (the scatter of this pass
@@ -289,11 +304,34 @@ __global__ __launch_bounds__(RS_T) void radix_scatter_kernel(PassArgs a) {
   uint32_t val[RS_IPT], pos[RS_IPT];
   bool bad = false;
   // wave w owns the contiguous slice [w*64*IPT, (w+1)*64*IPT) of the tile, lanes striped
+  if (IN == IN_COO && a.coo_vec && in_tile == (uint32_t)RS_TILE) {
+    // The caller's list has no order to keep, so which lane ranks which entry of the slice is free: four
+    // consecutive entries per 16-byte load (item 4q + c of a lane is entry q*256 + 4*lane + c of the slice).
+    static_assert(RS_IPT % 4 == 0, "entries are read four at a time");
+    const uint32_t first = base + w * (64 * RS_IPT);
+    const uint4 *r4 = reinterpret_cast<const uint4 *>(a.row + first), *c4 = reinterpret_cast<const uint4 *>(a.col + first);
+    const uint4 *v4 = reinterpret_cast<const uint4 *>(a.val_in + first);
+    uint4 rr[RS_IPT / 4], cc[RS_IPT / 4], vv[RS_IPT / 4];
 #pragma unroll
-  for (int j = 0; j < RS_IPT; ++j) {
-    uint32_t t = w * (64 * RS_IPT) + j * 64 + lane;
-    key[j] = 0; val[j] = 0;
-    if (t < in_tile) load_item<IN>(a, base + t, &key[j], &val[j], &bad);
+    for (int q = 0; q < RS_IPT / 4; ++q) { rr[q] = r4[q * 64 + lane]; cc[q] = c4[q * 64 + lane]; vv[q] = v4[q * 64 + lane]; }
+#pragma unroll
+    for (int q = 0; q < RS_IPT / 4; ++q) {
+      const uint32_t r[4] = {rr[q].x, rr[q].y, rr[q].z, rr[q].w}, c[4] = {cc[q].x, cc[q].y, cc[q].z, cc[q].w};
+      const uint32_t v[4] = {vv[q].x, vv[q].y, vv[q].z, vv[q].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        bad |= coo_out_of_range(a.ks, r[e], c[e]);
+        key[4 * q + e] = build_key(a.ks, r[e], c[e]);
+        val[4 * q + e] = v[e];
+      }
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < RS_IPT; ++j) {
+      uint32_t t = w * (64 * RS_IPT) + j * 64 + lane;
+      key[j] = 0; val[j] = 0;
+      if (t < in_tile) load_item<IN>(a, base + t, &key[j], &val[j], &bad);
+    }
   }
   if (IN == IN_COO && bad) a.flags->index_range = 1;
   __syncthreads();
@@ -794,6 +832,8 @@ static bool sort_generic(Env &env, int in_mode, const int32_t *row, const int32_
     a.tiles_per_xcd = ceil_div<uint32_t>(nblocks, 8u);
     a.hist = hist; a.chunk = chunk; a.dtotal = dtotal; a.nchunks = nchunks; a.ks = ks; a.flags = flags;
     a.hist_minor_only = first && in_mode == IN_COO && ks.mode == 0 && shifts[p] + widths[p] <= ks.b_bits && ks.b_bits <= 32;
+    a.coo_vec = first && in_mode == IN_COO &&
+                ((reinterpret_cast<uintptr_t>(row) | reinterpret_cast<uintptr_t>(col) | reinterpret_cast<uintptr_t>(val)) & 15u) == 0;
     const int lead_at = ks.b_bits + ks.ih_bits + ks.iw_bits;   // blocked keys: where the field a / bh starts
     a.hist_major_shift = (first && in_mode == IN_COO && ks.mode != 0 && shifts[p] >= lead_at) ? shifts[p] - lead_at : -1;
 
