@@ -108,7 +108,8 @@ def main():
         b = B.us_convert(ctx, m.nrows, m.ncols, r, c, v, DCSR)
         B.us_spmv(ctx, a, x, y)
         B.us_spmv(ctx, b, x, y)
-        a.free(); b.free()
+        # released without waiting for the products: torch's allocator orders the reuse of the memory with the stream
+        a.free(wait=False); b.free(wait=False)
 
     if args.pmc:
         a = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev).fill_(1.0)

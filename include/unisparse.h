@@ -18,7 +18,9 @@
  *     one read-back for most conversions, up to three for a decomposition); us_spmv /
  *     us_spmm only enqueue.
  *   - An array of a us_formatted may be allocated larger than the count us_formatted_array
- *     reports (the stored-row arrays of DCSR are sized before their count is known).
+ *     reports (the stored-row arrays of DCSR are sized before their count is known), and
+ *     several arrays of one us_formatted may lie in one allocation (each 256-byte aligned):
+ *     a pointer from us_formatted_array is for reading, never for us_ctx.free.
  *   - Every call returns a us_status; on error no output object is produced (*out = NULL)
  *     and nothing is leaked.  The library never aborts, throws or prints.
  *   - Indices are int32, values fp32 (fp32 accumulate), element counts must stay below 2^31.
@@ -183,7 +185,14 @@ us_status us_formatted_array(const us_formatted *f, int32_t level, int32_t which
                              const void **dev_ptr, int64_t *count);
 us_status us_formatted_info(const us_formatted *f, int64_t *nrows, int64_t *ncols, int64_t *nnz,
                             us_format_desc *desc);
+/* Releases a us_formatted (NULL is allowed).  us_free waits for ctx->hip_stream first, since products enqueued
+ * earlier may still read the arrays: safe with any allocator.  us_free_async does not wait: for an allocator
+ * whose free is ordered with that stream (memory freed while enqueued work still uses it is not handed to another
+ * stream or to the host before that work is done -- PyTorch's caching allocator is such, for the stream the
+ * memory was allocated on, and so is hipFreeAsync on the same stream); with hipFree itself the two are the same,
+ * as it waits by itself. */
 void us_free(const us_ctx *ctx, us_formatted *f);
+void us_free_async(const us_ctx *ctx, us_formatted *f);
 const char *us_status_str(us_status s); /* static storage */
 
 /* Optional per-kernel timing: HIP events recorded on ctx->hip_stream around every kernel the

@@ -27,7 +27,7 @@ US_P_SUM_GE_ABS, US_P_SUM_GE_FRAC_OF_CAPACITY, US_P_RANK_LT_ABS, US_P_RANK_LT_PE
 US_A_SIZE, US_A_PTR, US_A_IDX, US_A_VAL = range(4)
 
 EXPORTS = ["us_convert", "us_convert_formatted", "us_decompose", "us_spmv", "us_spmm", "us_formatted_array", "us_formatted_info",
-           "us_free", "us_status_str", "us_desc_preset", "us_profile_create", "us_profile_destroy",
+           "us_free", "us_free_async", "us_status_str", "us_desc_preset", "us_profile_create", "us_profile_destroy",
            "us_profile_reset", "us_profile_collect", "us_profile_entry", "us_profile_set_min_bytes",
            "us_set_sort_lds_finish"]
 
@@ -99,6 +99,8 @@ def lib() -> C.CDLL:
                                         C.POINTER(C.c_int64), C.POINTER(us_format_desc)]
         L.us_free.restype = None
         L.us_free.argtypes = [C.POINTER(us_ctx), C.c_void_p]
+        L.us_free_async.restype = None
+        L.us_free_async.argtypes = [C.POINTER(us_ctx), C.c_void_p]
         L.us_profile_create.argtypes = [C.POINTER(C.c_void_p)]
         L.us_profile_destroy.restype = None
         L.us_profile_destroy.argtypes = [C.c_void_p]
@@ -193,8 +195,13 @@ class Context:
         return out
 
     def tensor_at(self, ptr: int, count: int, dtype: torch.dtype) -> torch.Tensor:
-        t = self._live[ptr]
         nbytes = count * torch.empty((), dtype=dtype).element_size()
+        t = self._live.get(ptr)
+        if t is None:   # an array inside a larger allocation (a result may keep its arrays in one block)
+            for base, blk in self._live.items():
+                if base <= ptr and ptr + nbytes <= base + blk.numel():
+                    return blk[ptr - base:ptr - base + nbytes].view(dtype)
+            raise KeyError(f"device pointer {ptr:#x} does not lie in a live allocation of this context")
         return t[:nbytes].view(dtype)
 
     def live_bytes(self) -> int:
@@ -281,9 +288,12 @@ class Formatted:
     def idx(self, level): return self.us_formatted_array(level, US_A_IDX)[0]
     def val(self): return self.us_formatted_array(0, US_A_VAL)[0]
 
-    def free(self):
+    def free(self, wait: bool = True):
+        """wait=False: us_free_async, which does not wait for the stream.  The tensors behind this context come from
+        torch's caching allocator, whose reuse of freed memory is ordered with the stream they were allocated on:
+        safe as long as that is the context's stream (the current stream at its construction)."""
         if self.handle:
-            lib().us_free(C.byref(self.ctx.c), self.handle)
+            (lib().us_free if wait else lib().us_free_async)(C.byref(self.ctx.c), self.handle)
             self.handle = C.c_void_p(None)
 
     def __del__(self):

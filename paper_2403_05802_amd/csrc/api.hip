@@ -161,6 +161,12 @@ void us_free(const us_ctx *ctx, us_formatted *f) {
   free_formatted(env, f);
 }
 
+void us_free_async(const us_ctx *ctx, us_formatted *f) {
+  if (!f) return;
+  Env env(ctx);
+  free_formatted(env, f);   // the caller vouches that its free is ordered with the stream
+}
+
 // ------------------------------------------------------------------ profiling
 struct us_profile { Profile p; };
 

@@ -49,7 +49,7 @@ struct Env {
   explicit Env(const us_ctx *c)
       : ctx(c), stream(c ? (hipStream_t)c->hip_stream : nullptr), prof(c ? (Profile *)c->profile : nullptr),
         lds_finish(g_lds_finish) {}
-  ~Env() { release_temps(); }
+  ~Env() { release_temps(); drop_out(); }
 
   void *alloc_raw(size_t bytes);
   void free_raw(void *p);
@@ -71,9 +71,27 @@ struct Env {
     temps.push_back(p);
     return (T *)p;
   }
+  // The arrays of a result can come out of one block as well (reserve_out, for layouts whose array sizes are
+  // known, or bounded, before the first kernel): the result then owns the block (us_formatted::slab, handed over
+  // by adopt_out) and not its arrays one by one; free_raw leaves pointers into the block alone.  A block that no
+  // result adopted is released with the temporaries.
+  char *out_base = nullptr, *out_next = nullptr; size_t out_bytes = 0, out_left = 0;
+  bool one_result = false;          // set by the entry point whose call produces exactly one result, which adopts the block
+  void reserve_out(size_t bytes);   // (no error if it fails: owned() then allocates per array)
+  bool in_out(const void *p) const {
+    return out_base && (const char *)p >= out_base && (const char *)p < out_base + out_bytes;
+  }
+  void adopt_out(us_formatted *f);
+  void drop_out();
   template <typename T>
   T *owned(size_t count) {  // for arrays that end up in a us_formatted
-    void *p = alloc_raw(count * sizeof(T) < 256 ? 256 : count * sizeof(T));
+    const size_t need = granule(count * sizeof(T));
+    if (out_left >= need) {
+      void *p = out_next;
+      out_next += need; out_left -= need;
+      return (T *)p;
+    }
+    void *p = alloc_raw(need);
     if (!p) fail(US_ERR_ALLOC);
     return (T *)p;
   }
@@ -130,6 +148,8 @@ struct us_formatted {
   // scratch for the compute kernels (partial sums of rows cut by a tile boundary); grown on
   // demand by ensure_workspace and released by us_free.  One compute call at a time per tensor.
   mutable void *ws = nullptr; mutable size_t ws_bytes = 0;
+  // one allocation that holds some or all of the arrays above (they are then not freed one by one), or null
+  void *slab = nullptr; size_t slab_bytes = 0;
 };
 
 namespace us {

@@ -241,13 +241,18 @@ us_status flag_status(const Flags &h) {
 
 void free_formatted(Env &env, us_formatted *f) {
   if (!f) return;
+  const char *s0 = (const char *)f->slab, *s1 = s0 + f->slab_bytes;
+  auto drop = [&](void *p) {   // arrays inside the result's own block go with the block
+    if (p && !(s0 && (const char *)p >= s0 && (const char *)p < s1)) env.free_raw(p);
+  };
   for (int l = 0; l < 4; ++l) {
-    env.free_raw(f->level[l].ptr);
-    env.free_raw(f->level[l].idx);
+    drop(f->level[l].ptr);
+    drop(f->level[l].idx);
   }
-  env.free_raw(f->val);
-  env.free_raw(f->ws);
-  env.free_raw(f->mp_split);
+  drop(f->val);
+  drop(f->ws);
+  drop(f->mp_split);
+  env.free_raw(f->slab);
   delete f;
 }
 
@@ -306,14 +311,16 @@ us_formatted *new_empty_ell(Env &env, const us_format_desc &desc, int64_t nrows,
 // that move into the result (or are released when the format re-lays them out: ELL).
 us_status build_from_sorted(Env &env, const Plan &plan, const us_format_desc &desc, int64_t nrows,
                             int64_t ncols, int64_t nnz, int32_t *major, int32_t *minor, float *val,
-                            Flags *flags, bool check_dups, us_formatted **out, bool validated) {
-  // Takes ownership of major, minor and val (arrays of nnz entries from Env::owned).
+                            Flags *flags, bool check_dups, us_formatted **out, bool validated, bool major_is_temp) {
+  // Takes ownership of major, minor and val (arrays of nnz entries from Env::owned; major from Env::temp if
+  // major_is_temp, which the COO layout, the one that keeps it, does not allow).
   // validated: the caller has already read the flags after the sort (indices are in range).
+  if (major_is_temp && plan.pattern == P_COO) return US_ERR_UNSUPPORTED_DESC;
   us_formatted *f = new us_formatted();
   f->desc = desc; f->pattern = plan.pattern; f->swapped = plan.swapped;
   f->nrows = nrows; f->ncols = ncols; f->nnz = nnz;
   const int64_t nmaj = plan.swapped ? ncols : nrows;
-  bool major_loose = true, minor_loose = true, val_loose = true;  // not yet attached to f
+  bool major_loose = !major_is_temp, minor_loose = true, val_loose = true;  // not yet attached to f
   auto finish = [&](us_status s) {
     if (major_loose) env.free_raw(major);
     if (minor_loose) env.free_raw(minor);
@@ -424,7 +431,25 @@ us_status convert_with_plan(Env &env, const us_coo &coo, const Plan &plan, const
                             us_formatted **out) {
   const bool by_sort = plan.pattern == P_COO || plan.pattern == P_CSR || plan.pattern == P_DCSR ||
                        plan.pattern == P_ELL || plan.pattern == P_CISR;
-  if (by_sort) env.reserve(sort_temp_bytes(coo.nnz) + 4 * Env::granule(sizeof(Flags)));   // flags and the sort's buffers together
+  const bool rowcol = by_sort && plan.pattern != P_CISR;   // built below from the (major, minor) order
+  const int64_t n = coo.nnz;
+  if (by_sort) {
+    // two calls into the caller's allocator for the whole conversion: the flags, the sort's buffers and the other
+    // temporaries in one block, the arrays of the result in another (each call costs microseconds of an idle GPU)
+    auto g = [](size_t count) { return Env::granule(4 * count); };
+    const size_t nmaj = (size_t)(plan.swapped ? coo.ncols : coo.nrows), cap = nmaj < (size_t)n ? nmaj : (size_t)n;
+    size_t tmp = sort_temp_bytes(n) + 4 * Env::granule(sizeof(Flags)), res = 0;
+    if (rowcol && plan.pattern != P_COO) tmp += g(n);   // the major indices: only the COO layout keeps them
+    if (plan.pattern == P_COO) res = 3 * g(n);
+    if (plan.pattern == P_CSR) res = 2 * g(n) + g(nmaj + 1) + g(spmv_tiles(nmaj, n) + 1);
+    if (plan.pattern == P_DCSR) {
+      res = 2 * g(n) + g(cap) + g(cap + 1) + g(spmv_tiles(cap, n) + 1);
+      tmp += g(nmaj + 1) + 2 * g(nmaj) + g(nmaj / 1024 + 64);   // pointers over all rows, flags and positions, scan sums
+    }
+    if (plan.pattern == P_ELL) tmp += g(nmaj + 1);
+    env.reserve(tmp);
+    if (env.one_result) env.reserve_out(res);
+  }
   Flags *flags = new_flags(env);
   if (!env.ok()) return env.status;
   if (plan.pattern == P_DIA) return convert_dia(env, coo, plan, desc, flags, out);
@@ -432,14 +457,15 @@ us_status convert_with_plan(Env &env, const us_coo &coo, const Plan &plan, const
   if (plan.pattern == P_CSB) return convert_csb(env, coo, plan, desc, flags, out);
   if (plan.pattern == P_CISR) return convert_cisr(env, coo, plan, desc, flags, out);
   // COO / CSR / DCSR / ELL: sort by (major, minor), then build
-  const int64_t n = coo.nnz;
-  int32_t *major = env.owned<int32_t>(n), *minor = env.owned<int32_t>(n);
+  const bool keep_major = plan.pattern == P_COO;
+  int32_t *major = keep_major ? env.owned<int32_t>(n) : env.temp<int32_t>(n), *minor = env.owned<int32_t>(n);
   float *val = env.owned<float>(n);
-  if (!env.ok()) { env.free_raw(major); env.free_raw(minor); env.free_raw(val); return env.status; }
+  if (!env.ok()) { if (keep_major) env.free_raw(major); env.free_raw(minor); env.free_raw(val); return env.status; }
   SortOut so{};
   so.major = major; so.minor = minor; so.val = val;
   const bool checked = sort_coo(env, coo.row, coo.col, coo.val, n, rowcol_keyspec(coo, plan.swapped), so, flags);
-  return build_from_sorted(env, plan, desc, coo.nrows, coo.ncols, n, major, minor, val, flags, !checked, out);
+  return build_from_sorted(env, plan, desc, coo.nrows, coo.ncols, n, major, minor, val, flags, !checked, out, false,
+                           !keep_major);
 }
 
 us_status convert_impl(Env &env, const us_coo &coo, const us_format_desc &desc, us_formatted **out) {
@@ -449,9 +475,11 @@ us_status convert_impl(Env &env, const us_coo &coo, const us_format_desc &desc, 
   Plan plan;
   if (!match_desc(desc, &plan)) return US_ERR_UNSUPPORTED_DESC;
   if (plan.pattern == P_ELL && plan.swapped) return US_ERR_UNSUPPORTED_DESC;
+  env.one_result = true;
   s = convert_with_plan(env, coo, plan, desc, out);
   if (s == US_OK && !env.ok()) s = env.status;
   if (s != US_OK && *out) { free_formatted(env, *out); *out = nullptr; }
+  if (s == US_OK) env.adopt_out(*out);
   return s;
 }
 

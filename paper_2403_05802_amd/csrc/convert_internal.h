@@ -42,7 +42,7 @@ void sorted_ptr(Env &env, const int32_t *major, const int32_t *minor, int64_t n,
 us_formatted *new_empty_ell(Env &env, const us_format_desc &desc, int64_t nrows, int64_t ncols, int64_t nnz, int64_t K);
 us_status build_from_sorted(Env &env, const Plan &plan, const us_format_desc &desc, int64_t nrows, int64_t ncols,
                             int64_t nnz, int32_t *major, int32_t *minor, float *val, Flags *flags, bool check_dups,
-                            us_formatted **out, bool validated = false);
+                            us_formatted **out, bool validated = false, bool major_is_temp = false);
 us_status convert_with_plan(Env &env, const us_coo &coo, const Plan &plan, const us_format_desc &desc, us_formatted **out);
 
 // sum_query.hip: the sum query over diagonals / rows / columns, DIA, and the decomposition it drives

@@ -13,7 +13,7 @@ void *Env::alloc_raw(size_t bytes) {
   return p;
 }
 void Env::free_raw(void *p) {
-  if (!p) return;
+  if (!p || in_out(p)) return;
   if (ctx && ctx->alloc) { if (ctx->free) ctx->free(p, ctx->user); }
   else (void)hipFree(p);
 }
@@ -25,6 +25,25 @@ void Env::reserve(size_t bytes) {
   if (!p) return;   // temp() falls back to one allocation per array
   temps.push_back(p);
   arena = (char *)p; arena_left = granule(bytes);
+}
+
+void Env::reserve_out(size_t bytes) {
+  if (out_base || bytes == 0) return;
+  void *p = alloc_raw(granule(bytes));
+  if (!p) return;
+  out_base = out_next = (char *)p; out_bytes = out_left = granule(bytes);
+}
+void Env::adopt_out(us_formatted *f) {
+  if (!out_base || !f) return;
+  f->slab = out_base; f->slab_bytes = out_bytes;
+  out_base = out_next = nullptr; out_bytes = out_left = 0;
+}
+void Env::drop_out() {
+  if (!out_base) return;
+  (void)hipStreamSynchronize(stream);  // kernels of a failed call may still write its arrays
+  void *p = out_base;
+  out_base = out_next = nullptr; out_bytes = out_left = 0;
+  free_raw(p);
 }
 
 void Env::release_temps() {

@@ -105,6 +105,35 @@ def test_config1_csr_spmv(ctx):
     assert torch.equal(g.idx(1), g2.idx(1)) and torch.equal(g.ptr(1), g2.ptr(1))
 
 
+def test_free_without_waiting(ctx):
+    """us_free_async right after products were enqueued: the next conversion takes the freed memory over while
+    they may still run, and the stream order keeps their results intact."""
+    from paper_2403_05802_amd import binding as B
+    from helpers import TOL, assert_same_layout, dev, host, rel_err, us_desc_of
+    m = W.cfg2_powerlaw(n=1 << 15, target_nnz=1 << 20, max_len=4000)
+    r, c, v = dev(m.row), dev(m.col), dev(m.val)
+    rng = np.random.default_rng(3)
+    x = rng.uniform(-1, 1, m.ncols).astype(np.float32)
+    yref = O.spmv_coo(m.nrows, m.ncols, m.row, m.col, m.val, x)
+    scale = O.abs_row_sums(m.nrows, m.row, m.col, m.val, x)
+    xd = dev(x)
+    before = ctx.live_bytes()
+    ys = []
+    for d in (O.CSR(), O.DCSR(), O.CSC(), O.CSR()):
+        g = B.us_convert(ctx, m.nrows, m.ncols, r, c, v, us_desc_of(d))
+        y = torch.empty(m.nrows, device="cuda")
+        for _ in range(3):
+            B.us_spmv(ctx, g, xd, y)
+        g.free(wait=False)
+        ys.append(y)
+    g = B.us_convert(ctx, m.nrows, m.ncols, r, c, v, us_desc_of(O.CSR()))
+    assert_same_layout(g, O.convert(m.nrows, m.ncols, m.row, m.col, m.val, O.CSR()), "after async frees")
+    g.free()
+    for y in ys:
+        assert rel_err(host(y), yref, scale) <= TOL
+    assert ctx.live_bytes() == before
+
+
 def test_error_paths(ctx):
     from paper_2403_05802_amd import binding as B
     from helpers import dev, us_desc_of
@@ -127,13 +156,22 @@ def test_error_paths(ctx):
         B.us_convert(ctx, 3, 3, dev(np.array([1, 1], np.int32)), dev(np.array([0, 2], np.int32)), dev(v[:2]),
                      us_desc_of(O.ELL(1)))
     assert ei.value.code == "US_ERR_SHAPE"
-    # allocator failure leaves nothing behind
+    # allocator failure leaves nothing behind, whichever of a call's allocations is the first to fail
     before = ctx.live_bytes()
-    ctx.fail_alloc_after = ctx._nalloc + 2
-    with pytest.raises(B.UnisparseError) as ei:
-        B.us_convert(ctx, 3, 3, dev(r[:2]), dev(c[:2]), dev(v[:2]), us_desc_of(O.CSR()))
-    ctx.fail_alloc_after = None
-    assert ei.value.code == "US_ERR_ALLOC" and ctx.live_bytes() == before
+    for d in (O.CSR(), O.COO(), O.DCSR(), O.DCSC(), O.ELL(), O.BCSR(2), O.DIA(), O.CISR_PLUS(2)):
+        failed = 0
+        for k in range(12):
+            ctx.fail_alloc_after = ctx._nalloc + k
+            try:
+                g = B.us_convert(ctx, 3, 3, dev(r[:2]), dev(c[:2]), dev(v[:2]), us_desc_of(d))
+                ctx.fail_alloc_after = None
+                g.free()
+            except B.UnisparseError as e:
+                ctx.fail_alloc_after = None
+                assert e.code == "US_ERR_ALLOC", (d, k)
+                failed += 1
+            assert ctx.live_bytes() == before, (d, k)
+        assert failed >= 1, d   # (k = 0: the very first allocation fails)
     g = B.us_convert(ctx, 3, 3, dev(r[:2]), dev(c[:2]), dev(v[:2]), us_desc_of(O.CSR()))
     X = torch.zeros(3, 4, device="cuda")
     with pytest.raises(B.UnisparseError) as ei:   # N = 0
