@@ -1,6 +1,7 @@
 // Internal host/device helpers shared by the translation units of the library.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <string.h>
 
@@ -102,19 +103,27 @@ struct Env {
   void sync() { check(hipStreamSynchronize(stream)); }
 };
 
-struct LaunchScope {  // brackets one kernel launch with events when profiling is on
-  Env &env; int idx = -1; hipEvent_t a{}, b{}; double bytes;
-  LaunchScope(Env &e, const char *name, double alg_bytes);
+// Times one kernel launch with a pair of events when profiling is on.  in_dispatch: the launch itself carries the
+// events (hipExtLaunchKernelGGL: they take the start and end of that dispatch, no marker packets before and
+// after it, which cost the queue ~5 us a pair); otherwise the events are recorded around whatever the scope holds.
+struct LaunchScope {
+  Env &env; int idx = -1; hipEvent_t a{}, b{}; double bytes; bool in_dispatch;
+  LaunchScope(Env &e, const char *name, double alg_bytes, bool in_dispatch = false);
   ~LaunchScope();
+  bool active() const { return idx >= 0; }
 };
 
 // US_LAUNCH(env, "name", algorithmic_bytes, kernel<...>, grid, block, args...)
 #define US_LAUNCH(env, name, algbytes, kern, grid, block, ...)                         \
   do {                                                                                 \
     if ((env).ok()) {                                                                  \
-      ::us::LaunchScope _ls((env), (name), (double)(algbytes));                        \
-      hipLaunchKernelGGL(kern, dim3((unsigned)(grid)), dim3((unsigned)(block)), 0,     \
-                         (env).stream, __VA_ARGS__);                                   \
+      ::us::LaunchScope _ls((env), (name), (double)(algbytes), true);                  \
+      if (_ls.active())                                                                \
+        hipExtLaunchKernelGGL(kern, dim3((unsigned)(grid)), dim3((unsigned)(block)), 0, \
+                              (env).stream, _ls.a, _ls.b, 0, __VA_ARGS__);             \
+      else                                                                             \
+        hipLaunchKernelGGL(kern, dim3((unsigned)(grid)), dim3((unsigned)(block)), 0,   \
+                           (env).stream, __VA_ARGS__);                                 \
       (env).check(hipGetLastError());                                                  \
     }                                                                                  \
   } while (0)

@@ -67,16 +67,18 @@ hipEvent_t Profile::get_event() {
   return e;
 }
 
-LaunchScope::LaunchScope(Env &e, const char *name, double alg_bytes) : env(e), bytes(alg_bytes) {
+LaunchScope::LaunchScope(Env &e, const char *name, double alg_bytes, bool in_dispatch_)
+    : env(e), bytes(alg_bytes), in_dispatch(in_dispatch_) {
   if (!env.prof || alg_bytes < env.prof->min_bytes) return;
   idx = env.prof->intern(name);
   a = env.prof->get_event();
   b = env.prof->get_event();
-  env.check(hipEventRecord(a, env.stream));
+  if (!a || !b) { idx = -1; env.fail(US_ERR_HIP); return; }
+  if (!in_dispatch) env.check(hipEventRecord(a, env.stream));
 }
 LaunchScope::~LaunchScope() {
   if (!env.prof || idx < 0) return;
-  env.check(hipEventRecord(b, env.stream));
+  if (!in_dispatch) env.check(hipEventRecord(b, env.stream));
   env.prof->pending.push_back({idx, a, b, bytes});
 }
 
