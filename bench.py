@@ -28,7 +28,7 @@ FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix peak, published
 # HBM bytes per launch (fetched + written) of the dominant kernel on the headline workload, from the
 # two rocprofv3 --pmc runs summarised in profiles/config2_hbm_traffic_pmc.txt (mean over all
 # scatter launches; FETCH_SIZE x2.00, WRITE_SIZE x1.00 after calibration with a plain copy)
-PMC_TRAFFIC_BYTES = {"radix_scatter": 436.8e6}
+PMC_TRAFFIC_BYTES = {"radix_scatter": 435.1e6}
 
 
 def parse():
