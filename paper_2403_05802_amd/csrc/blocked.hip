@@ -120,6 +120,8 @@ us_status emit_blocked(Env &env, const Plan &plan, const us_format_desc &desc, i
   f->nrows = nrows; f->ncols = ncols; f->nnz = n;
   f->nlevels = bdia ? 3 : 4;
   f->level[0].size = nbr;
+  if (env.one_result)   // the sizes are known now: one block for the three arrays
+    env.reserve_out(Env::granule(4 * (size_t)(nbr + 1)) + Env::granule(4 * (size_t)nblk) + Env::granule(4 * (size_t)(nblk * bsz)));
   f->level[1].ptr = env.owned<int32_t>(nbr + 1); f->level[1].nptr = nbr + 1;
   f->level[1].idx = env.owned<int32_t>(nblk); f->level[1].nidx = nblk;
   f->level[2].size = plan.bh;
@@ -128,7 +130,9 @@ us_status emit_blocked(Env &env, const Plan &plan, const us_format_desc &desc, i
   f->nmajor = nbr; f->bh = plan.bh; f->bw = plan.bw; f->nblk = nblk;
   int32_t *blk_row = env.temp<int32_t>(nblk);
   if (!env.ok()) { free_formatted(env, f); return env.status; }
-  fill_u32(env, (uint32_t *)f->val, nblk * bsz, 0u);
+  // (the flags just read say that the keys are distinct and in range: with as many entries as slots every slot
+  // receives a value and nothing needs clearing first)
+  if (nblk * bsz != n) fill_u32(env, (uint32_t *)f->val, nblk * bsz, 0u);
   if (n > 0)
     US_LAUNCH(env, "bcsr_emit", 12.0 * n + 4.0 * n, bcsr_emit_kernel, nb, BE_T, skey, sval, n, ks,
               (int32_t)(bdia ? nrows - 1 : 0), (const uint32_t *)partial, blk_row, f->level[1].idx, f->val);

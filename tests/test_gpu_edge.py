@@ -259,3 +259,23 @@ def test_hypersparse_dcsr_array_counts(ctx):
     assert float(y[5]) == 3.0 and float(y[17]) == 15.0 and float(y[2_999_999]) == 3.0 and float(y.sum()) == 21.0
     g.free()
     roundtrip(ctx, n, n, r, c, v, [O.DCSR(), O.CSR(), O.DCSC()])
+
+
+@pytest.mark.parametrize("shift", [(1, 0, 0), (0, 2, 0), (0, 0, 3), (1, 2, 3)], ids=["row", "col", "val", "all"])
+def test_coordinate_arrays_that_are_not_16_byte_aligned(ctx, shift):
+    """The first pass of the sort reads four entries per load when the caller's arrays are 16-byte aligned; arrays
+    that start 4, 8 or 12 bytes into an allocation take the one-entry loads and must give the same layouts."""
+    from paper_2403_05802_amd import binding as B
+    from helpers import assert_same_layout, dev, us_desc_of
+    rng = np.random.default_rng(11)
+    nr, nc, n = 3000, 2500, 4096 * 3 + 517        # several full tiles and a ragged one
+    lin = rng.choice(nr * nc, size=n, replace=False)
+    r, c = (lin // nc).astype(np.int32), (lin % nc).astype(np.int32)
+    v = rng.uniform(0.1, 1, n).astype(np.float32)
+    pad = lambda a, k: dev(np.concatenate([np.zeros(k, a.dtype), a]))[k:]
+    rd, cd, vd = pad(r, shift[0]), pad(c, shift[1]), pad(v, shift[2])
+    assert rd.data_ptr() % 16 == 4 * shift[0] and cd.data_ptr() % 16 == 4 * shift[1] and vd.data_ptr() % 16 == 4 * shift[2]
+    for d in (O.CSR(), O.CSC(), O.BCSR(4), O.BDIA(4), O.ELL()):
+        g = B.us_convert(ctx, nr, nc, rd, cd, vd, us_desc_of(d))
+        assert_same_layout(g, O.convert(nr, nc, r, c, v, d), f"{d} shift {shift}")
+        g.free()
