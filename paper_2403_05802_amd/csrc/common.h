@@ -223,9 +223,7 @@ bool sort_coo(Env &env, const int32_t *row, const int32_t *col, const float *val
               const KeySpec &ks, const SortOut &out, Flags *flags_dev);
 // what a whole-array sort of nnz entries takes from Env::temp (for Env::reserve by a caller with temporaries of its own)
 size_t sort_temp_bytes(int64_t nnz);
-// ascending sort of 32-bit keys
-void sort_u32(Env &env, const uint32_t *key, int64_t n, int bits, uint32_t *out, Flags *flags_dev);
-// the same, stable, with a 32-bit payload that travels with its key
+// stable ascending sort of 32-bit keys with a 32-bit payload that travels with its key
 void sort_u32_payload(Env &env, const uint32_t *key, const uint32_t *payload, int64_t n, int bits, uint32_t *key_out,
                       uint32_t *payload_out, Flags *flags_dev);
 // convert.hip

@@ -6,11 +6,52 @@
 namespace us {
 
 // ------------------------------------------------------------------ decompose
-__global__ __launch_bounds__(256) void row_len_kernel(const int32_t *ptr, int64_t n, uint32_t *len) {
-  int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (g < n) len[g] = (uint32_t)(ptr[g + 1] - ptr[g]);
+// The row length of a given rank (the nearest-rank percentile) without sorting the lengths: digit by digit from
+// the top, a pass counts the values of the next digit among the rows whose length agrees with the digits picked
+// so far, and the workgroup that finishes last picks the digit that holds the rank and clears the counters for
+// the next pass (no workgroup waits for another).
+struct SelectState { uint32_t prefix, rank, done, pad; uint32_t hist[256]; };
+constexpr int SEL_GRID = 256;
+
+__global__ __launch_bounds__(256) void select_init_kernel(SelectState *s, uint32_t rank) {
+  s->hist[threadIdx.x] = 0;
+  if (threadIdx.x == 0) { s->prefix = 0; s->rank = rank; s->done = 0; s->pad = 0; }
 }
-__global__ void pick_kernel(const uint32_t *sorted, int64_t at, int32_t *out) { *out = (int32_t)sorted[at]; }
+__global__ __launch_bounds__(256) void select_pass_kernel(const int32_t *ptr, int64_t nrows, int shift, int bits,
+                                                         SelectState *s, int32_t *out) {   // out: last pass only
+  __shared__ uint32_t s_hist[256];
+  __shared__ uint32_t s_wave[256 / 64 + 1];
+  __shared__ bool s_last;
+  s_hist[threadIdx.x] = 0;
+  __syncthreads();
+  const uint32_t prefix = s->prefix, rank = s->rank;   // left by the previous pass
+  const int hi = shift + bits;
+  const uint32_t mask = (1u << bits) - 1u;
+  for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < nrows; g += (int64_t)gridDim.x * 256) {
+    const uint32_t v = (uint32_t)(ptr[g + 1] - ptr[g]);
+    if ((hi >= 32 ? 0u : v >> hi) == prefix) atomicAdd(&s_hist[(v >> shift) & mask], 1u);
+  }
+  __syncthreads();
+  const uint32_t mine = s_hist[threadIdx.x];
+  if (mine) atomicAdd(&s->hist[threadIdx.x], mine);
+  __threadfence();   // the adds above come before this workgroup is counted as done
+  __syncthreads();
+  if (threadIdx.x == 0) s_last = atomicAdd(&s->done, 1u) == gridDim.x - 1;
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  const uint32_t cnt = atomicAdd(&s->hist[threadIdx.x], 0u);   // read where the adds were made
+  uint32_t total;
+  const uint32_t before = block_exclusive_sum<256>(cnt, s_wave, &total);
+  s->hist[threadIdx.x] = 0;
+  if (threadIdx.x == 0) s->done = 0;
+  if (cnt > 0 && before <= rank && rank < before + cnt) {   // one thread, unless the lengths are garbage
+    const uint32_t picked = (prefix << bits) | threadIdx.x;
+    s->prefix = picked;
+    s->rank = rank - before;
+    if (out) *out = (int32_t)picked;
+  }
+}
 
 // K_dev != null: the cut is still on the device (the percentile picked just before)
 __global__ __launch_bounds__(256) void clipped_len_kernel(const int32_t *ptr, int64_t n, int64_t K, const int32_t *K_dev,
@@ -55,8 +96,13 @@ static bool row_major_family(const Plan &p) {
 static us_status decompose_rank(Env &env, const us_coo &coo, const Plan &pa, const us_format_desc &da, const Plan &pb,
                                 const us_format_desc &db, const us_predicate &pred, us_formatted **oa,
                                 us_formatted **ob) {
-  Flags *flags = new_flags(env);
   const int64_t n = coo.nnz, nrows = coo.nrows;
+  {  // every temporary of the call in one allocation
+    auto g = [](size_t count) { return Env::granule(4 * count); };
+    env.reserve(sort_temp_bytes(n) + 3 * g(n) + 3 * g(nrows + 1) + g(nrows) + g(nrows / 1024 + 64) +
+                Env::granule(sizeof(SelectState)) + 4 * Env::granule(sizeof(Flags)));
+  }
+  Flags *flags = new_flags(env);
   int32_t *major = env.temp<int32_t>(n), *minor = env.temp<int32_t>(n);
   float *val = env.temp<float>(n);
   int32_t *ptr = env.temp<int32_t>(nrows + 1), *ptr_a = env.temp<int32_t>(nrows + 1), *clip = env.temp<int32_t>(nrows + 1);
@@ -68,17 +114,23 @@ static us_status decompose_rank(Env &env, const us_coo &coo, const Plan &pa, con
   Flags h{};
   int64_t K = pred.abs;
   if (pred.kind == US_P_RANK_LT_PERCENTILE) {
-    // nearest-rank percentile of the row lengths over all rows: sort the lengths, pick one
-    uint32_t *len = env.temp<uint32_t>(nrows), *slen = env.temp<uint32_t>(nrows);
+    // nearest-rank percentile of the row lengths over all rows: the length of rank k - 1 in ascending order
+    SelectState *sel = env.temp<SelectState>(1);
     if (!env.ok()) return env.status;
-    US_LAUNCH(env, "row_len", 8.0 * nrows, row_len_kernel, ceil_div<int64_t>(nrows, 256), 256, (const int32_t *)ptr,
-              nrows, len);
     const int64_t maxlen = n < coo.ncols ? n : coo.ncols;
-    sort_u32(env, len, nrows, bits_for((uint64_t)maxlen), slen, flags);
     int64_t k = (pred.num * nrows + pred.den - 1) / pred.den;
     if (k < 1) k = 1;
     if (k > nrows) k = nrows;
-    US_LAUNCH(env, "pick", 8.0, pick_kernel, 1, 1, (const uint32_t *)slen, k - 1, &flags->scalar[2]);
+    US_LAUNCH(env, "select_init", 1024.0, select_init_kernel, 1, 256, sel, (uint32_t)(k - 1));
+    const int total_bits = bits_for((uint64_t)maxlen) > 0 ? bits_for((uint64_t)maxlen) : 1;
+    const int npass = ceil_div(total_bits, 8);
+    const int64_t grid = ceil_div<int64_t>(nrows, 256) < SEL_GRID ? ceil_div<int64_t>(nrows, 256) : SEL_GRID;
+    for (int p = 0, left = total_bits; p < npass; ++p) {
+      const int w = total_bits / npass + (p < total_bits % npass ? 1 : 0);
+      left -= w;
+      US_LAUNCH(env, "select_pass", 4.0 * nrows, select_pass_kernel, grid, 256, (const int32_t *)ptr, nrows, left, w, sel,
+                p == npass - 1 ? &flags->scalar[2] : (int32_t *)nullptr);
+    }
   }
   // the cut K (if picked above), the size of part A and the longest row all come back in one read of the flags
   const bool by_percentile = pred.kind == US_P_RANK_LT_PERCENTILE;

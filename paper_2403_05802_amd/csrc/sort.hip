@@ -903,18 +903,7 @@ bool sort_coo(Env &env, const int32_t *row, const int32_t *col, const float *val
   return sort_generic(env, IN_COO, row, col, nullptr, val, nnz, ks, out, flags_dev);
 }
 
-// ascending sort of 32-bit keys (no payload of interest)
-void sort_u32(Env &env, const uint32_t *key, int64_t n, int bits, uint32_t *out, Flags *flags_dev) {
-  if (n <= 0) return;
-  KeySpec ks{};
-  ks.total_bits = bits;
-  float *dummy_in = env.temp<float>(n), *dummy_out = env.temp<float>(n);
-  if (!env.ok()) return;
-  SortOut so{};
-  so.key32 = out; so.val = dummy_out;
-  sort_generic(env, IN_KEY32, nullptr, nullptr, key, dummy_in, n, ks, so, flags_dev);
-}
-
+// stable ascending sort of 32-bit keys that carry a 32-bit payload
 void sort_u32_payload(Env &env, const uint32_t *key, const uint32_t *payload, int64_t n, int bits, uint32_t *key_out,
                       uint32_t *payload_out, Flags *flags_dev) {
   if (n <= 0) return;

@@ -279,3 +279,37 @@ def test_coordinate_arrays_that_are_not_16_byte_aligned(ctx, shift):
         g = B.us_convert(ctx, nr, nc, rd, cd, vd, us_desc_of(d))
         assert_same_layout(g, O.convert(nr, nc, r, c, v, d), f"{d} shift {shift}")
         g.free()
+
+
+def test_percentile_cut_over_many_length_distributions(ctx):
+    """The nearest-rank percentile of the row lengths is picked on the device digit by digit: lengths that need one,
+    two and three digits, many equal lengths, empty rows, more rows than one sweep of the counting grid covers, and
+    ranks at both ends."""
+    from paper_2403_05802_amd import binding as B
+    from helpers import assert_same_layout, dev, us_desc_of, us_pred_of
+    rng = np.random.default_rng(21)
+
+    def matrix(lens, ncols):
+        r = np.repeat(np.arange(lens.size, dtype=np.int64), lens)
+        c = np.concatenate([rng.choice(ncols, size=l, replace=False) for l in lens if l > 0]) if r.size else r
+        p = rng.permutation(r.size)
+        return r[p].astype(np.int32), c[p].astype(np.int32), rng.uniform(0.1, 1, r.size).astype(np.float32)
+
+    cases = [
+        (rng.integers(0, 9, 700), 40),                                             # one digit, ties everywhere
+        (np.where(rng.random(3000) < 0.9, 3, 300).astype(np.int64), 1000),         # two values far apart
+        (np.minimum(rng.zipf(1.6, 5000), 2_000).astype(np.int64), 70_000),         # three digits (17-bit lengths), long tail
+        (np.concatenate([np.zeros(66_000, np.int64), np.array([5, 1, 2])]), 8),    # nearly all rows empty, > 256*256 rows
+        (np.full(513, 7, np.int64), 7),                                            # all equal, full rows
+    ]
+    for lens, ncols in cases:
+        nrows = int(lens.size)
+        r, c, v = matrix(lens, ncols)
+        for num, den in ((9, 10), (1, 2), (1, 1), (1, 1000), (999, 1000)):
+            pred = O.Predicate((O.d0(),), O.RANK_LT_PERCENTILE, num=num, den=den)
+            oa, ob, _ = O.decompose(nrows, ncols, r, c, v, O.ELL(), O.COO(), pred)
+            ga, gb = B.us_decompose(ctx, nrows, ncols, dev(r), dev(c), dev(v), us_desc_of(O.ELL()), us_desc_of(O.COO()),
+                                    us_pred_of(pred))
+            assert_same_layout(ga, oa, f"ELL part, {nrows} rows, {num}/{den}")
+            assert_same_layout(gb, ob, f"COO part, {nrows} rows, {num}/{den}")
+            ga.free(); gb.free()
