@@ -449,6 +449,12 @@ us_status convert_with_plan(Env &env, const us_coo &coo, const Plan &plan, const
     if (plan.pattern == P_ELL) tmp += g(nmaj + 1);
     env.reserve(tmp);
     if (env.one_result) env.reserve_out(res);
+  } else if (plan.pattern == P_DIA) {   // counters, flags, positions and slab indices of the diagonals, scan sums
+    const size_t nbins = (size_t)(coo.nrows + coo.ncols);
+    env.reserve(4 * Env::granule(4 * nbins) + Env::granule(4 * (nbins / 1024 + 64)) + 8 * Env::granule(256));
+  } else if (plan.pattern == P_BCSR || plan.pattern == P_BDIA) {   // sorted keys and values, block counts per tile
+    env.reserve(Env::granule(8 * (size_t)n) + Env::granule(4 * (size_t)n) + Env::granule(4 * ((size_t)n / 1024 + 64)) +
+                8 * Env::granule(256));
   }
   Flags *flags = new_flags(env);
   if (!env.ok()) return env.status;

@@ -303,6 +303,11 @@ static GroupCounts group_flags(Env &env, const us_coo &coo, int gkind, int pkind
   return g;
 }
 
+// what the histogram, the flags and (for DIA) the positions and slab indices of the groups take from Env::temp
+static size_t group_temp_bytes(int64_t nbins) {
+  return 4 * Env::granule(4 * (size_t)nbins) + Env::granule(4 * ((size_t)nbins / 1024 + 64)) + 8 * Env::granule(256);
+}
+
 us_status convert_dia(Env &env, const us_coo &coo, const Plan &plan, const us_format_desc &desc,
                       Flags *flags, us_formatted **out) {
   GroupCounts g = group_flags(env, coo, G_DIAG, -1, 0, 1, 0, flags);
@@ -313,6 +318,7 @@ us_status convert_dia(Env &env, const us_coo &coo, const Plan &plan, const us_fo
 us_status decompose_sum(Env &env, const us_coo &coo, const Plan &pa, const us_format_desc &da, const Plan &pb,
                         const us_format_desc &db, const us_predicate &pred, int gkind, us_formatted **oa,
                         us_formatted **ob) {
+  env.reserve(group_temp_bytes(gkind == G_DIAG ? coo.nrows + coo.ncols - 1 : (gkind == G_ROW ? coo.nrows : coo.ncols)));
   Flags *flags = new_flags(env);
   if (!env.ok()) return env.status;
   GroupCounts g = group_flags(env, coo, gkind, pred.kind, pred.num, pred.den, pred.abs, flags);
