@@ -7,44 +7,54 @@ namespace us {
 
 // ------------------------------------------------------------------ decompose
 // The row length of a given rank (the nearest-rank percentile) without sorting the lengths: digit by digit from
-// the top, a pass counts the values of the next digit among the rows whose length agrees with the digits picked
-// so far, and the workgroup that finishes last picks the digit that holds the rank and clears the counters for
-// the next pass (no workgroup waits for another).
-struct SelectState { uint32_t prefix, rank, done, pad; uint32_t hist[256]; };
-constexpr int SEL_GRID = 256;
+// the top, one kernel counts the values of the next digit among the rows whose length agrees with the digits
+// picked so far, the next one picks the digit that holds the rank.  Every workgroup of the count leaves its 256
+// counts in a row of its own and the pick adds the rows up: the lengths of a matrix crowd into a few values, and
+// adds from a thousand workgroups to the same few device counters took their turns at ~20 ns each (63 us a pass
+// on 2 M rows); a single kernel per pass, whose last workgroup picks, was slower too (37 us: every workgroup
+// then needs a device-wide fence, which writes its L2 back).
+constexpr int SEL_GRID = 256, SEL_IPT = 8, SEL_TILE = 256 * SEL_IPT;
+struct SelectState { uint32_t prefix, rank, pad[2]; uint32_t hist[SEL_GRID][256]; };
 
-__global__ __launch_bounds__(256) void select_init_kernel(SelectState *s, uint32_t rank) {
-  s->hist[threadIdx.x] = 0;
-  if (threadIdx.x == 0) { s->prefix = 0; s->rank = rank; s->done = 0; s->pad = 0; }
-}
-__global__ __launch_bounds__(256) void select_pass_kernel(const int32_t *ptr, int64_t nrows, int shift, int bits,
-                                                         SelectState *s, int32_t *out) {   // out: last pass only
+__global__ void select_init_kernel(SelectState *s, uint32_t rank) { s->prefix = 0; s->rank = rank; }
+
+__global__ __launch_bounds__(256) void select_count_kernel(const int32_t *ptr, int64_t nrows, int shift, int bits,
+                                                          SelectState *s) {
   __shared__ uint32_t s_hist[256];
-  __shared__ uint32_t s_wave[256 / 64 + 1];
-  __shared__ bool s_last;
   s_hist[threadIdx.x] = 0;
   __syncthreads();
-  const uint32_t prefix = s->prefix, rank = s->rank;   // left by the previous pass
+  const uint32_t prefix = s->prefix;   // left by the previous pick
   const int hi = shift + bits;
   const uint32_t mask = (1u << bits) - 1u;
-  for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < nrows; g += (int64_t)gridDim.x * 256) {
-    const uint32_t v = (uint32_t)(ptr[g + 1] - ptr[g]);
-    if ((hi >= 32 ? 0u : v >> hi) == prefix) atomicAdd(&s_hist[(v >> shift) & mask], 1u);
+  for (int64_t base = (int64_t)blockIdx.x * SEL_TILE; base < nrows; base += (int64_t)gridDim.x * SEL_TILE) {
+    uint32_t v[SEL_IPT];
+#pragma unroll
+    for (int k = 0; k < SEL_IPT; ++k) {   // all loads first
+      const int64_t g = base + k * 256 + threadIdx.x;
+      v[k] = g < nrows ? (uint32_t)(ptr[g + 1] - ptr[g]) : 0xFFFFFFFFu;
+    }
+#pragma unroll
+    for (int k = 0; k < SEL_IPT; ++k) {
+      const int64_t g = base + k * 256 + threadIdx.x;
+      if (g < nrows && (hi >= 32 ? 0u : v[k] >> hi) == prefix) atomicAdd(&s_hist[(v[k] >> shift) & mask], 1u);
+    }
   }
   __syncthreads();
-  const uint32_t mine = s_hist[threadIdx.x];
-  if (mine) atomicAdd(&s->hist[threadIdx.x], mine);
-  __threadfence();   // the adds above come before this workgroup is counted as done
-  __syncthreads();
-  if (threadIdx.x == 0) s_last = atomicAdd(&s->done, 1u) == gridDim.x - 1;
-  __syncthreads();
-  if (!s_last) return;
-  __threadfence();
-  const uint32_t cnt = atomicAdd(&s->hist[threadIdx.x], 0u);   // read where the adds were made
+  s->hist[blockIdx.x][threadIdx.x] = s_hist[threadIdx.x];
+}
+__global__ __launch_bounds__(256) void select_pick_kernel(SelectState *s, int nrows_hist, int bits, int32_t *out) {   // out: last pass only
+  __shared__ uint32_t s_wave[256 / 64 + 1];
+  const uint32_t prefix = s->prefix, rank = s->rank;
+  uint32_t cnt = 0;
+  for (int w0 = 0; w0 < nrows_hist; w0 += 32) {   // 32 loads in flight
+    uint32_t part[32];
+#pragma unroll
+    for (int k = 0; k < 32; ++k) part[k] = w0 + k < nrows_hist ? s->hist[w0 + k][threadIdx.x] : 0u;
+#pragma unroll
+    for (int k = 0; k < 32; ++k) cnt += part[k];
+  }
   uint32_t total;
   const uint32_t before = block_exclusive_sum<256>(cnt, s_wave, &total);
-  s->hist[threadIdx.x] = 0;
-  if (threadIdx.x == 0) s->done = 0;
   if (cnt > 0 && before <= rank && rank < before + cnt) {   // one thread, unless the lengths are garbage
     const uint32_t picked = (prefix << bits) | threadIdx.x;
     s->prefix = picked;
@@ -121,14 +131,15 @@ static us_status decompose_rank(Env &env, const us_coo &coo, const Plan &pa, con
     int64_t k = (pred.num * nrows + pred.den - 1) / pred.den;
     if (k < 1) k = 1;
     if (k > nrows) k = nrows;
-    US_LAUNCH(env, "select_init", 1024.0, select_init_kernel, 1, 256, sel, (uint32_t)(k - 1));
+    US_LAUNCH(env, "select_init", 8.0, select_init_kernel, 1, 1, sel, (uint32_t)(k - 1));
     const int total_bits = bits_for((uint64_t)maxlen) > 0 ? bits_for((uint64_t)maxlen) : 1;
     const int npass = ceil_div(total_bits, 8);
-    const int64_t grid = ceil_div<int64_t>(nrows, 256) < SEL_GRID ? ceil_div<int64_t>(nrows, 256) : SEL_GRID;
+    const int64_t grid = ceil_div<int64_t>(nrows, SEL_TILE) < SEL_GRID ? ceil_div<int64_t>(nrows, SEL_TILE) : SEL_GRID;
     for (int p = 0, left = total_bits; p < npass; ++p) {
       const int w = total_bits / npass + (p < total_bits % npass ? 1 : 0);
       left -= w;
-      US_LAUNCH(env, "select_pass", 4.0 * nrows, select_pass_kernel, grid, 256, (const int32_t *)ptr, nrows, left, w, sel,
+      US_LAUNCH(env, "select_count", 4.0 * nrows, select_count_kernel, grid, 256, (const int32_t *)ptr, nrows, left, w, sel);
+      US_LAUNCH(env, "select_pick", 1024.0 * grid, select_pick_kernel, 1, 256, sel, (int)grid, w,
                 p == npass - 1 ? &flags->scalar[2] : (int32_t *)nullptr);
     }
   }
