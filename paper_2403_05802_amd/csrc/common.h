@@ -118,7 +118,7 @@ struct LaunchScope {
   do {                                                                                 \
     if ((env).ok()) {                                                                  \
       ::us::LaunchScope _ls((env), (name), (double)(algbytes), true);                  \
-      if (_ls.active())                                                                \
+      if (_ls.active() && _ls.in_dispatch)                                             \
         hipExtLaunchKernelGGL(kern, dim3((unsigned)(grid)), dim3((unsigned)(block)), 0, \
                               (env).stream, _ls.a, _ls.b, 0, __VA_ARGS__);             \
       else                                                                             \

@@ -70,6 +70,11 @@ hipEvent_t Profile::get_event() {
 LaunchScope::LaunchScope(Env &e, const char *name, double alg_bytes, bool in_dispatch_)
     : env(e), bytes(alg_bytes), in_dispatch(in_dispatch_) {
   if (!env.prof || alg_bytes < env.prof->min_bytes) return;
+  // With every launch timed (no byte threshold) the events are recorded around the launches: in-dispatch pairs on
+  // runs of short back-to-back kernels came out several times too long (a 5 us kernel reported with the duration
+  // of the 180 us one that followed it), while on the few large launches that a threshold selects they agree
+  // with rocprofv3's kernel trace to a few tenths of a microsecond.
+  if (env.prof->min_bytes <= 0.0) in_dispatch = false;
   idx = env.prof->intern(name);
   a = env.prof->get_event();
   b = env.prof->get_event();
