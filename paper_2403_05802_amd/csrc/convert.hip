@@ -135,14 +135,17 @@ __global__ __launch_bounds__(256) void max_len_kernel(const int32_t *ptr, int64_
 // EF_SLOTS slots at a time through LDS -- in, EF_RPL rows per load instruction (EF_SLOTS consecutive entries of a
 // row each); out, a lane per row, 256 contiguous bytes per slot and array, pads included (no separate fill).
 constexpr int EF_ROWS = 64, EF_SLOTS = 16, EF_PITCH = EF_SLOTS + 1, EF_RPL = 64 / EF_SLOTS;   // rows per load instruction
+// clip >= 0: only the first `clip` entries of a row belong to this layout (the rank split of a decomposition).
 __global__ __launch_bounds__(64) void ell_fill_kernel(const int32_t *minor, const float *val, const int32_t *ptr,
-                                                     int64_t nrows, int64_t K, int32_t *ecol, float *eval,
+                                                     int64_t nrows, int64_t K, int64_t clip, int32_t *ecol, float *eval,
                                                      Flags *flags) {
   __shared__ int32_t s_col[EF_ROWS * EF_PITCH];
   __shared__ float s_val[EF_ROWS * EF_PITCH];
   const int lane = threadIdx.x;
   const int64_t r = (int64_t)blockIdx.x * EF_ROWS + lane;
-  const int64_t start = r < nrows ? ptr[r] : 0, len = r < nrows ? ptr[r + 1] - start : 0;
+  const int64_t start = r < nrows ? ptr[r] : 0;
+  int64_t len = r < nrows ? ptr[r + 1] - start : 0;
+  if (clip >= 0 && len > clip) len = clip;
   if (len > K) flags->ell_overflow = 1;
   for (int64_t k0 = 0; k0 < K; k0 += EF_SLOTS) {
 #pragma unroll 4
@@ -297,12 +300,22 @@ static bool ell_shell(Env &env, us_formatted *f, int64_t K, bool fill = true) {
   return true;
 }
 
-us_formatted *new_empty_ell(Env &env, const us_format_desc &desc, int64_t nrows, int64_t ncols, int64_t nnz,
-                            int64_t K) {
+static void ell_fill(Env &env, const int32_t *minor, const float *val, const int32_t *ptr, int64_t nrows, int64_t nnz,
+                     int64_t K, int64_t clip, us_formatted *f, Flags *flags) {
+  if (K > 0)
+    US_LAUNCH(env, "ell_fill", 8.0 * nnz + 8.0 * K * nrows, ell_fill_kernel, ceil_div<int64_t>(nrows, EF_ROWS), EF_ROWS, minor,
+              val, ptr, nrows, K, clip, f->level[2].idx, f->val, flags);
+}
+
+// ELL of width K over the first min(length, clip) entries of every row of a list sorted by (row, col), ptr over its
+// rows; nnz = how many entries that is.  The list must be known to be in range (the slab is indexed by row).
+us_formatted *new_ell_of_rows(Env &env, const us_format_desc &desc, int64_t nrows, int64_t ncols, int64_t nnz, int64_t K,
+                              int64_t clip, const int32_t *minor, const float *val, const int32_t *ptr, Flags *flags) {
   us_formatted *f = new us_formatted();
   f->desc = desc; f->pattern = P_ELL; f->swapped = false;
   f->nrows = nrows; f->ncols = ncols; f->nnz = nnz;
-  if (!ell_shell(env, f, K)) { free_formatted(env, f); return nullptr; }
+  if (!ell_shell(env, f, K, false)) { free_formatted(env, f); return nullptr; }
+  ell_fill(env, minor, val, ptr, nrows, nnz, K, clip, f, flags);
   return f;
 }
 
@@ -404,10 +417,7 @@ us_status build_from_sorted(Env &env, const Plan &plan, const us_format_desc &de
     }
     if (K * nrows >= (1ll << 31)) return finish(US_ERR_OVERFLOW);
     if (!ell_shell(env, f, K, false)) return finish(env.status);
-    if (K > 0)
-      US_LAUNCH(env, "ell_fill", 8.0 * nnz + 8.0 * K * nrows, ell_fill_kernel, ceil_div<int64_t>(nrows, EF_ROWS), EF_ROWS,
-                (const int32_t *)minor, (const float *)val, (const int32_t *)ptr, nrows, K, f->level[2].idx, f->val,
-                flags);
+    ell_fill(env, minor, val, ptr, nrows, nnz, K, -1, f, flags);
     return finish(flags_ok(&h));
   }
   return finish(US_ERR_UNSUPPORTED_DESC);

@@ -39,7 +39,8 @@ void nonempty_flags(Env &env, const int32_t *ptr, int64_t n, int32_t *flag);
 void max_group_len(Env &env, const int32_t *ptr, int64_t n, int32_t *out_max);
 void sorted_ptr(Env &env, const int32_t *major, const int32_t *minor, int64_t n, int64_t ngroups, int32_t *ptr,
                 bool check_dups, Flags *flags);
-us_formatted *new_empty_ell(Env &env, const us_format_desc &desc, int64_t nrows, int64_t ncols, int64_t nnz, int64_t K);
+us_formatted *new_ell_of_rows(Env &env, const us_format_desc &desc, int64_t nrows, int64_t ncols, int64_t nnz, int64_t K,
+                              int64_t clip, const int32_t *minor, const float *val, const int32_t *ptr, Flags *flags);
 us_status build_from_sorted(Env &env, const Plan &plan, const us_format_desc &desc, int64_t nrows, int64_t ncols,
                             int64_t nnz, int32_t *major, int32_t *minor, float *val, Flags *flags, bool check_dups,
                             us_formatted **out, bool validated = false, bool major_is_temp = false);

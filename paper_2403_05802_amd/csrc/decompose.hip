@@ -73,23 +73,17 @@ __global__ __launch_bounds__(256) void clipped_len_kernel(const int32_t *ptr, in
 
 // stable split of the sorted list by rank-in-row: rank < K -> part A, else part B.  (Equal neighbours have
 // been looked for before: the two copies of a coordinate may end up in different parts.)
-// ell_col != null: part A is an ELL slab of width ell_width over nrows rows and takes its entries directly
-// (slot rank * nrows + row) instead of the list (ar, ac, av).
+// ar == null: part A is not written as a list (an ELL part A is built from the rows of the sorted list itself).
 __global__ __launch_bounds__(256) void rank_split_kernel(const int32_t *major, const int32_t *minor, const float *val,
                                                         const int32_t *ptr, const int32_t *ptr_a, int64_t n,
                                                         int64_t K, int32_t *ar, int32_t *ac, float *av, int32_t *br,
-                                                        int32_t *bc, float *bv, int32_t *ell_col, float *ell_val,
-                                                        int64_t ell_width, int64_t nrows, Flags *flags) {
+                                                        int32_t *bc, float *bv) {
   int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= n) return;
   const int32_t r = major[i], c = minor[i];
   int64_t rank = i - ptr[r];
   if (rank < K) {
-    if (ell_col) {
-      if (rank >= ell_width) { flags->ell_overflow = 1; return; }
-      const int64_t slot = rank * nrows + r;
-      ell_col[slot] = c; ell_val[slot] = val[i];
-    } else {
+    if (ar) {
       int64_t p = ptr_a[r] + rank;
       ar[p] = r; ac[p] = c; av[p] = val[i];
     }
@@ -154,23 +148,22 @@ static us_status decompose_rank(Env &env, const us_coo &coo, const Plan &pa, con
   if (by_percentile) K = h.scalar[2];
   const int64_t longest = h.scalar[3];
   const int64_t na = h.scalar[1], nb = n - na;
-  // part A as row-major ELL: the split writes its slab directly (its rows hold min(length, K) entries, which
-  // gives the automatic width); any other format gets a sorted list first
+  // part A as row-major ELL: its slab is built from the first min(length, K) entries of every row of the sorted
+  // list (which gives the automatic width), 64 rows at a time through LDS; only part B is split off as a list.
+  // Any other format of part A gets a sorted list first.
   us_formatted *ell = nullptr;
-  int64_t ell_width = 0;
   if (pa.pattern == P_ELL && !pa.swapped) {
-    ell_width = pa.ell_width > 0 ? pa.ell_width : (longest < K ? longest : K);
+    const int64_t ell_width = pa.ell_width > 0 ? pa.ell_width : (longest < K ? longest : K);
     if (ell_width * nrows >= (1ll << 31)) return US_ERR_OVERFLOW;
-    ell = new_empty_ell(env, da, nrows, coo.ncols, na, ell_width);
+    ell = new_ell_of_rows(env, da, nrows, coo.ncols, na, ell_width, K, minor, val, ptr, flags);
     if (!ell) return env.status;
   }
   CooLists la = ell ? CooLists() : alloc_lists(env, na), lb = alloc_lists(env, nb);
   us_status st = env.status;
-  if (st == US_OK && n > 0) {
-    US_LAUNCH(env, "rank_split", 16.0 * n + 12.0 * n, rank_split_kernel, ceil_div<int64_t>(n, 256), 256,
+  if (st == US_OK && n > 0 && (nb > 0 || !ell)) {
+    US_LAUNCH(env, "rank_split", 16.0 * n + 12.0 * (ell ? nb : n), rank_split_kernel, ceil_div<int64_t>(n, 256), 256,
               (const int32_t *)major, (const int32_t *)minor, (const float *)val, (const int32_t *)ptr,
-              (const int32_t *)ptr_a, n, K, la.r, la.c, la.v, lb.r, lb.c, lb.v,
-              ell ? ell->level[2].idx : (int32_t *)nullptr, ell ? ell->val : (float *)nullptr, ell_width, nrows, flags);
+              (const int32_t *)ptr_a, n, K, la.r, la.c, la.v, lb.r, lb.c, lb.v);
     st = env.status;
   }
   auto finish_part = [&](const Plan &p, const us_format_desc &d, CooLists &l, int64_t cnt, us_formatted **o) {
