@@ -70,19 +70,32 @@ __global__ __launch_bounds__(CM_T) void cisr_move_kernel(const int32_t *ptr_new,
     s_src[i] = p0 + i < nnr ? ptr[row_idx[p0 + i]] : 0;
   }
   __syncthreads();
+  // where every entry comes from first, then all loads, then all stores: one trip to memory, not CM_IPT
+  int64_t src[CM_IPT];
 #pragma unroll
   for (int k = 0; k < CM_IPT; ++k) {
     const int64_t e = e0 + k * CM_T + threadIdx.x;
+    src[k] = -1;
     if (e >= n) continue;
     int lo = 0, hi = cnt - 1;   // s_ptr[lo] <= e < s_ptr[hi] throughout
     while (hi - lo > 1) {
       const int mid = (lo + hi) >> 1;
       if (s_ptr[mid] <= e) lo = mid; else hi = mid;
     }
-    int64_t src = (int64_t)s_src[lo] + (e - s_ptr[lo]);
-    src = src < 0 ? 0 : (src >= n ? n - 1 : src);
-    col_out[e] = minor[src];
-    val_out[e] = val[src];
+    const int64_t from = (int64_t)s_src[lo] + (e - s_ptr[lo]);
+    src[k] = from < 0 ? 0 : (from >= n ? n - 1 : from);
+  }
+  int32_t c[CM_IPT];
+  float v[CM_IPT];
+#pragma unroll
+  for (int k = 0; k < CM_IPT; ++k) {
+    c[k] = src[k] >= 0 ? minor[src[k]] : 0;
+    v[k] = src[k] >= 0 ? val[src[k]] : 0.f;
+  }
+#pragma unroll
+  for (int k = 0; k < CM_IPT; ++k) {
+    const int64_t e = e0 + k * CM_T + threadIdx.x;
+    if (src[k] >= 0) { col_out[e] = c[k]; val_out[e] = v[k]; }
   }
 }
 

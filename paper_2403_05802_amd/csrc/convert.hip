@@ -143,18 +143,27 @@ __global__ __launch_bounds__(64) void ell_fill_kernel(const int32_t *minor, cons
   __shared__ float s_val[EF_ROWS * EF_PITCH];
   const int lane = threadIdx.x;
   const int64_t r = (int64_t)blockIdx.x * EF_ROWS + lane;
-  const int64_t start = r < nrows ? ptr[r] : 0;
-  int64_t len = r < nrows ? ptr[r + 1] - start : 0;
-  if (clip >= 0 && len > clip) len = clip;
+  const int32_t start = r < nrows ? ptr[r] : 0;
+  int32_t len = r < nrows ? ptr[r + 1] - start : 0;
+  if (clip >= 0 && len > clip) len = (int32_t)clip;
   if (len > K) flags->ell_overflow = 1;
   for (int64_t k0 = 0; k0 < K; k0 += EF_SLOTS) {
-#pragma unroll 4
+    // all loads of the chunk first (32 in flight), then the LDS writes: one trip to memory per chunk
+    int32_t cv[EF_ROWS / EF_RPL];
+    float vv[EF_ROWS / EF_RPL];
+#pragma unroll
     for (int j = 0; j < EF_ROWS; j += EF_RPL) {
       const int row = j + lane / EF_SLOTS, kk = lane % EF_SLOTS;
-      const int64_t st = __shfl(start, row), ln = __shfl(len, row);
+      const int32_t st = __shfl(start, row), ln = __shfl(len, row);
       const bool has = k0 + kk < ln;
-      s_col[row * EF_PITCH + kk] = has ? minor[st + k0 + kk] : -1;
-      s_val[row * EF_PITCH + kk] = has ? val[st + k0 + kk] : 0.f;
+      cv[j / EF_RPL] = has ? minor[(int64_t)st + k0 + kk] : -1;
+      vv[j / EF_RPL] = has ? val[(int64_t)st + k0 + kk] : 0.f;
+    }
+#pragma unroll
+    for (int j = 0; j < EF_ROWS; j += EF_RPL) {
+      const int row = j + lane / EF_SLOTS, kk = lane % EF_SLOTS;
+      s_col[row * EF_PITCH + kk] = cv[j / EF_RPL];
+      s_val[row * EF_PITCH + kk] = vv[j / EF_RPL];
     }
     __syncthreads();
     if (r < nrows) {

@@ -74,22 +74,40 @@ __global__ __launch_bounds__(256) void clipped_len_kernel(const int32_t *ptr, in
 // stable split of the sorted list by rank-in-row: rank < K -> part A, else part B.  (Equal neighbours have
 // been looked for before: the two copies of a coordinate may end up in different parts.)
 // ar == null: part A is not written as a list (an ELL part A is built from the rows of the sorted list itself).
+constexpr int RSP_IPT = 4;
 __global__ __launch_bounds__(256) void rank_split_kernel(const int32_t *major, const int32_t *minor, const float *val,
                                                         const int32_t *ptr, const int32_t *ptr_a, int64_t n,
                                                         int64_t K, int32_t *ar, int32_t *ac, float *av, int32_t *br,
                                                         int32_t *bc, float *bv) {
-  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= n) return;
-  const int32_t r = major[i], c = minor[i];
-  int64_t rank = i - ptr[r];
-  if (rank < K) {
-    if (ar) {
-      int64_t p = ptr_a[r] + rank;
-      ar[p] = r; ac[p] = c; av[p] = val[i];
+  // RSP_IPT entries per thread, each step for all of them before the next: the entry, then the two pointers of its
+  // row, then the stores
+  const int64_t base = (int64_t)blockIdx.x * (256 * RSP_IPT) + threadIdx.x;
+  int32_t r[RSP_IPT], c[RSP_IPT], p0[RSP_IPT], pa[RSP_IPT];
+  float v[RSP_IPT];
+#pragma unroll
+  for (int k = 0; k < RSP_IPT; ++k) {
+    const int64_t i = base + k * 256;
+    r[k] = i < n ? major[i] : 0; c[k] = i < n ? minor[i] : 0; v[k] = i < n ? val[i] : 0.f;
+  }
+#pragma unroll
+  for (int k = 0; k < RSP_IPT; ++k) {
+    const bool in = base + k * 256 < n;
+    p0[k] = in ? ptr[r[k]] : 0; pa[k] = in ? ptr_a[r[k]] : 0;
+  }
+#pragma unroll
+  for (int k = 0; k < RSP_IPT; ++k) {
+    const int64_t i = base + k * 256;
+    if (i >= n) continue;
+    const int64_t rank = i - p0[k];
+    if (rank < K) {
+      if (ar) {
+        const int64_t p = pa[k] + rank;
+        ar[p] = r[k]; ac[p] = c[k]; av[p] = v[k];
+      }
+    } else {
+      const int64_t p = (int64_t)(p0[k] - pa[k]) + (rank - K);
+      br[p] = r[k]; bc[p] = c[k]; bv[p] = v[k];
     }
-  } else {
-    int64_t p = (int64_t)(ptr[r] - ptr_a[r]) + (rank - K);
-    br[p] = r; bc[p] = c; bv[p] = val[i];
   }
 }
 
@@ -161,7 +179,7 @@ static us_status decompose_rank(Env &env, const us_coo &coo, const Plan &pa, con
   CooLists la = ell ? CooLists() : alloc_lists(env, na), lb = alloc_lists(env, nb);
   us_status st = env.status;
   if (st == US_OK && n > 0 && (nb > 0 || !ell)) {
-    US_LAUNCH(env, "rank_split", 16.0 * n + 12.0 * (ell ? nb : n), rank_split_kernel, ceil_div<int64_t>(n, 256), 256,
+    US_LAUNCH(env, "rank_split", 16.0 * n + 12.0 * (ell ? nb : n), rank_split_kernel, ceil_div<int64_t>(n, 256 * RSP_IPT), 256,
               (const int32_t *)major, (const int32_t *)minor, (const float *)val, (const int32_t *)ptr,
               (const int32_t *)ptr_a, n, K, la.r, la.c, la.v, lb.r, lb.c, lb.v);
     st = env.status;
