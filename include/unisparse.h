@@ -204,8 +204,10 @@ typedef struct us_profile us_profile;
 us_status us_profile_create(us_profile **out);
 void us_profile_destroy(us_profile *p);
 us_status us_profile_reset(us_profile *p);
-/* Only launches whose algorithmic bytes reach min_bytes are bracketed by events (0 = all): lets a
- * timed region keep the per-launch cost of event recording off the many tiny kernels. */
+/* Only launches whose algorithmic bytes reach min_bytes are timed (0 = all): lets a timed region keep
+ * the per-launch cost of event recording off the many tiny kernels.  With a threshold set the two
+ * events of a launch travel in its dispatch (start and end of that kernel, nothing added to the
+ * queue); with 0 they are recorded on the stream before and after the launch. */
 us_status us_profile_set_min_bytes(us_profile *p, double min_bytes);
 us_status us_profile_collect(us_profile *p, int32_t *n);
 us_status us_profile_entry(const us_profile *p, int32_t i, const char **name, int64_t *launches,
