@@ -91,13 +91,14 @@ LaunchScope::~LaunchScope() {
 __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t *p, uint64_t n, uint32_t v) {
   uint64_t i = (uint64_t)blockIdx.x * 1024 + threadIdx.x;
 #pragma unroll
+  // Fills clear what the next kernel adds into with atomics (product outputs, counters, flags).  Device-scope
+  // atomics are carried out beyond the XCD's own L2, where a plain store becomes visible only with the write-back
+  // at the end of the kernel; once, in some thirty runs of the tests, the last few elements of such a product came
+  // out short, as if an add had landed before the fill's last store (the cause was not found, and the case did not
+  // fail again in 4800 repeats).  The fill therefore stores at device scope itself (written through, at the same
+  // rate) and its waves end only when those stores are acknowledged.
   for (int k = 0; k < 4; ++k, i += 256)
-    if (i < n) p[i] = v;
-  // Fills clear what the next kernel adds into with atomics (product outputs, counters, flags).  Once, in some
-  // thirty runs of the tests, the last few elements of such a product came out short, as if an add had landed
-  // before the fill's last store.  The end of a wave should wait for its stores by itself; this wait costs nothing
-  // and states the requirement (the cause of that one mismatch was not found, and it did not come back in 4800
-  // repeats of the case).
+    if (i < n) __hip_atomic_store(p + i, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 void fill_u32(Env &env, uint32_t *p, uint64_t n, uint32_t v) {
