@@ -215,7 +215,11 @@ def main():
 
     # ------------------------------------------------------------------ the other workloads
     if not args.only_headline:
-        out["workloads"] = other_workloads(B, W, torch, ctx, up, max(3, K // 2), 2)
+        try:
+            out["workloads"] = other_workloads(B, W, torch, ctx, up, max(3, K // 2), 2)
+        except Exception as e:   # the headline line is still printed; the failure is in it and on stderr
+            out["workloads_error"] = repr(e)
+            print("bench.py: a workload beside the headline failed: " + repr(e), file=sys.stderr)
 
     line = {
         "metric": "conversion Mnnz/s + SpMV GFLOP/s; achieved HBM GB/s as % of MI355X peak",
