@@ -92,23 +92,48 @@ __global__ __launch_bounds__(256) void nonempty_flag_kernel(const int32_t *ptr, 
   if (g < n) flag[g] = ptr[g + 1] > ptr[g] ? 1 : 0;
 }
 
-// *nnr_dev = number of non-empty groups (the total of the scan that made pos); the arrays hold `cap` of
-// them, which a valid input never exceeds
-__global__ __launch_bounds__(256) void dcsr_compact_kernel(const int32_t *ptr, const int32_t *pos, int64_t n,
-                                                          const int32_t *nnr_dev, int64_t cap, int32_t nnz,
-                                                          int32_t *idx0, int32_t *ptr1) {
-  int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (g == 0) {
+// Trim of the major level (DCSR): the groups that have children, in order, with where their children start.
+// Counted per tile, the tile counts scanned by one workgroup (scan_partials_launch, which leaves the total, nnr, in
+// device memory), then every tile numbers its own groups and writes them: no flag or position arrays in between.
+// The arrays hold `cap` groups, which a valid input never exceeds.
+constexpr int NE_T = 256, NE_IPT = 8, NE_TILE = NE_T * NE_IPT;
+__global__ __launch_bounds__(NE_T) void nonempty_count_kernel(const int32_t *ptr, int64_t n, uint32_t *partial) {
+  __shared__ uint32_t s_wave[NE_T / 64 + 1];
+  const int64_t base = (int64_t)blockIdx.x * NE_TILE;
+  uint32_t s = 0;
+#pragma unroll
+  for (int k = 0; k < NE_IPT; ++k) {
+    const int64_t g = base + k * NE_T + threadIdx.x;
+    if (g < n) s += ptr[g + 1] > ptr[g] ? 1u : 0u;
+  }
+  uint32_t total;
+  block_exclusive_sum<NE_T>(s, s_wave, &total);
+  if (threadIdx.x == 0) partial[blockIdx.x] = total;
+}
+__global__ __launch_bounds__(NE_T) void nonempty_compact_kernel(const int32_t *ptr, int64_t n, const uint32_t *partial,
+                                                               const int32_t *nnr_dev, int64_t cap, int32_t nnz,
+                                                               int32_t *idx0, int32_t *ptr1) {
+  __shared__ uint32_t s_wave[NE_T / 64 + 1];
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
     const int64_t nnr = *nnr_dev;
     ptr1[nnr >= 0 && nnr < cap ? nnr : cap] = nnz;
   }
-  if (g < n && ptr[g + 1] > ptr[g]) {
-    int32_t k = pos[g];
-    if (k >= 0 && k < cap) {
-      idx0[k] = (int32_t)g;
-      ptr1[k] = ptr[g];
+  // a thread owns NE_IPT consecutive groups, so its numbers are consecutive too
+  const int64_t g0 = (int64_t)blockIdx.x * NE_TILE + (int64_t)threadIdx.x * NE_IPT;
+  int32_t p[NE_IPT + 1];
+#pragma unroll
+  for (int k = 0; k <= NE_IPT; ++k) p[k] = g0 + k <= n ? ptr[g0 + k] : 0;
+  uint32_t s = 0;
+#pragma unroll
+  for (int k = 0; k < NE_IPT; ++k) s += (g0 + k < n && p[k + 1] > p[k]) ? 1u : 0u;
+  uint32_t total;
+  int64_t at = (int64_t)block_exclusive_sum<NE_T>(s, s_wave, &total) + partial[blockIdx.x];
+#pragma unroll
+  for (int k = 0; k < NE_IPT; ++k)
+    if (g0 + k < n && p[k + 1] > p[k]) {
+      if (at < cap) { idx0[at] = (int32_t)(g0 + k); ptr1[at] = p[k]; }
+      ++at;
     }
-  }
 }
 
 // Kernels that end with one atomic per workgroup on a single counter run on at most ONE_COUNTER_GRID
@@ -392,7 +417,8 @@ us_status build_from_sorted(Env &env, const Plan &plan, const us_format_desc &de
     // device until the one read of the flags that ends the call: idx and ptr are allocated for the most
     // there can be, min(nmaj, nnz), and the kernels in between take nnr from device memory.
     const int64_t cap = nmaj < nnz ? nmaj : nnz;
-    int32_t *flag = env.temp<int32_t>(nmaj), *pos = env.temp<int32_t>(nmaj);
+    const int64_t ntile = ceil_div<int64_t>(nmaj, NE_TILE);
+    uint32_t *partial = env.temp<uint32_t>(ntile);
     int32_t *idx0 = env.owned<int32_t>(cap), *ptr1 = env.owned<int32_t>(cap + 1);
     f->nlevels = 2;
     f->level[0].idx = idx0; f->level[0].nidx = 0;
@@ -401,11 +427,10 @@ us_status build_from_sorted(Env &env, const Plan &plan, const us_format_desc &de
     f->val = val; f->nval = nnz; f->nmajor = 0;
     minor_loose = val_loose = false;
     if (!env.ok()) return finish(env.status);
-    nonempty_flags(env, ptr, nmaj, flag);
-    exclusive_scan_i32(env, flag, pos, nmaj, &flags->scalar[0]);
-    US_LAUNCH(env, "dcsr_compact", 12.0 * nmaj + 8.0 * cap, dcsr_compact_kernel, ceil_div<int64_t>(nmaj, 256), 256,
-              (const int32_t *)ptr, (const int32_t *)pos, nmaj, (const int32_t *)&flags->scalar[0], cap,
-              (int32_t)nnz, idx0, ptr1);
+    US_LAUNCH(env, "nonempty_count", 4.0 * nmaj, nonempty_count_kernel, ntile, NE_T, (const int32_t *)ptr, nmaj, partial);
+    scan_partials_launch(env, partial, ntile, &flags->scalar[0]);
+    US_LAUNCH(env, "nonempty_compact", 4.0 * nmaj + 8.0 * cap, nonempty_compact_kernel, ntile, NE_T, (const int32_t *)ptr,
+              nmaj, (const uint32_t *)partial, (const int32_t *)&flags->scalar[0], cap, (int32_t)nnz, idx0, ptr1);
     spmv_prepare(env, f, &flags->scalar[0], cap);
     us_status s = flags_ok(&h);
     if (s != US_OK) return finish(s);
@@ -463,7 +488,7 @@ us_status convert_with_plan(Env &env, const us_coo &coo, const Plan &plan, const
     if (plan.pattern == P_CSR) res = 2 * g(n) + g(nmaj + 1) + g(spmv_tiles(nmaj, n) + 1);
     if (plan.pattern == P_DCSR) {
       res = 2 * g(n) + g(cap) + g(cap + 1) + g(spmv_tiles(cap, n) + 1);
-      tmp += g(nmaj + 1) + 2 * g(nmaj) + g(nmaj / 1024 + 64);   // pointers over all rows, flags and positions, scan sums
+      tmp += g(nmaj + 1) + g(nmaj / 1024 + 64);   // pointers over all rows, counts of the stored rows per tile
     }
     if (plan.pattern == P_ELL) tmp += g(nmaj + 1);
     env.reserve(tmp);
