@@ -297,7 +297,8 @@ void *ensure_workspace(Env &env, const us_formatted &A, size_t bytes) {
   if (A.ws_bytes >= bytes && A.ws) return A.ws;
   if (A.ws) {
     env.sync();  // an earlier compute call may still use the old scratch
-    env.free_raw(A.ws);
+    const char *s0 = (const char *)A.slab, *w = (const char *)A.ws;
+    if (!(s0 && w >= s0 && w < s0 + A.slab_bytes)) env.free_raw(A.ws);   // (scratch set aside inside the result's own block stays there)
     A.ws = nullptr; A.ws_bytes = 0;
   }
   A.ws = env.alloc_raw(bytes < 256 ? 256 : bytes);
@@ -351,6 +352,16 @@ us_formatted *new_ell_of_rows(Env &env, const us_format_desc &desc, int64_t nrow
   if (!ell_shell(env, f, K, false)) { free_formatted(env, f); return nullptr; }
   ell_fill(env, minor, val, ptr, nrows, nnz, K, clip, f, flags);
   return f;
+}
+
+// The scratch of the merge-path product (two words per tile) comes out of the result's own block when that has
+// room for it (convert_with_plan sizes it so); otherwise the first product allocates it.
+static void product_scratch(Env &env, us_formatted *f) {
+  if (!f->mp_split || f->mp_tiles <= 0 || f->swapped) return;
+  const size_t bytes = 2 * Env::granule(4 * (size_t)f->mp_tiles);
+  if (env.out_left < bytes) return;
+  f->ws = env.owned<char>(bytes);
+  f->ws_bytes = bytes;
 }
 
 // Build COO / CSR / DCSR / ELL from entries already sorted by (major, minor).  `major` is a
@@ -409,6 +420,7 @@ us_status build_from_sorted(Env &env, const Plan &plan, const us_format_desc &de
     f->val = val; f->nval = nnz; f->nmajor = nmaj;
     minor_loose = val_loose = false;
     spmv_prepare(env, f);
+    product_scratch(env, f);
     return finish(flags_ok(&h));
   }
 
@@ -432,6 +444,7 @@ us_status build_from_sorted(Env &env, const Plan &plan, const us_format_desc &de
     US_LAUNCH(env, "nonempty_compact", 4.0 * nmaj + 8.0 * cap, nonempty_compact_kernel, ntile, NE_T, (const int32_t *)ptr,
               nmaj, (const uint32_t *)partial, (const int32_t *)&flags->scalar[0], cap, (int32_t)nnz, idx0, ptr1);
     spmv_prepare(env, f, &flags->scalar[0], cap);
+    product_scratch(env, f);
     us_status s = flags_ok(&h);
     if (s != US_OK) return finish(s);
     const int64_t nnr = h.scalar[0];
@@ -485,9 +498,10 @@ us_status convert_with_plan(Env &env, const us_coo &coo, const Plan &plan, const
     size_t tmp = sort_temp_bytes(n) + 4 * Env::granule(sizeof(Flags)), res = 0;
     if (rowcol && plan.pattern != P_COO) tmp += g(n);   // the major indices: only the COO layout keeps them
     if (plan.pattern == P_COO) res = 3 * g(n);
-    if (plan.pattern == P_CSR) res = 2 * g(n) + g(nmaj + 1) + g(spmv_tiles(nmaj, n) + 1);
+    // (with the tile starts of the product goes its scratch, two words per tile: the first product then allocates nothing)
+    if (plan.pattern == P_CSR) res = 2 * g(n) + g(nmaj + 1) + g(spmv_tiles(nmaj, n) + 1) + 2 * g(spmv_tiles(nmaj, n));
     if (plan.pattern == P_DCSR) {
-      res = 2 * g(n) + g(cap) + g(cap + 1) + g(spmv_tiles(cap, n) + 1);
+      res = 2 * g(n) + g(cap) + g(cap + 1) + g(spmv_tiles(cap, n) + 1) + 2 * g(spmv_tiles(cap, n));
       tmp += g(nmaj + 1) + g(nmaj / 1024 + 64);   // pointers over all rows, counts of the stored rows per tile
     }
     if (plan.pattern == P_ELL) tmp += g(nmaj + 1);
