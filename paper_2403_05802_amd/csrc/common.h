@@ -5,6 +5,7 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <functional>
 #include <string>
 #include <vector>
 
@@ -218,6 +219,10 @@ struct SortOut {
   int32_t *major = nullptr, *minor = nullptr;  // unpacked output (mode 0 only)
   uint64_t *key64 = nullptr; uint32_t *key32 = nullptr;  // packed output
   float *val = nullptr;
+  // Unpacked output whose arrays are not there yet: `late` sets major, minor and val and is called once all but
+  // the last step of the sort are enqueued (an allocation made then costs no idle time on the GPU).  After a
+  // failure inside it (Env::status) nothing more is launched.
+  std::function<void(SortOut &)> late;
 };
 bool sort_coo(Env &env, const int32_t *row, const int32_t *col, const float *val, int64_t nnz,
               const KeySpec &ks, const SortOut &out, Flags *flags_dev);

@@ -490,6 +490,7 @@ us_status convert_with_plan(Env &env, const us_coo &coo, const Plan &plan, const
                        plan.pattern == P_ELL || plan.pattern == P_CISR;
   const bool rowcol = by_sort && plan.pattern != P_CISR;   // built below from the (major, minor) order
   const int64_t n = coo.nnz;
+  size_t late_res = 0;
   if (by_sort) {
     // two calls into the caller's allocator for the whole conversion: the flags, the sort's buffers and the other
     // temporaries in one block, the arrays of the result in another (each call costs microseconds of an idle GPU)
@@ -506,7 +507,8 @@ us_status convert_with_plan(Env &env, const us_coo &coo, const Plan &plan, const
     }
     if (plan.pattern == P_ELL) tmp += g(nmaj + 1);
     env.reserve(tmp);
-    if (env.one_result) env.reserve_out(res);
+    late_res = env.one_result && rowcol ? res : 0;   // the block of the result is allocated while the sort runs
+    if (env.one_result && !rowcol) env.reserve_out(res);
   } else if (plan.pattern == P_DIA) {   // counters, flags, positions and slab indices of the diagonals, scan sums
     const size_t nbins = (size_t)(coo.nrows + coo.ncols);
     env.reserve(4 * Env::granule(4 * nbins) + Env::granule(4 * (nbins / 1024 + 64)) + 8 * Env::granule(256));
@@ -522,12 +524,18 @@ us_status convert_with_plan(Env &env, const us_coo &coo, const Plan &plan, const
   if (plan.pattern == P_CISR) return convert_cisr(env, coo, plan, desc, flags, out);
   // COO / CSR / DCSR / ELL: sort by (major, minor), then build
   const bool keep_major = plan.pattern == P_COO;
-  int32_t *major = keep_major ? env.owned<int32_t>(n) : env.temp<int32_t>(n), *minor = env.owned<int32_t>(n);
-  float *val = env.owned<float>(n);
-  if (!env.ok()) { if (keep_major) env.free_raw(major); env.free_raw(minor); env.free_raw(val); return env.status; }
+  int32_t *major = nullptr, *minor = nullptr;
+  float *val = nullptr;
   SortOut so{};
-  so.major = major; so.minor = minor; so.val = val;
+  so.late = [&](SortOut &o) {
+    if (late_res) env.reserve_out(late_res);
+    major = keep_major ? env.owned<int32_t>(n) : env.temp<int32_t>(n);
+    minor = env.owned<int32_t>(n);
+    val = env.owned<float>(n);
+    o.major = major; o.minor = minor; o.val = val;
+  };
   const bool checked = sort_coo(env, coo.row, coo.col, coo.val, n, rowcol_keyspec(coo, plan.swapped), so, flags);
+  if (!env.ok()) { if (keep_major) env.free_raw(major); env.free_raw(minor); env.free_raw(val); return env.status; }
   return build_from_sorted(env, plan, desc, coo.nrows, coo.ncols, n, major, minor, val, flags, !checked, out, false,
                            !keep_major);
 }

@@ -754,9 +754,13 @@ static void launch_scatter_out(Env &env, const PassArgs &a, int out_mode, double
 // 64-bit keys (out.key64) or 32-bit keys (out.key32).  Returns true when equal keys have been
 // looked for (and flagged) on the way.
 static bool sort_generic(Env &env, int in_mode, const int32_t *row, const int32_t *col, const uint32_t *key32_in,
-                         const float *val, int64_t nnz, const KeySpec &ks, const SortOut &out, Flags *flags) {
-  if (nnz <= 0 || !env.ok()) return false;
-  const int final_mode = out.major ? OUT_UNPACK : (out.key64 ? OUT_KEY64 : OUT_KEY32);
+                         const float *val, int64_t nnz, const KeySpec &ks, const SortOut &out_in, Flags *flags) {
+  SortOut out = out_in;
+  if (nnz <= 0 || !env.ok()) {
+    if (out.late && env.ok()) out.late(out);   // the caller still gets its (empty) arrays
+    return false;
+  }
+  const int final_mode = (out.major || out.late) ? OUT_UNPACK : (out.key64 ? OUT_KEY64 : OUT_KEY32);
   const int total_bits = ks.total_bits > 0 ? ks.total_bits : 1;
 
   // Whole-array passes over the top `high_bits`, then the in-LDS finish over the rest: enough top
@@ -812,6 +816,10 @@ static bool sort_generic(Env &env, int in_mode, const int32_t *row, const int32_
   const double kb = 8.0;  // key bytes between passes
   for (int p = 0; p < npass; ++p) {
     const bool first = p == 0, last_pass = p == npass - 1, last = last_pass && !finish_local;
+    if (last && out.late) {
+      out.late(out); out.late = nullptr;
+      if (!env.ok()) return false;
+    }
     PassArgs a{};
     a.row = first ? row : nullptr;
     a.col = first ? col : nullptr;
@@ -859,6 +867,10 @@ static bool sort_generic(Env &env, int in_mode, const int32_t *row, const int32_
     else launch_scatter_out<IN_SPLIT>(env, a, om, bytes);
   }
   if (!finish_local) return false;
+  if (out.late) {
+    out.late(out); out.late = nullptr;
+    if (!env.ok()) return false;
+  }
 
   la.nbuckets = nbuckets; la.n = (uint32_t)nnz; la.low_bits = low_bits; la.b_bits = ks.b_bits;
   uint32_t *off = env.temp<uint32_t>((size_t)nbuckets + 1);
