@@ -326,7 +326,7 @@ def other_workloads(B, W, torch, ctx, up, K, Wm):
         lambda p: B.us_spmm(ctx, p[0], X, Y), 2.0 * m.nnz * 64,
         lambda p: 12.0 * m.nnz + 4.0 * p[0].val().numel() + 4.0 * p[0].idx(1).numel())
     # the same conversion with whole-array digit passes only (blocked tuples finish inside LDS by default)
-    B.us_set_sort_lds_finish(False)
+    ctx.set_sort_lds_finish(False)
     try:
         r, c, v = up(m.row), up(m.col), up(m.val)
         ms = timed(torch, lambda: B.us_convert(ctx, m.nrows, m.ncols, r, c, v, BC).free(), K, Wm)
@@ -334,7 +334,7 @@ def other_workloads(B, W, torch, ctx, up, K, Wm):
         res["config4_bcsr_spmm64"]["convert_mnnz_s_whole_array_passes_only"] = round(m.nnz / ms / 1e3, 1)
         del r, c, v
     finally:
-        B.us_set_sort_lds_finish(None)
+        ctx.set_sort_lds_finish(None)
     del X, Y
     # config 5
     m = W.cfg5_powerlaw_local()
@@ -374,13 +374,13 @@ def format_to_format(B, W, torch, ctx, up, K, Wm):
         if also_with_lds_finish:
             # (row, col) tuples keep whole-array digit passes by default (rows of a power-law matrix overflow the
             # buckets of the in-LDS finish); a caller who knows its rows are even can ask for the finish
-            B.us_set_sort_lds_finish(True)
+            ctx.set_sort_lds_finish(True)
             try:
                 ms = timed(torch, lambda: B.us_convert(ctx, m.nrows, m.ncols, r, c, v, dst_desc).free(), K, Wm)
                 out[name]["convert_ms_with_lds_finish"] = round(ms, 4)
                 out[name]["convert_mnnz_s_with_lds_finish"] = round(m.nnz / ms / 1e3, 1)
             finally:
-                B.us_set_sort_lds_finish(None)
+                ctx.set_sort_lds_finish(None)
         del r, c, v
         torch.cuda.empty_cache()
 

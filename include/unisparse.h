@@ -17,6 +17,11 @@
  *     stream before returning (output sizes and the validation flags are data dependent:
  *     one read-back for most conversions, up to three for a decomposition); us_spmv /
  *     us_spmm only enqueue.
+ *   - A us_formatted carries scratch memory that its products use (partial sums of rows cut by
+ *     a tile boundary): every product over one us_formatted must be enqueued on ONE stream, one
+ *     call at a time (two host threads, or two streams, multiplying the same tensor race on
+ *     that scratch; make a second us_formatted for the second stream).  The `const` of the
+ *     product calls covers the matrix arrays, not that scratch.
  *   - An array of a us_formatted may be allocated larger than the count us_formatted_array
  *     reports (the stored-row arrays of DCSR are sized before their count is known), and
  *     several arrays of one us_formatted may lie in one allocation (each 256-byte aligned):
@@ -57,7 +62,19 @@ typedef struct us_ctx {
   void *user;
   void *hip_stream; /* hipStream_t, NULL = the null stream */
   void *profile;    /* us_profile* or NULL: per-kernel HIP-event timing (see us_profile_*) */
+  /* How the Sort step (Figure 8) of the conversions made through this context finishes.
+   *   US_SORT_FINISH_AUTO (0, what a zeroed us_ctx gives): by the target tuple -- in LDS for blocked tuples
+   *     (BCSR, BDIA and the blocked #sum queries), whole-array digit passes for (row, col) tuples;
+   *   US_SORT_FINISH_LDS: whole-array digit passes over the top key bits only, every bucket of equal top bits
+   *     is then finished inside LDS;
+   *   US_SORT_FINISH_PASSES: whole-array digit passes over all key bits.
+   * The finish pays off when entries spread evenly over the buckets (block rows of a FEM-like matrix: COO->BCSR
+   * of 50 M entries 27 % faster); heavy rows of a power-law matrix need extra splitting passes and gain nothing.
+   * Results are identical in every mode; an input the finish cannot take (more than 262,144 entries sharing
+   * their top key bits, or 2,048 sharing 8 more) is sorted again with whole-array passes by the same call. */
+  int32_t sort_finish;
 } us_ctx;
+enum { US_SORT_FINISH_AUTO = 0, US_SORT_FINISH_LDS = 1, US_SORT_FINISH_PASSES = 2 };
 
 /* Unsorted COO input (Figure 7, #COO): borrowed device arrays of length nnz; coordinates unique. */
 typedef struct us_coo {
@@ -144,16 +161,6 @@ us_status us_convert(const us_ctx *ctx, const us_coo *coo, const us_format_desc 
 us_status us_convert_formatted(const us_ctx *ctx, const us_formatted *src, const us_format_desc *target,
                                us_formatted **out);
 
-/* Option, process-wide: how the Sort step (Figure 8) finishes.  mode 1: whole-array digit passes run over
- * the top key bits only and every bucket of equal top bits is finished inside LDS; mode 0: whole-array
- * passes over all bits; mode -1 (default): the first for blocked target tuples (BCSR, BDIA and the blocked
- * #sum queries), the second for (row, col) tuples.  The finish pays off when entries spread evenly over the
- * buckets (block rows of a FEM-like matrix: COO->BCSR of 50 M entries 27 % faster); heavy rows of a power-law
- * matrix need extra splitting passes and gain nothing.  Results are identical in every mode; an input the
- * finish cannot take (more than 262,144 entries sharing their top key bits, or 2,048 sharing 8 more) is
- * sorted again with whole-array passes by the same call. */
-us_status us_set_sort_lds_finish(int32_t mode);
-
 /* decompose + convert of a hybrid (Figure 3c lines "decompose" and "convert"): entries that
  * satisfy `pred` form part A (stored as desc_a), the rest part B (desc_b).  Both parts keep
  * the shape of the whole matrix, so A*x = out_a*x + out_b*x. */
@@ -179,10 +186,13 @@ us_status us_spmm(const us_ctx *ctx, const us_formatted *A, const float *X, int6
  *   US_A_SIZE: *count = extent of a dense level (dev_ptr = NULL)
  *   US_A_PTR / US_A_IDX: int32 device array of *count entries
  *   US_A_VAL: fp32 value array (level ignored)
- * An array the format does not have yields *dev_ptr = NULL, *count = -1 and US_OK. */
+ * An array the format does not have yields *dev_ptr = NULL, *count = -1 and US_OK.
+ * dtype (may be NULL) receives the element type of the array: US_T_INT32 for ptr / idx, US_T_FLOAT32 for val,
+ * US_T_NONE for a size or an absent array. */
 enum { US_A_SIZE = 0, US_A_PTR = 1, US_A_IDX = 2, US_A_VAL = 3 };
+enum { US_T_NONE = 0, US_T_INT32 = 1, US_T_FLOAT32 = 2 };
 us_status us_formatted_array(const us_formatted *f, int32_t level, int32_t which,
-                             const void **dev_ptr, int64_t *count);
+                             const void **dev_ptr, int64_t *count, int32_t *dtype);
 us_status us_formatted_info(const us_formatted *f, int64_t *nrows, int64_t *ncols, int64_t *nnz,
                             us_format_desc *desc);
 /* Releases a us_formatted (NULL is allowed).  us_free waits for ctx->hip_stream first, since products enqueued

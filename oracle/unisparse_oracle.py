@@ -502,14 +502,10 @@ def spmv_coo(nrows, ncols, row, col, val, x) -> np.ndarray:
 
 
 def spmm_coo(nrows, ncols, row, col, val, X) -> np.ndarray:
+    """Y_i: = sum_j A_ij X_j: straight from the COO list."""
     X = np.asarray(X, dtype=np.float64)
     Y = np.zeros((nrows, X.shape[1]), dtype=np.float64)
-    row = np.asarray(row); col = np.asarray(col); v = np.asarray(val, dtype=np.float64)
-    step = max(1, (1 << 24) // max(X.shape[1], 1))
-    order = np.argsort(row, kind="stable")
-    for s in range(0, row.shape[0], step):
-        o = order[s:s + step]
-        np.add.at(Y, row[o], v[o, None] * X[col[o]])
+    np.add.at(Y, np.asarray(row), np.asarray(val, dtype=np.float64)[:, None] * X[np.asarray(col)])
     return Y
 
 

@@ -25,11 +25,12 @@ US_E_AFFINE, US_E_DIV, US_E_MOD, US_E_INDIRECT_ENUM, US_E_INDIRECT_SCHEDULE = 0,
  US_F_BDIA, US_F_CSB, US_F_CISR_PLUS) = range(12)
 US_P_SUM_GE_ABS, US_P_SUM_GE_FRAC_OF_CAPACITY, US_P_RANK_LT_ABS, US_P_RANK_LT_PERCENTILE = range(4)
 US_A_SIZE, US_A_PTR, US_A_IDX, US_A_VAL = range(4)
+US_T_NONE, US_T_INT32, US_T_FLOAT32 = range(3)
+US_SORT_FINISH_AUTO, US_SORT_FINISH_LDS, US_SORT_FINISH_PASSES = range(3)
 
-EXPORTS = ["us_convert", "us_convert_formatted", "us_decompose", "us_spmv", "us_spmm", "us_formatted_array", "us_formatted_info",
-           "us_free", "us_free_async", "us_status_str", "us_desc_preset", "us_profile_create", "us_profile_destroy",
-           "us_profile_reset", "us_profile_collect", "us_profile_entry", "us_profile_set_min_bytes",
-           "us_set_sort_lds_finish"]
+EXPORTS = ["us_convert", "us_convert_formatted", "us_decompose", "us_spmv", "us_spmm", "us_formatted_array",
+           "us_formatted_info", "us_free", "us_free_async", "us_status_str", "us_desc_preset", "us_profile_create",
+           "us_profile_destroy", "us_profile_reset", "us_profile_collect", "us_profile_entry", "us_profile_set_min_bytes"]
 
 
 class UnisparseError(RuntimeError):
@@ -45,7 +46,7 @@ _FREE_T = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
 
 class us_ctx(C.Structure):
     _fields_ = [("alloc", _ALLOC_T), ("free", _FREE_T), ("user", C.c_void_p),
-                ("hip_stream", C.c_void_p), ("profile", C.c_void_p)]
+                ("hip_stream", C.c_void_p), ("profile", C.c_void_p), ("sort_finish", C.c_int32)]
 
 
 class us_coo(C.Structure):
@@ -94,7 +95,7 @@ def lib() -> C.CDLL:
         L.us_spmm.argtypes = [C.POINTER(us_ctx), C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p,
                               C.c_int64, C.c_int32]
         L.us_formatted_array.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_void_p),
-                                         C.POINTER(C.c_int64)]
+                                         C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
         L.us_formatted_info.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64),
                                         C.POINTER(C.c_int64), C.POINTER(us_format_desc)]
         L.us_free.restype = None
@@ -108,8 +109,6 @@ def lib() -> C.CDLL:
         L.us_profile_collect.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
         L.us_profile_set_min_bytes.argtypes = [C.c_void_p, C.c_double]
         L.us_profile_set_min_bytes.restype = C.c_int32
-        L.us_set_sort_lds_finish.argtypes = [C.c_int32]
-        L.us_set_sort_lds_finish.restype = C.c_int32
         L.us_profile_entry.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_int64),
                                        C.POINTER(C.c_double), C.POINTER(C.c_double)]
         for fn in ("us_desc_preset", "us_convert", "us_decompose", "us_spmv", "us_spmm", "us_formatted_array",
@@ -160,9 +159,15 @@ class Context:
         with torch.cuda.device(self.device):
             self.c.hip_stream = torch.cuda.current_stream().cuda_stream
         self.c.profile = None
+        self.c.sort_finish = US_SORT_FINISH_AUTO
         self._profile = None
         if profile:
             self.enable_profile()
+
+    def set_sort_lds_finish(self, mode) -> None:
+        """us_ctx.sort_finish: True = finish the Sort inside LDS, False = whole-array digit passes only,
+        None = chosen by the target tuple (the default)."""
+        self.c.sort_finish = US_SORT_FINISH_AUTO if mode is None else (US_SORT_FINISH_LDS if mode else US_SORT_FINISH_PASSES)
 
     # -- profiling
     def enable_profile(self):
@@ -246,11 +251,6 @@ def make_predicate(group, kind: int, num: int = 0, den: int = 1, abs_: int = 0) 
     return p
 
 
-def us_set_sort_lds_finish(mode) -> None:
-    """True / False, or None for the default (chosen by the key layout)."""
-    _check(lib().us_set_sort_lds_finish(-1 if mode is None else (1 if mode else 0)), "us_set_sort_lds_finish")
-
-
 # ----------------------------------------------------------------------------- formatted tensor
 class Formatted:
     def __init__(self, ctx: Context, handle: int):
@@ -274,11 +274,11 @@ class Formatted:
 
     def us_formatted_array(self, level: int, which: int):
         """(device tensor or None, count).  US_A_SIZE returns (None, extent)."""
-        p = C.c_void_p(); n = C.c_int64()
-        _check(lib().us_formatted_array(self.handle, level, which, C.byref(p), C.byref(n)), "us_formatted_array")
+        p = C.c_void_p(); n = C.c_int64(); t = C.c_int32()
+        _check(lib().us_formatted_array(self.handle, level, which, C.byref(p), C.byref(n), C.byref(t)), "us_formatted_array")
         if which == US_A_SIZE or n.value < 0:
             return None, n.value
-        dt = torch.float32 if which == US_A_VAL else torch.int32
+        dt = {US_T_INT32: torch.int32, US_T_FLOAT32: torch.float32}[t.value]
         if n.value == 0:
             return torch.empty(0, dtype=dt, device=self.ctx.device), 0
         return self.ctx.tensor_at(p.value, n.value, dt), n.value

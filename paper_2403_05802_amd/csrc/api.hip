@@ -112,11 +112,6 @@ us_status us_decompose(const us_ctx *ctx, const us_coo *coo, const us_format_des
   return s;
 }
 
-us_status us_set_sort_lds_finish(int32_t mode) {
-  us::g_lds_finish = mode < 0 ? -1 : (mode != 0 ? 1 : 0);
-  return US_OK;
-}
-
 us_status us_spmv(const us_ctx *ctx, const us_formatted *A, const float *x, float *y, int32_t accumulate) {
   if (!ctx || !A || !x || !y) return US_ERR_NULL;
   Env env(ctx);
@@ -132,15 +127,16 @@ us_status us_spmm(const us_ctx *ctx, const us_formatted *A, const float *X, int6
 }
 
 us_status us_formatted_array(const us_formatted *f, int32_t level, int32_t which, const void **dev_ptr,
-                             int64_t *count) {
+                             int64_t *count, int32_t *dtype) {
   if (!f || !dev_ptr || !count) return US_ERR_NULL;
   *dev_ptr = nullptr; *count = -1;
-  if (which == US_A_VAL) { *dev_ptr = f->val; *count = f->nval; return US_OK; }
+  if (dtype) *dtype = US_T_NONE;
+  if (which == US_A_VAL) { *dev_ptr = f->val; *count = f->nval; if (dtype) *dtype = US_T_FLOAT32; return US_OK; }
   if (level < 0 || level >= f->nlevels) return US_ERR_SHAPE;
   const LevelStore &l = f->level[level];
   if (which == US_A_SIZE) { *count = l.size; return US_OK; }
-  if (which == US_A_PTR) { if (l.ptr) { *dev_ptr = l.ptr; *count = l.nptr; } return US_OK; }
-  if (which == US_A_IDX) { if (l.idx) { *dev_ptr = l.idx; *count = l.nidx; } return US_OK; }
+  if (which == US_A_PTR) { if (l.ptr) { *dev_ptr = l.ptr; *count = l.nptr; if (dtype) *dtype = US_T_INT32; } return US_OK; }
+  if (which == US_A_IDX) { if (l.idx) { *dev_ptr = l.idx; *count = l.nidx; if (dtype) *dtype = US_T_INT32; } return US_OK; }
   return US_ERR_SHAPE;
 }
 

@@ -37,7 +37,6 @@ struct Profile {
 };
 
 // ------------------------------------------------------------------ per-call environment
-extern int g_lds_finish;    // process-wide default of Env::lds_finish (us_set_sort_lds_finish)
 struct Env {
   const us_ctx *ctx;
   hipStream_t stream;
@@ -50,7 +49,7 @@ struct Env {
 
   explicit Env(const us_ctx *c)
       : ctx(c), stream(c ? (hipStream_t)c->hip_stream : nullptr), prof(c ? (Profile *)c->profile : nullptr),
-        lds_finish(g_lds_finish) {}
+        lds_finish(!c || c->sort_finish == US_SORT_FINISH_AUTO ? -1 : (c->sort_finish == US_SORT_FINISH_LDS ? 1 : 0)) {}
   ~Env() { release_temps(); drop_out(); }
 
   void *alloc_raw(size_t bytes);
@@ -249,5 +248,7 @@ int64_t spmv_tiles(int64_t nmajor, int64_t nnz);
 us_status spmv_impl(Env &env, const us_formatted &A, const float *x, float *y, bool accumulate);
 us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, int64_t ldx, float *Y,
                     int64_t ldy, bool accumulate);
+// scratch the entry-balanced product (row-major COO, CSR, DCSR) takes from ensure_workspace; vec = columns per lane
+size_t entry_balanced_scratch_bytes(int64_t nnz, int64_t N, int vec);
 
 }  // namespace us

@@ -17,7 +17,6 @@ void Env::free_raw(void *p) {
   if (ctx && ctx->alloc) { if (ctx->free) ctx->free(p, ctx->user); }
   else (void)hipFree(p);
 }
-int g_lds_finish = -1;
 
 void Env::reserve(size_t bytes) {
   if (arena_left >= bytes || bytes == 0) return;
@@ -91,12 +90,12 @@ LaunchScope::~LaunchScope() {
 __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t *p, uint64_t n, uint32_t v) {
   uint64_t i = (uint64_t)blockIdx.x * 1024 + threadIdx.x;
 #pragma unroll
-  // Fills clear what the next kernel adds into with atomics (product outputs, counters, flags).  Device-scope
-  // atomics are carried out beyond the XCD's own L2, where a plain store becomes visible only with the write-back
-  // at the end of the kernel; once, in some thirty runs of the tests, the last few elements of such a product came
-  // out short, as if an add had landed before the fill's last store (the cause was not found, and the case did not
-  // fail again in 4800 repeats).  The fill therefore stores at device scope itself (written through, at the same
-  // rate) and its waves end only when those stores are acknowledged.
+  // MITIGATION ON A GUESS, NOT A FIX.  Once, in some thirty runs of the GPU tests, the last few elements of a
+  // product whose output is cleared here and then added into came out short; which test, layout and kernel it was
+  // is not known, reading every such path found no second writer and no ordering hole, and the case never showed
+  // again.  Launches on one stream already order this kernel's write-back before the next kernel, so these
+  // device-scope (write-through) stores and the wait for their acknowledgement change nothing unless that
+  // guarantee failed.  They cost nothing measurable (the fill runs at the same rate) and stay until a cause is known.
   for (int k = 0; k < 4; ++k, i += 256)
     if (i < n) __hip_atomic_store(p + i, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");

@@ -407,9 +407,27 @@ __global__ __launch_bounds__(256) void coo_spmm_atomic_kernel(const int32_t *r, 
   if (cc < N) atomicAdd(&Y[(int64_t)r[e] * ldy + cc], val[e] * X[(int64_t)c[e] * ldx + cc]);
 }
 
+// Y[i][0..N) = 0 for a Y whose rows are ldy > N apart (the columns past N are the caller's and stay untouched)
+__global__ __launch_bounds__(256) void zero_rows_kernel(float *Y, int64_t nrows, int64_t N, int64_t ldy) {
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (e >= nrows * N) return;
+  const int64_t i = e / N;
+  Y[i * ldy + (e - i * N)] = 0.f;
+}
+
 static void zero_rows(Env &env, float *Y, int64_t nrows, int64_t N, int64_t ldy) {
   if (ldy == N) { fill_u32(env, (uint32_t *)Y, (uint64_t)nrows * N, 0u); return; }
-  for (int64_t i = 0; i < nrows && env.ok(); ++i) fill_u32(env, (uint32_t *)(Y + i * ldy), N, 0u);
+  if (nrows > 0)
+    US_LAUNCH(env, "zero_rows", 4.0 * nrows * N, zero_rows_kernel, ceil_div<int64_t>(nrows * N, 256), 256, Y, nrows, N, ldy);
+}
+
+// scratch of the entry-balanced product: two carry rows per chunk (row index + one value per column of the lane layout)
+static size_t carry_rows_bytes(int64_t nnz) {
+  return ((size_t)ceil_div<int64_t>(nnz, CS_CHUNK) * 2 * sizeof(int32_t) + 255) / 256 * 256;
+}
+size_t entry_balanced_scratch_bytes(int64_t nnz, int64_t N, int vec) {
+  const int cbw = 64 * vec;
+  return carry_rows_bytes(nnz) + (size_t)ceil_div<int64_t>(nnz, CS_CHUNK) * 2 * ceil_div<int64_t>(N, cbw) * cbw * sizeof(float);
 }
 
 static void entry_balanced_spmm(Env &env, const us_formatted &A, const RowSrc &rs, const int32_t *col,
@@ -418,11 +436,10 @@ static void entry_balanced_spmm(Env &env, const us_formatted &A, const RowSrc &r
   // Y must already hold the values to add to (zeros for a plain product)
   const double xy = 4.0 * N * (A.ncols + A.nrows);
   const int64_t nchunks = ceil_div<int64_t>(A.nnz, CS_CHUNK);
-  const size_t rows_bytes = (size_t)nchunks * 2 * sizeof(int32_t);
-  const size_t rows_pad = (rows_bytes + 255) / 256 * 256;
+  const size_t rows_pad = carry_rows_bytes(A.nnz);
   const int cbw = 64 * vec;
   const int64_t ncbv = ceil_div<int64_t>(N, cbw);
-  char *ws = (char *)ensure_workspace(env, A, rows_pad + (size_t)nchunks * 2 * ncbv * cbw * sizeof(float));
+  char *ws = (char *)ensure_workspace(env, A, entry_balanced_scratch_bytes(A.nnz, N, vec));
   if (!env.ok()) return;
   int32_t *carry_row = (int32_t *)ws;
   float *carry = (float *)(ws + rows_pad);

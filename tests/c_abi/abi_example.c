@@ -60,12 +60,14 @@ int main(void) {
 
   us_formatted *csr = NULL, *dia = NULL;
   US_OK_(us_convert(&ctx, &coo, &csr_desc, &csr));
-  const void *p; int64_t n;
-  US_OK_(us_formatted_array(csr, 1, US_A_PTR, &p, &n));
+  const void *p; int64_t n; int32_t t;
+  US_OK_(us_formatted_array(csr, 1, US_A_PTR, &p, &n, &t));
+  if (t != US_T_INT32) { printf("csr.ptr reported with element type %d\n", (int)t); return 2; }
   if (print_i32("csr.ptr", p, n)) return 2;
-  US_OK_(us_formatted_array(csr, 1, US_A_IDX, &p, &n));
+  US_OK_(us_formatted_array(csr, 1, US_A_IDX, &p, &n, NULL));
   if (print_i32("csr.idx", p, n)) return 2;
-  US_OK_(us_formatted_array(csr, 0, US_A_VAL, &p, &n));
+  US_OK_(us_formatted_array(csr, 0, US_A_VAL, &p, &n, &t));
+  if (t != US_T_FLOAT32) { printf("csr.val reported with element type %d\n", (int)t); return 2; }
   if (print_f32("csr.val", p, n)) return 2;
 
   US_OK_(us_spmv(&ctx, csr, d_x, d_y, 0));
@@ -73,9 +75,9 @@ int main(void) {
   if (print_f32("y", d_y, 5)) return 2;
 
   US_OK_(us_convert_formatted(&ctx, csr, &dia_desc, &dia));
-  US_OK_(us_formatted_array(dia, 0, US_A_IDX, &p, &n));
+  US_OK_(us_formatted_array(dia, 0, US_A_IDX, &p, &n, NULL));
   if (print_i32("dia.offsets", p, n)) return 2;
-  US_OK_(us_formatted_array(dia, 0, US_A_VAL, &p, &n));
+  US_OK_(us_formatted_array(dia, 0, US_A_VAL, &p, &n, NULL));
   if (print_f32("dia.val", p, n)) return 2;
   US_OK_(us_spmv(&ctx, dia, d_x, d_y, 0));
   HIP_OK(hipDeviceSynchronize());

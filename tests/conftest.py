@@ -10,6 +10,8 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (runs the HIP library)")
+    import progress
+    progress.capture_manager = config.pluginmanager.getplugin("capturemanager")
 
 
 def load_golden(name):

@@ -104,4 +104,4 @@ def test_host_side_checks_return_before_any_device_work():
     assert L.us_decompose(C.byref(ctx), C.byref(coo), C.byref(csr), C.byref(csr), C.byref(pred),
                           C.byref(oa), C.byref(ob)) == -4
     assert L.us_spmm(C.byref(ctx), None, None, 4, 4, None, 4, 0) == -1
-    assert L.us_formatted_array(None, 0, 0, None, None) == -1
+    assert L.us_formatted_array(None, 0, 0, None, None, None) == -1

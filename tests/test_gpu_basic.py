@@ -1,4 +1,6 @@
 """HIP library vs oracle on small inputs: every format, edge cases, error paths."""
+import zlib
+
 import numpy as np
 import pytest
 import torch
@@ -43,18 +45,19 @@ def test_convert_matches_oracle(ctx, name, desc, shape):
     nr, nc, nnz = shape
     if name in ("DIA", "DIAv") and nnz > 5000:
         pytest.skip("dense diagonal slab too large for a scattered matrix")
-    rng = np.random.default_rng(hash((name, shape)) % (2 ** 32))
+    seed = zlib.crc32(repr((name, shape)).encode())   # the same input in every run of the suite
+    rng = np.random.default_rng(seed)
     r, c, v = random_coo(rng, nr, nc, nnz)
     o = O.convert(nr, nc, r, c, v, desc)
     g = B.us_convert(ctx, nr, nc, dev(r), dev(c), dev(v), us_desc_of(desc))
-    assert_same_layout(g, o, f"{name} {shape}")
+    assert_same_layout(g, o, f"{name} {shape} seed {seed}")
     g.free()
 
 
 @pytest.mark.parametrize("name,desc", FORMATS, ids=[f[0] for f in FORMATS])
 def test_spmv_spmm_all_formats(ctx, name, desc):
     from paper_2403_05802_amd import binding as B
-    from helpers import TOL, dev, host, rel_err, us_desc_of
+    from helpers import assert_product, dev, host, row_terms, us_desc_of
     rng = np.random.default_rng(7)
     nr, nc = 777, 530
     r, c, v = random_coo(rng, nr, nc, 1500 if name.startswith("DIA") else 30000)
@@ -62,31 +65,32 @@ def test_spmv_spmm_all_formats(ctx, name, desc):
     x = rng.uniform(-1, 1, nc).astype(np.float32)
     yref = O.spmv_coo(nr, nc, r, c, v, x)
     scale = O.abs_row_sums(nr, r, c, v, x)
+    nt = row_terms(nr, r)
     y = torch.full((nr,), 7.0, device="cuda")
     B.us_spmv(ctx, g, dev(x), y)
-    assert rel_err(host(y), yref, scale) <= TOL, name
+    assert_product(host(y), yref, scale, nt, f"{name} spmv")
     y0 = rng.uniform(-1, 1, nr).astype(np.float32)
     y = dev(y0)
     B.us_spmv(ctx, g, dev(x), y, accumulate=True)
-    assert rel_err(host(y), yref + y0, scale + np.abs(y0)) <= TOL, name
+    assert_product(host(y), yref + y0, scale + np.abs(y0), nt + 1, f"{name} spmv accumulate")
     for N in (1, 5, 64, 130, 260):
         X = rng.uniform(-1, 1, (nc, N)).astype(np.float32)
         Yref = O.spmm_coo(nr, nc, r, c, v, X)
         S = O.spmm_coo(nr, nc, r, c, np.abs(v), np.abs(X))
         Y = torch.full((nr, N), -3.0, device="cuda")
         B.us_spmm(ctx, g, dev(X), Y)
-        assert rel_err(host(Y), Yref, S) <= TOL, (name, N)
+        assert_product(host(Y), Yref, S, nt[:, None], f"{name} spmm N={N}")
         Y0 = rng.uniform(-1, 1, (nr, N)).astype(np.float32)
         Y = dev(Y0)
         B.us_spmm(ctx, g, dev(X), Y, accumulate=True)
-        assert rel_err(host(Y), Yref + Y0, S + np.abs(Y0)) <= TOL, (name, N)
+        assert_product(host(Y), Yref + Y0, S + np.abs(Y0), nt[:, None] + 1, f"{name} spmm N={N} accumulate")
     g.free()
 
 
 def test_config1_csr_spmv(ctx):
     """4096 x 4096, 40,960 uniformly placed entries: COO -> CSR bit-exact, then SpMV."""
     from paper_2403_05802_amd import binding as B
-    from helpers import TOL, assert_same_layout, coo_to_dev, dev, host, rel_err, us_desc_of
+    from helpers import assert_product, assert_same_layout, coo_to_dev, dev, host, row_terms, us_desc_of
     m = W.cfg1_uniform()
     o = O.convert(m.nrows, m.ncols, m.row, m.col, m.val, O.CSR())
     g = B.us_convert(ctx, m.nrows, m.ncols, *coo_to_dev(m), us_desc_of(O.CSR()))
@@ -96,7 +100,7 @@ def test_config1_csr_spmv(ctx):
     B.us_spmv(ctx, g, dev(x), y)
     yref = O.spmv(o, x)
     np.testing.assert_allclose(yref, O.spmv_coo(m.nrows, m.ncols, m.row, m.col, m.val, x), atol=1e-12)
-    assert rel_err(host(y), yref, O.abs_row_sums(m.nrows, m.row, m.col, m.val, x)) <= TOL
+    assert_product(host(y), yref, O.abs_row_sums(m.nrows, m.row, m.col, m.val, x), row_terms(m.nrows, m.row), "cfg1 spmv")
     # determinism: a second conversion and product give identical bytes
     g2 = B.us_convert(ctx, m.nrows, m.ncols, *coo_to_dev(m), us_desc_of(O.CSR()))
     y2 = torch.empty(m.nrows, device="cuda")
@@ -109,7 +113,7 @@ def test_free_without_waiting(ctx):
     """us_free_async right after products were enqueued: the next conversion takes the freed memory over while
     they may still run, and the stream order keeps their results intact."""
     from paper_2403_05802_amd import binding as B
-    from helpers import TOL, assert_same_layout, dev, host, rel_err, us_desc_of
+    from helpers import assert_product, assert_same_layout, dev, host, row_terms, us_desc_of
     m = W.cfg2_powerlaw(n=1 << 15, target_nnz=1 << 20, max_len=4000)
     r, c, v = dev(m.row), dev(m.col), dev(m.val)
     rng = np.random.default_rng(3)
@@ -130,7 +134,7 @@ def test_free_without_waiting(ctx):
     assert_same_layout(g, O.convert(m.nrows, m.ncols, m.row, m.col, m.val, O.CSR()), "after async frees")
     g.free()
     for y in ys:
-        assert rel_err(host(y), yref, scale) <= TOL
+        assert_product(host(y), yref, scale, row_terms(m.nrows, m.row), "after async frees")
     assert ctx.live_bytes() == before
 
 
@@ -185,7 +189,7 @@ def test_bcsr44_spmm_fast_and_guarded_groups(ctx, nc, N):
     """4x4 blocks on the matrix cores: block rows with 0..70 blocks (full groups of eight, leftovers, more than
     64 blocks), a block grid that divides the matrix (nc = 512) or sticks out of it (530), ragged N."""
     from paper_2403_05802_amd import binding as B
-    from helpers import TOL, dev, host, rel_err, us_desc_of
+    from helpers import assert_product, dev, host, row_terms, us_desc_of
     rng = np.random.default_rng(nc + N)
     nr = 301
     rows, cols = [], []
@@ -205,9 +209,10 @@ def test_bcsr44_spmm_fast_and_guarded_groups(ctx, nc, N):
     S = O.spmm_coo(nr, nc, r, c, np.abs(v), np.abs(X))
     Y = torch.full((nr, N), -3.0, device="cuda")
     B.us_spmm(ctx, g, dev(X), Y)
-    assert rel_err(host(Y), O.spmm_coo(nr, nc, r, c, v, X), S) <= TOL
+    nt = row_terms(nr, r)[:, None]
+    assert_product(host(Y), O.spmm_coo(nr, nc, r, c, v, X), S, nt, f"bcsr44 nc={nc} N={N}")
     Y0 = rng.uniform(-1, 1, (nr, N)).astype(np.float32)
     Y = dev(Y0)
     B.us_spmm(ctx, g, dev(X), Y, accumulate=True)
-    assert rel_err(host(Y), O.spmm_coo(nr, nc, r, c, v, X) + Y0, S + np.abs(Y0)) <= TOL
+    assert_product(host(Y), O.spmm_coo(nr, nc, r, c, v, X) + Y0, S + np.abs(Y0), nt + 1, f"bcsr44 nc={nc} N={N} accumulate")
     g.free()

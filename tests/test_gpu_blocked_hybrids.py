@@ -42,7 +42,7 @@ def broken_bands(n, ncols, seed, keep=0.85, extra=0.02):
 @pytest.mark.parametrize("b,thld", [(3, 3), (3, 2), (4, 4), (16, 12), (1, 1)])
 def test_bdia_csr_hybrid(ctx, shape, b, thld):
     from paper_2403_05802_amd import binding as B
-    from helpers import TOL, assert_same_layout, dev, host, rel_err, us_desc_of, us_pred_of
+    from helpers import assert_product, row_terms, assert_same_layout, dev, host, us_desc_of, us_pred_of
     nr, nc = shape
     r, c, v = broken_bands(nr, nc, seed=b * 100 + thld)
     pred = block_pred(b, thld)
@@ -57,13 +57,13 @@ def test_bdia_csr_hybrid(ctx, shape, b, thld):
     y = torch.full((nr,), 3.0, device="cuda")
     B.us_spmv(ctx, ga, dev(x), y)
     B.us_spmv(ctx, gb, dev(x), y, accumulate=True)
-    assert rel_err(host(y), O.spmv_coo(nr, nc, r, c, v, x), O.abs_row_sums(nr, r, c, v, x)) <= TOL
+    assert_product(host(y), O.spmv_coo(nr, nc, r, c, v, x), O.abs_row_sums(nr, r, c, v, x), row_terms(nr, r), "hybrid spmv")
     X = rng.uniform(-1, 1, (nc, 70)).astype(np.float32)
     Y = torch.full((nr, 70), 3.0, device="cuda")
     B.us_spmm(ctx, ga, dev(X), Y)
     B.us_spmm(ctx, gb, dev(X), Y, accumulate=True)
     S = O.spmm_coo(nr, nc, r, c, np.abs(v), np.abs(X))
-    assert rel_err(host(Y), O.spmm_coo(nr, nc, r, c, v, X), S) <= TOL
+    assert_product(host(Y), O.spmm_coo(nr, nc, r, c, v, X), S, row_terms(nr, r)[:, None], "hybrid spmm")
     ga.free(); gb.free()
 
 
@@ -109,7 +109,7 @@ def test_bdia_hybrid_errors_and_empty(ctx):
 def test_bdia_hybrid_on_scaled_banded_workload(ctx):
     """Config-3-like matrix (7 diagonals + 1 % scattered) at 2^17 rows with the Figure 3c program."""
     from paper_2403_05802_amd import binding as B
-    from helpers import TOL, assert_same_layout, coo_to_dev, dev, host, rel_err, us_desc_of, us_pred_of
+    from helpers import assert_product, row_terms, assert_same_layout, coo_to_dev, dev, host, us_desc_of, us_pred_of
     m = W.cfg3_banded(n=1 << 17)
     pred = block_pred(4, 4)
     oa, ob, mask = O.decompose(m.nrows, m.ncols, m.row, m.col, m.val, O.BDIA(4), O.CSR(), pred)
@@ -121,7 +121,7 @@ def test_bdia_hybrid_on_scaled_banded_workload(ctx):
     B.us_spmv(ctx, ga, dev(x), y); B.us_spmv(ctx, gb, dev(x), y, accumulate=True)
     yref = O.spmv(oa, x) + O.spmv(ob, x)
     np.testing.assert_allclose(yref, O.spmv_coo(m.nrows, m.ncols, m.row, m.col, m.val, x), atol=1e-9)
-    assert rel_err(host(y), yref, O.abs_row_sums(m.nrows, m.row, m.col, m.val, x)) <= TOL
+    assert_product(host(y), yref, O.abs_row_sums(m.nrows, m.row, m.col, m.val, x), row_terms(m.nrows, m.row), "hybrid spmv")
 
 
 def clustered_blocks(nr, nc, seed, bh, bw, dense_blocks, fill, extra):
@@ -148,7 +148,7 @@ def test_block_threshold_hybrid(ctx, bh, bw, thld):
     """Decomposition of the BELL/COO case study (Section 7.2.2): blocks holding at least `thld` entries go to
     the blocked part (stored as BCSR here), the rest stays COO; SpMM over the hybrid."""
     from paper_2403_05802_amd import binding as B
-    from helpers import TOL, assert_same_layout, dev, host, rel_err, us_desc_of, us_pred_of
+    from helpers import assert_product, row_terms, assert_same_layout, dev, host, us_desc_of, us_pred_of
     nr, nc = 1003, 2050
     r, c, v = clustered_blocks(nr, nc, seed=bh * 10 + bw, bh=bh, bw=bw, dense_blocks=1500, fill=0.8, extra=20_000)
     pred = O.Predicate((O.div(0, bh), O.div(1, bw)), O.SUM_GE_ABS, abs=thld)
@@ -163,5 +163,5 @@ def test_block_threshold_hybrid(ctx, bh, bw, thld):
         Y = torch.full((nr, 33), 9.0, device="cuda")
         B.us_spmm(ctx, ga, dev(X), Y); B.us_spmm(ctx, gb, dev(X), Y, accumulate=True)
         S = O.spmm_coo(nr, nc, r, c, np.abs(v), np.abs(X))
-        assert rel_err(host(Y), O.spmm_coo(nr, nc, r, c, v, X), S) <= TOL
+        assert_product(host(Y), O.spmm_coo(nr, nc, r, c, v, X), S, row_terms(nr, r)[:, None], "hybrid spmm")
         ga.free(); gb.free()

@@ -34,19 +34,21 @@ def test_all_entries_in_one_row_and_one_column(ctx):
     roundtrip(ctx, n, n, rows, cols, v, [O.CSR(), O.DCSR(), O.COO(), O.CSC(), O.BCSR(4)])
     roundtrip(ctx, n, n, cols, rows, v, [O.CSR(), O.DCSR(), O.CSC(), O.DCSC()])
     from paper_2403_05802_amd import binding as B
-    from helpers import TOL, dev, host, rel_err, us_desc_of
+    from helpers import assert_product, dev, host, row_terms, us_desc_of
     x = rng.uniform(-1, 1, n).astype(np.float32)
     for d in (O.CSR(), O.DCSR(), O.COO()):
         g = B.us_convert(ctx, n, n, dev(rows), dev(cols), dev(v), us_desc_of(d))
         y = torch.empty(n, device="cuda")
         B.us_spmv(ctx, g, dev(x), y)
-        assert rel_err(host(y), O.spmv_coo(n, n, rows, cols, v, x), O.abs_row_sums(n, rows, cols, v, x)) <= TOL
+        assert_product(host(y), O.spmv_coo(n, n, rows, cols, v, x), O.abs_row_sums(n, rows, cols, v, x), row_terms(n, rows),
+                       f"one row of {cols.size} entries, spmv {d}")
         X = rng.uniform(-1, 1, (n, 128)).astype(np.float32)
         Y = torch.empty(n, 128, device="cuda")
         B.us_spmm(ctx, g, dev(X), Y)
         ref = v.astype(np.float64) @ X[cols].astype(np.float64)
         got = host(Y[12345])
-        assert np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 2.0 ** -4 * (np.abs(v) @ np.abs(X[cols])))) <= TOL
+        assert_product(got, ref, np.abs(v).astype(np.float64) @ np.abs(X[cols]).astype(np.float64), float(cols.size),
+                       f"one row of {cols.size} entries, spmm {d}")
         assert float(Y.abs().sum()) == pytest.approx(float(np.abs(got).sum()), rel=1e-5)   # other rows are zero
         g.free()
 
@@ -313,3 +315,32 @@ def test_percentile_cut_over_many_length_distributions(ctx):
             assert_same_layout(ga, oa, f"ELL part, {nrows} rows, {num}/{den}")
             assert_same_layout(gb, ob, f"COO part, {nrows} rows, {num}/{den}")
             ga.free(); gb.free()
+
+
+def test_spmm_with_row_strides(ctx):
+    """X and Y as column slices of wider arrays (ldx > N, ldy > N): every layout, with and without accumulation;
+    the columns of Y beyond N are the caller's and must come back untouched."""
+    from paper_2403_05802_amd import binding as B
+    from helpers import assert_product, dev, host, row_terms, us_desc_of
+    rng = np.random.default_rng(31)
+    nr, nc, N, ldx, ldy = 300, 260, 70, 96, 80
+    lin = rng.choice(nr * nc, size=6000, replace=False)
+    r, c = (lin // nc).astype(np.int32), (lin % nc).astype(np.int32)
+    v = rng.uniform(-1, 1, r.size).astype(np.float32); v[v == 0] = 0.5
+    Xw = rng.uniform(-1, 1, (nc, ldx)).astype(np.float32)
+    Yw0 = rng.uniform(-1, 1, (nr, ldy)).astype(np.float32)
+    ref = O.spmm_coo(nr, nc, r, c, v, Xw[:, :N])
+    S = O.spmm_coo(nr, nc, r, c, np.abs(v), np.abs(Xw[:, :N]))
+    nt = row_terms(nr, r)[:, None]
+    for d in (O.CSR(), O.DCSR(), O.COO(), O.CSC(), O.ELL(), O.BCSR(4), O.BCSR(2, 3), O.BDIA(3), O.CSB(16), O.CISR_PLUS(5)):
+        g = B.us_convert(ctx, nr, nc, dev(r), dev(c), dev(v), us_desc_of(d))
+        for acc in (False, True):
+            Xd, Yd = dev(Xw), dev(Yw0)
+            B.us_spmm(ctx, g, Xd[:, :N], Yd[:, :N], accumulate=acc)
+            got = host(Yd)
+            assert np.array_equal(got[:, N:], Yw0[:, N:]), (d, acc)
+            if acc:
+                assert_product(got[:, :N], ref + Yw0[:, :N], S + np.abs(Yw0[:, :N]), nt + 1, f"strided spmm {d} accumulate")
+            else:
+                assert_product(got[:, :N], ref, S, nt, f"strided spmm {d}")
+        g.free()

@@ -38,11 +38,11 @@ def test_csr_beyond_the_benchmark_sizes(n, finish):
     from paper_2403_05802_amd import binding as B
     dim, n, row, col, val, sums = generate(n)
     ctx = B.Context("cuda:0")
-    B.us_set_sort_lds_finish(finish)
+    ctx.set_sort_lds_finish(finish)
     try:
         g = B.us_convert(ctx, dim, dim, row, col, val, B.us_desc_preset(B.US_F_CSR))
     finally:
-        B.us_set_sort_lds_finish(None)
+        ctx.set_sort_lds_finish(None)
     ptr, idx, v = g.ptr(1), g.idx(1), g.val()
     assert ptr.numel() == dim + 1 and idx.numel() == n and v.numel() == n
     assert int(ptr[0]) == 0 and int(ptr[-1]) == n

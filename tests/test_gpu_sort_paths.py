@@ -19,13 +19,12 @@ def ctx():
 
 
 @contextlib.contextmanager
-def lds_finish():
-    from paper_2403_05802_amd import binding as B
-    B.us_set_sort_lds_finish(True)
+def lds_finish(ctx):
+    ctx.set_sort_lds_finish(True)
     try:
         yield
     finally:
-        B.us_set_sort_lds_finish(None)
+        ctx.set_sort_lds_finish(None)
 
 
 def distinct(nr, nc, r, c):
@@ -45,7 +44,7 @@ def scatter_passes(ctx, nr, nc, r, c, v, desc):
     from helpers import dev, us_desc_of
     ctx.enable_profile(); ctx.profile_reset()
     try:
-        with lds_finish():
+        with lds_finish(ctx):
             B.us_convert(ctx, nr, nc, dev(r), dev(c), dev(v), us_desc_of(desc)).free()
         return {e["kernel"]: e["launches"] for e in ctx.profile_report()}.get("radix_scatter", 0)
     finally:
@@ -57,7 +56,7 @@ def check(ctx, nr, nc, r, c, v, descs):
     from helpers import assert_same_layout, dev, us_desc_of
     for d in descs:
         o = O.convert(nr, nc, r, c, v, d)
-        with lds_finish():
+        with lds_finish(ctx):
             g = B.us_convert(ctx, nr, nc, dev(r), dev(c), dev(v), us_desc_of(d))
         assert_same_layout(g, o, str(d))
         g.free()
@@ -114,13 +113,13 @@ def test_errors_are_reported_on_this_path_too(ctx):
     for at in (3, r.size - 1, int(np.flatnonzero(r == 5)[7])):       # duplicate in a small and in a split bucket
         r2 = np.append(r, r[at]); c2 = np.append(c, c[at]); v2 = np.append(v, np.float32(1))
         for d in (O.CSR(), O.BCSR(4)):
-            with lds_finish(), pytest.raises(B.UnisparseError) as ei:
+            with lds_finish(ctx), pytest.raises(B.UnisparseError) as ei:
                 B.us_convert(ctx, nr, nc, dev(r2), dev(c2), dev(v2), us_desc_of(d))
             assert ei.value.code == "US_ERR_DUPLICATE"
     for bad_r, bad_c in ((nr, 0), (0, nc), (-1, 3), (2**31 - 1, 2**31 - 1)):
         r2 = np.append(r, np.int32(bad_r)); c2 = np.append(c, np.int32(bad_c)); v2 = np.append(v, np.float32(1))
         for d in (O.CSR(), O.BCSR(4), O.CSC()):
-            with lds_finish(), pytest.raises(B.UnisparseError) as ei:
+            with lds_finish(ctx), pytest.raises(B.UnisparseError) as ei:
                 B.us_convert(ctx, nr, nc, dev(r2), dev(c2), dev(v2), us_desc_of(d))
             assert ei.value.code == "US_ERR_INDEX_RANGE"
 
@@ -135,7 +134,7 @@ def test_scaled_workloads_and_hybrids(ctx):
     m = W.cfg5_powerlaw_local(n=100_000, target_nnz=2_000_000, max_len=20000)
     pred = O.Predicate((O.d0(),), O.RANK_LT_PERCENTILE, num=9, den=10)
     oa, ob, _ = O.decompose(m.nrows, m.ncols, m.row, m.col, m.val, O.ELL(), O.COO(), pred)
-    with lds_finish():
+    with lds_finish(ctx):
         ga, gb = B.us_decompose(ctx, m.nrows, m.ncols, *coo_to_dev(m), us_desc_of(O.ELL()), us_desc_of(O.COO()),
                                 us_pred_of(pred))
     assert_same_layout(ga, oa, "ELL part"); assert_same_layout(gb, ob, "COO part")
