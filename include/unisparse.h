@@ -51,7 +51,8 @@ enum {
   US_ERR_ALLOC = -6,            /* allocator returned NULL                                       */
   US_ERR_OVERFLOW = -7,         /* an output array would need 2^31 or more elements             */
   US_ERR_HIP = -8,              /* a HIP runtime call or kernel launch failed                    */
-  US_ERR_FORMAT_MISMATCH = -9   /* compute op not available for this formatted tensor            */
+  US_ERR_FORMAT_MISMATCH = -9,  /* compute op not available for this formatted tensor            */
+  US_ERR_SCRATCH_LIMIT = -10    /* us_spmv_noalloc: the product needs more scratch than US_NOALLOC_SCRATCH_BYTES */
 };
 
 /* Execution context.  alloc/free may be NULL: the library then uses hipMalloc/hipFree.
@@ -176,6 +177,20 @@ us_status us_decompose(const us_ctx *ctx, const us_coo *coo, const us_format_des
  * COO, CSB) scatter with fp32 atomics, so the last bits may differ from call to call; this holds for
  * us_spmm as well. */
 us_status us_spmv(const us_ctx *ctx, const us_formatted *A, const float *x, float *y, int32_t accumulate);
+
+/* us_spmv for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical results; the scratch of the
+ * product (partial sums of rows cut by a tile boundary, which us_spmv keeps with the tensor and may have to
+ * allocate or grow through us_ctx.alloc) is a fixed array of US_NOALLOC_SCRATCH_BYTES in the device memory of
+ * every GPU the library runs on, held until the process ends.  The call makes no hipMalloc / hipFree, never
+ * calls us_ctx.alloc / us_ctx.free and ignores us_ctx.profile (event creation allocates).
+ * Limit: a product that needs more scratch returns US_ERR_SCRATCH_LIMIT and enqueues nothing.  Compressed rows
+ * (CSR, DCSR, CISR-plus) take 8 bytes per 2048 rows + entries, so every tensor the interface can hold fits;
+ * row-major COO takes 520 bytes per 512 entries (about 16.5 M entries at most); the other layouts take none.
+ * All calls on one GPU share the array: two calls that overlap in time on one GPU (two streams, two threads)
+ * race on it, whatever tensors they multiply. */
+#define US_NOALLOC_SCRATCH_BYTES (16u << 20)
+us_status us_spmv_noalloc(const us_ctx *ctx, const us_formatted *A, const float *x, float *y, int32_t accumulate);
 
 /* Y = A X or Y += A X with dense row-major X (ncols x N, leading dimension ldx >= N) and
  * Y (nrows x N, ldy >= N), device (Section 7.2.2). */

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libunisparse_hip.so")
 US_OK = 0
 STATUS_NAMES = {0: "US_OK", -1: "US_ERR_NULL", -2: "US_ERR_SHAPE", -3: "US_ERR_INDEX_RANGE",
                 -4: "US_ERR_UNSUPPORTED_DESC", -5: "US_ERR_DUPLICATE", -6: "US_ERR_ALLOC",
-                -7: "US_ERR_OVERFLOW", -8: "US_ERR_HIP", -9: "US_ERR_FORMAT_MISMATCH"}
+                -7: "US_ERR_OVERFLOW", -8: "US_ERR_HIP", -9: "US_ERR_FORMAT_MISMATCH", -10: "US_ERR_SCRATCH_LIMIT"}
 US_E_AFFINE, US_E_DIV, US_E_MOD, US_E_INDIRECT_ENUM, US_E_INDIRECT_SCHEDULE = 0, 1, 2, 3, 4
 (US_F_COO, US_F_CSR, US_F_DCSR, US_F_CSC, US_F_DCSC, US_F_DIA, US_F_DIA_VARIANT, US_F_BCSR, US_F_ELL,
  US_F_BDIA, US_F_CSB, US_F_CISR_PLUS) = range(12)
@@ -27,8 +27,9 @@ US_P_SUM_GE_ABS, US_P_SUM_GE_FRAC_OF_CAPACITY, US_P_RANK_LT_ABS, US_P_RANK_LT_PE
 US_A_SIZE, US_A_PTR, US_A_IDX, US_A_VAL = range(4)
 US_T_NONE, US_T_INT32, US_T_FLOAT32 = range(3)
 US_SORT_FINISH_AUTO, US_SORT_FINISH_LDS, US_SORT_FINISH_PASSES = range(3)
+US_NOALLOC_SCRATCH_BYTES = 16 << 20
 
-EXPORTS = ["us_convert", "us_convert_formatted", "us_decompose", "us_spmv", "us_spmm", "us_formatted_array",
+EXPORTS = ["us_convert", "us_convert_formatted", "us_decompose", "us_spmv", "us_spmv_noalloc", "us_spmm", "us_formatted_array",
            "us_formatted_info", "us_free", "us_free_async", "us_status_str", "us_desc_preset", "us_profile_create",
            "us_profile_destroy", "us_profile_reset", "us_profile_collect", "us_profile_entry", "us_profile_set_min_bytes"]
 
@@ -92,6 +93,7 @@ def lib() -> C.CDLL:
                                    C.POINTER(us_format_desc), C.POINTER(us_predicate),
                                    C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]
         L.us_spmv.argtypes = [C.POINTER(us_ctx), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
+        L.us_spmv_noalloc.argtypes = [C.POINTER(us_ctx), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
         L.us_spmm.argtypes = [C.POINTER(us_ctx), C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p,
                               C.c_int64, C.c_int32]
         L.us_formatted_array.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_void_p),
@@ -111,7 +113,7 @@ def lib() -> C.CDLL:
         L.us_profile_set_min_bytes.restype = C.c_int32
         L.us_profile_entry.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_int64),
                                        C.POINTER(C.c_double), C.POINTER(C.c_double)]
-        for fn in ("us_desc_preset", "us_convert", "us_decompose", "us_spmv", "us_spmm", "us_formatted_array",
+        for fn in ("us_desc_preset", "us_convert", "us_decompose", "us_spmv", "us_spmv_noalloc", "us_spmm", "us_formatted_array",
                    "us_formatted_info", "us_profile_create", "us_profile_reset", "us_profile_collect",
                    "us_profile_entry"):
             getattr(L, fn).restype = C.c_int32
@@ -337,6 +339,14 @@ def us_spmv(ctx: Context, A: Formatted, x: torch.Tensor, y: torch.Tensor, accumu
     assert x.dtype == torch.float32 and y.dtype == torch.float32 and x.is_cuda and y.is_cuda
     assert x.is_contiguous() and y.is_contiguous() and x.numel() == A.ncols and y.numel() == A.nrows
     _check(lib().us_spmv(C.byref(ctx.c), A.handle, x.data_ptr(), y.data_ptr(), 1 if accumulate else 0), "us_spmv")
+    return y
+
+
+def us_spmv_noalloc(ctx: Context, A: Formatted, x: torch.Tensor, y: torch.Tensor, accumulate: bool = False) -> torch.Tensor:
+    assert x.dtype == torch.float32 and y.dtype == torch.float32 and x.is_cuda and y.is_cuda
+    assert x.is_contiguous() and y.is_contiguous() and x.numel() == A.ncols and y.numel() == A.nrows
+    _check(lib().us_spmv_noalloc(C.byref(ctx.c), A.handle, x.data_ptr(), y.data_ptr(), 1 if accumulate else 0),
+           "us_spmv_noalloc")
     return y
 
 

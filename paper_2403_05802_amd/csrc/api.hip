@@ -17,6 +17,7 @@ const char *us_status_str(us_status s) {
     case US_ERR_OVERFLOW: return "US_ERR_OVERFLOW";
     case US_ERR_HIP: return "US_ERR_HIP";
     case US_ERR_FORMAT_MISMATCH: return "US_ERR_FORMAT_MISMATCH";
+    case US_ERR_SCRATCH_LIMIT: return "US_ERR_SCRATCH_LIMIT";
     default: return "US_ERR_UNKNOWN";
   }
 }
@@ -116,6 +117,12 @@ us_status us_spmv(const us_ctx *ctx, const us_formatted *A, const float *x, floa
   if (!ctx || !A || !x || !y) return US_ERR_NULL;
   Env env(ctx);
   return spmv_impl(env, *A, x, y, accumulate != 0);
+}
+
+us_status us_spmv_noalloc(const us_ctx *ctx, const us_formatted *A, const float *x, float *y, int32_t accumulate) {
+  if (!ctx || !A || !x || !y) return US_ERR_NULL;
+  Env env(ctx);
+  return spmv_noalloc_impl(env, *A, x, y, accumulate != 0);
 }
 
 us_status us_spmm(const us_ctx *ctx, const us_formatted *A, const float *X, int64_t N, int64_t ldx, float *Y,

@@ -46,6 +46,9 @@ struct Env {
   int lds_finish;             // sort: finish buckets inside LDS: 1 always, 0 never (also the retry after Flags::retry),
                               // -1 by key layout (blocked tuples yes, (row, col) tuples no)
   bool dia_marks = false;     // DIA slab: find occupied slots with a byte map instead of the fill pattern (set for the retry)
+  // set by the entry point that must not allocate: ensure_workspace hands out this memory instead of the tensor's
+  // own scratch and fails with US_ERR_SCRATCH_LIMIT when a product needs more
+  char *fixed_ws = nullptr; size_t fixed_ws_bytes = 0;
 
   explicit Env(const us_ctx *c)
       : ctx(c), stream(c ? (hipStream_t)c->hip_stream : nullptr), prof(c ? (Profile *)c->profile : nullptr),
@@ -246,6 +249,7 @@ void *ensure_workspace(Env &env, const us_formatted &A, size_t bytes);
 void spmv_prepare(Env &env, us_formatted *f, const int32_t *nmajor_dev = nullptr, int64_t nmajor_cap = 0);
 int64_t spmv_tiles(int64_t nmajor, int64_t nnz);
 us_status spmv_impl(Env &env, const us_formatted &A, const float *x, float *y, bool accumulate);
+us_status spmv_noalloc_impl(Env &env, const us_formatted &A, const float *x, float *y, bool accumulate);
 us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, int64_t ldx, float *Y,
                     int64_t ldy, bool accumulate);
 // scratch the entry-balanced product (row-major COO, CSR, DCSR) takes from ensure_workspace; vec = columns per lane

@@ -294,6 +294,10 @@ void free_formatted(Env &env, us_formatted *f) {
 }
 
 void *ensure_workspace(Env &env, const us_formatted &A, size_t bytes) {
+  if (env.fixed_ws) {
+    if (bytes > env.fixed_ws_bytes) { env.fail(US_ERR_SCRATCH_LIMIT); return nullptr; }
+    return env.fixed_ws;
+  }
   if (A.ws_bytes >= bytes && A.ws) return A.ws;
   if (A.ws) {
     env.sync();  // an earlier compute call may still use the old scratch

@@ -4,6 +4,8 @@
 #include "common.h"
 #include "device.h"
 
+#include <atomic>
+
 namespace us {
 
 // ------------------------------------------------------------------ compressed rows (CSR / DCSR / CSC-transposed use)
@@ -392,6 +394,41 @@ us_status spmv_impl(Env &env, const us_formatted &A, const float *x, float *y, b
     default: break;
   }
   return US_ERR_FORMAT_MISMATCH;
+}
+
+// ------------------------------------------------------------------ the product for callers that cannot allocate
+// The partial-sum scratch of the kernels above comes from this array instead of the tensor's own (allocated) one.
+// Every GPU holds its own copy of the array at its own address; the name below is only a handle for
+// hipGetSymbolAddress, which is asked once per device (with that device current), and the kernels get the
+// address it returns as an ordinary argument.
+static __device__ __align__(256) unsigned char scratch[US_NOALLOC_SCRATCH_BYTES];
+constexpr int NOALLOC_MAX_DEVICES = 64;
+static std::atomic<void *> g_scratch_ptr[NOALLOC_MAX_DEVICES];
+
+static void *scratch_of_current_device(Env &env) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= NOALLOC_MAX_DEVICES) { env.fail(US_ERR_HIP); return nullptr; }
+  void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p) return p;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { env.fail(US_ERR_HIP); return nullptr; }
+  g_scratch_ptr[dev].store(p, std::memory_order_release);   // (two first calls at once store the same address)
+  return p;
+}
+
+us_status spmv_noalloc_impl(Env &env, const us_formatted &A, const float *x, float *y, bool accumulate) {
+  env.prof = nullptr;   // timing a launch creates events, which allocates
+  env.fixed_ws = (char *)scratch_of_current_device(env);
+  env.fixed_ws_bytes = US_NOALLOC_SCRATCH_BYTES;
+  if (!env.ok()) return env.status;
+  // Nothing of the array has to start at zero: the kernels write every carry slot they later read (one pair per
+  // tile or chunk of THIS call), so what an earlier, larger call left behind is never looked at.
+  // The scratch a product needs is known before its first launch (ensure_workspace is asked first), so a call
+  // over the limit enqueues nothing -- except the clearing of y that some layouts start with, which is why the
+  // size is checked here for the layouts that have one.
+  if (A.pattern == P_COO && !A.swapped && A.nnz > 0 &&
+      entry_balanced_scratch_bytes(A.nnz, 1, 1) > US_NOALLOC_SCRATCH_BYTES)   // (the product runs as an SpMM of one column)
+    return US_ERR_SCRATCH_LIMIT;
+  return spmv_impl(env, A, x, y, accumulate);
 }
 
 }  // namespace us
