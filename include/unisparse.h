@@ -185,11 +185,11 @@ us_status us_spmv(const us_ctx *ctx, const us_formatted *A, const float *x, floa
  * every GPU the library runs on, held until the process ends.  The call makes no hipMalloc / hipFree, never
  * calls us_ctx.alloc / us_ctx.free and ignores us_ctx.profile (event creation allocates).
  * Limit: a product that needs more scratch returns US_ERR_SCRATCH_LIMIT and enqueues nothing.  Compressed rows
- * (CSR, DCSR, CISR-plus) take 8 bytes per 2048 rows + entries, so every tensor the interface can hold fits;
- * row-major COO takes 520 bytes per 512 entries (about 16.5 M entries at most); the other layouts take none.
+ * (CSR, DCSR, CISR-plus) take 8 bytes per 2048 stored rows + entries and row-major COO 8 bytes per 2048 entries,
+ * each half rounded up to 256 bytes: tensors of up to 2^31 - 2048 rows + entries fit; the other layouts take none.
  * All calls on one GPU share the array: two calls that overlap in time on one GPU (two streams, two threads)
  * race on it, whatever tensors they multiply. */
-#define US_NOALLOC_SCRATCH_BYTES (16u << 20)
+#define US_NOALLOC_SCRATCH_BYTES (8u << 20)
 us_status us_spmv_noalloc(const us_ctx *ctx, const us_formatted *A, const float *x, float *y, int32_t accumulate);
 
 /* Y = A X or Y += A X with dense row-major X (ncols x N, leading dimension ldx >= N) and

@@ -27,7 +27,7 @@ US_P_SUM_GE_ABS, US_P_SUM_GE_FRAC_OF_CAPACITY, US_P_RANK_LT_ABS, US_P_RANK_LT_PE
 US_A_SIZE, US_A_PTR, US_A_IDX, US_A_VAL = range(4)
 US_T_NONE, US_T_INT32, US_T_FLOAT32 = range(3)
 US_SORT_FINISH_AUTO, US_SORT_FINISH_LDS, US_SORT_FINISH_PASSES = range(3)
-US_NOALLOC_SCRATCH_BYTES = 16 << 20
+US_NOALLOC_SCRATCH_BYTES = 8 << 20
 
 EXPORTS = ["us_convert", "us_convert_formatted", "us_decompose", "us_spmv", "us_spmv_noalloc", "us_spmm", "us_formatted_array",
            "us_formatted_info", "us_free", "us_free_async", "us_status_str", "us_desc_preset", "us_profile_create",

@@ -192,6 +192,97 @@ static void spmv_compressed(Env &env, const us_formatted &A, const int32_t *ptr,
   }
 }
 
+// ------------------------------------------------------------------ row-major COO: y[row] += sum of val * x[col] over the row's run
+// The list is sorted by (row, col), so a row is a run of consecutive entries.  A workgroup takes COO_TILE consecutive
+// entries: coalesced loads, products into LDS, then every thread walks COO_IPT consecutive entries and closes the
+// runs that end inside its slice; the run still open at the end of a slice goes through the same segmented scan as
+// the merge-path kernel above, and a run that a tile boundary cuts leaves its partial sum in the tile's carry slot
+// for the fix-up kernel (fixed order everywhere: two calls give the same bits).  y must hold what the sums are
+// added to (zeros for a plain product): rows without entries are not visited.
+constexpr int COO_T = 256, COO_IPT = 8, COO_TILE = COO_T * COO_IPT;
+
+__global__ __launch_bounds__(COO_T) void coo_spmv_kernel(const int32_t *row, const int32_t *col, const float *val,
+                                                        int64_t nnz, int64_t nrows, const float *x, float *y,
+                                                        int32_t *carry_row, float *carry_val) {
+  __shared__ float s_prod[COO_TILE];
+  __shared__ int32_t s_row[COO_TILE + 1];
+  __shared__ int32_t s_wkey[COO_T / 64];
+  __shared__ float s_wval[COO_T / 64];
+  const int64_t base = (int64_t)blockIdx.x * COO_TILE;
+  const int cnt = (int)min((int64_t)COO_TILE, nnz - base);
+  {
+    int32_t ri[COO_IPT], ci[COO_IPT];
+    float vv[COO_IPT], xv[COO_IPT];
+#pragma unroll
+    for (int k = 0; k < COO_IPT; ++k) {   // all loads of the lists first, then all gathers of x
+      const int i = k * COO_T + threadIdx.x;
+      ri[k] = i < cnt ? row[base + i] : -1;
+      ci[k] = i < cnt ? col[base + i] : 0;
+      vv[k] = i < cnt ? val[base + i] : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < COO_IPT; ++k) xv[k] = (k * COO_T + (int)threadIdx.x) < cnt ? x[ci[k]] : 0.f;
+#pragma unroll
+    for (int k = 0; k < COO_IPT; ++k) {
+      const int i = k * COO_T + threadIdx.x;
+      s_prod[i] = vv[k] * xv[k];
+      s_row[i] = ri[k];
+    }
+    // the row of the entry behind the tile (-1: none), which tells whether the tile's last run goes on
+    if (threadIdx.x == 0) s_row[COO_TILE] = base + COO_TILE < nnz ? row[base + COO_TILE] : -1;
+  }
+  __syncthreads();
+
+  const int d = (int)threadIdx.x * COO_IPT;
+  // runs that end inside this thread's slice: the first one may have begun in an earlier thread (it takes what the
+  // scan hands over), the others lie wholly inside the slice and are added to y at once
+  int32_t first_row = -1, open_row = -3;   // open_row: the row whose run goes on behind the slice, or none
+  float sum = 0.f, first_sum = 0.f;
+  bool seen_end = false;
+#pragma unroll
+  for (int k = 0; k < COO_IPT; ++k) {
+    const int i = d + k;
+    if (i < cnt) {
+      const int32_t r = s_row[i];
+      sum += s_prod[i];
+      const int32_t next = s_row[i + 1 < cnt ? i + 1 : COO_TILE];   // behind the last tile: -1
+      if (next != r) {   // the run of row r ends with entry i
+        if (!seen_end) { first_row = r; first_sum = sum; seen_end = true; }
+        else y[r] += sum;
+        sum = 0.f;
+        open_row = -3;
+      } else {
+        open_row = r;
+      }
+    }
+  }
+  SegPair p{open_row, sum};
+  const int lane = lane_id(), w = wave_id();
+#pragma unroll
+  for (int dd = 1; dd < 64; dd <<= 1) {
+    int32_t k = __shfl_up(p.key, dd);
+    float v = __shfl_up(p.val, dd);
+    if (lane >= dd && k == p.key) p.val += v;
+  }
+  if (lane == 63) { s_wkey[w] = p.key; s_wval[w] = p.val; }
+  __syncthreads();
+  int32_t head_key = -2;
+  float wave_carry = 0.f;
+  for (int ww = 0; ww < w; ++ww) {
+    if (s_wkey[ww] == head_key) wave_carry += s_wval[ww];
+    else { head_key = s_wkey[ww]; wave_carry = s_wval[ww]; }
+  }
+  const float incl = p.val + (p.key == head_key ? wave_carry : 0.f);
+  int32_t prev_key = __shfl_up(p.key, 1);
+  float prev_val = __shfl_up(incl, 1);
+  if (lane == 0) { prev_key = head_key; prev_val = wave_carry; }
+  if (first_row >= 0) y[first_row] += first_sum + (prev_key == first_row ? prev_val : 0.f);
+  if (threadIdx.x == COO_T - 1) {   // a run still open here goes on in the next tile: its sum so far is the tile's carry
+    carry_row[blockIdx.x] = p.key >= 0 ? p.key : (int32_t)nrows;
+    carry_val[blockIdx.x] = p.key >= 0 ? incl : 0.f;
+  }
+}
+
 // ------------------------------------------------------------------ DIA: y[i] (+)= sum_k val[k*nrows+i] * x[i+off_k]
 // (the DIA variant keeps the slab indexed by column: val[k*ncols + j], j = i + off_k)
 __global__ __launch_bounds__(256) void dia_spmv_kernel(const int32_t *off, const float *val, int64_t ndiag,
@@ -312,6 +403,22 @@ __global__ __launch_bounds__(256) void csb_spmv_atomic_kernel(const int32_t *ptr
   atomicAdd(&y[row], val[e] * x[col]);
 }
 
+static void spmv_coo_rows(Env &env, const us_formatted &A, const float *x, float *y, bool accumulate) {
+  const int64_t nb = ceil_div<int64_t>(A.nnz, COO_TILE);
+  const size_t half = Env::granule((size_t)(nb > 0 ? nb : 1) * 4);
+  char *ws = (char *)ensure_workspace(env, A, 2 * half);   // (asked for before anything is enqueued)
+  if (!env.ok()) return;
+  if (!accumulate) fill_u32(env, (uint32_t *)y, A.nrows, 0u);
+  if (A.nnz == 0) return;
+  int32_t *carry_row = (int32_t *)ws;
+  float *carry_val = (float *)(ws + half);
+  US_LAUNCH(env, "spmv_coo", 12.0 * A.nnz + 4.0 * A.ncols + 4.0 * A.nrows, coo_spmv_kernel, nb, COO_T,
+            (const int32_t *)A.level[0].idx, (const int32_t *)A.level[1].idx, (const float *)A.val, A.nnz, A.nrows, x, y,
+            carry_row, carry_val);
+  US_LAUNCH(env, "spmv_coo_fixup", 8.0 * nb, (csr_spmv_fixup_kernel<false>), ceil_div<int64_t>(nb, 256), 256,
+            (const int32_t *)carry_row, (const float *)carry_val, nb, A.nrows, (const int32_t *)nullptr, y);
+}
+
 int64_t spmv_tiles(int64_t nmajor, int64_t nnz) { return ceil_div<int64_t>(nmajor + nnz, MP_TILE); }
 
 void spmv_prepare(Env &env, us_formatted *f, const int32_t *nmajor_dev, int64_t nmajor_cap) {
@@ -383,9 +490,8 @@ us_status spmv_impl(Env &env, const us_formatted &A, const float *x, float *y, b
                 (const float *)A.val, (int)A.bh, A.nrows, A.ncols, x, y, accumulate ? 1 : 0);
       return env.status;
     case P_COO:
-      // row-major COO: the entry-balanced SpMM kernel with one column (fixed summation order);
-      // column-major COO scatters with float atomics
-      if (!A.swapped) return spmm_impl(env, A, x, 1, 1, y, 1, accumulate);
+      // row-major COO: runs of equal rows summed in a fixed order; column-major COO scatters with float atomics
+      if (!A.swapped) { spmv_coo_rows(env, A, x, y, accumulate); return env.status; }
       if (!accumulate) fill_u32(env, (uint32_t *)y, A.nrows, 0u);
       if (A.nnz > 0)
         US_LAUNCH(env, "spmv_coo_atomic", 16.0 * A.nnz, coo_spmv_atomic_kernel, ceil_div<int64_t>(A.nnz, 256), 256,
@@ -422,12 +528,13 @@ us_status spmv_noalloc_impl(Env &env, const us_formatted &A, const float *x, flo
   if (!env.ok()) return env.status;
   // Nothing of the array has to start at zero: the kernels write every carry slot they later read (one pair per
   // tile or chunk of THIS call), so what an earlier, larger call left behind is never looked at.
-  // The scratch a product needs is known before its first launch (ensure_workspace is asked first), so a call
-  // over the limit enqueues nothing -- except the clearing of y that some layouts start with, which is why the
-  // size is checked here for the layouts that have one.
-  if (A.pattern == P_COO && !A.swapped && A.nnz > 0 &&
-      entry_balanced_scratch_bytes(A.nnz, 1, 1) > US_NOALLOC_SCRATCH_BYTES)   // (the product runs as an SpMM of one column)
-    return US_ERR_SCRATCH_LIMIT;
+  // what the product will ask ensure_workspace for, checked before anything (a clearing of y, say) is enqueued
+  size_t need = 0;
+  if ((A.pattern == P_CSR || A.pattern == P_DCSR || A.pattern == P_CISR) && !A.swapped)
+    need = 2 * Env::granule(4 * (size_t)spmv_tiles(A.nmajor, A.nnz));
+  else if (A.pattern == P_COO && !A.swapped)
+    need = 2 * Env::granule(4 * (size_t)ceil_div<int64_t>(A.nnz > 0 ? A.nnz : 1, COO_TILE));
+  if (need > US_NOALLOC_SCRATCH_BYTES) return US_ERR_SCRATCH_LIMIT;
   return spmv_impl(env, A, x, y, accumulate);
 }
 

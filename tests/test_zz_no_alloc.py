@@ -57,29 +57,28 @@ def test_noalloc_spmv_matches_spmv_and_never_allocates():
 
 
 def test_noalloc_spmv_rejects_what_does_not_fit():
+    """Compressed rows take 8 bytes of scratch per 2048 rows + entries: 2^31 - 1 entries in 2^20 rows need
+    8,392,704 bytes, the array holds 8 MiB = 8,388,608; 2^29 entries fit."""
     from paper_2403_05802_amd import binding as B
-    from helpers import dev
+    from test_gpu_large import generate
     ctx = B.Context("cuda:0")
-    # row-major COO takes 520 bytes of scratch per 512 entries: 2^25 entries need 34 MB, the array holds 16 MiB
-    n = 1 << 25
-    dim = 1 << 15
-    lin = torch.randperm(dim * dim, device="cuda")[:n]
-    row = (lin // dim).to(torch.int32); col = (lin % dim).to(torch.int32)
-    val = torch.ones(n, device="cuda")
-    del lin
-    g = B.us_convert(ctx, dim, dim, row, col, val, B.us_desc_preset(B.US_F_COO))
+    dim, n, row, col, val, _ = generate((1 << 31) - 1)
+    g = B.us_convert(ctx, dim, dim, row, col, val, B.us_desc_preset(B.US_F_CSR))
+    del row, col, val
     x = torch.ones(dim, device="cuda")
     y = torch.full((dim,), 3.0, device="cuda")
+    n_before = ctx._nalloc
     with pytest.raises(B.UnisparseError) as ei:
         B.us_spmv_noalloc(ctx, g, x, y)
-    assert ei.value.code == "US_ERR_SCRATCH_LIMIT"
+    assert ei.value.code == "US_ERR_SCRATCH_LIMIT" and ctx._nalloc == n_before
     torch.cuda.synchronize()
     assert bool((y == 3.0).all())          # nothing was enqueued
-    B.us_spmv(ctx, g, x, y)                # the allocating call takes it
-    assert float(y.sum()) == float(n)
-    # the same matrix as CSR fits (8 bytes per 2048 rows + entries)
-    h = B.us_convert(ctx, dim, dim, row, col, val, B.us_desc_preset(B.US_F_CSR))
+    g.free()
+    dim, n, row, col, val, _ = generate(1 << 29)
+    g = B.us_convert(ctx, dim, dim, row, col, val, B.us_desc_preset(B.US_F_CSR))
+    del row, col, val
     y2 = torch.empty(dim, device="cuda")
-    B.us_spmv_noalloc(ctx, h, x, y2)
-    assert torch.equal(y2, y)
-    g.free(); h.free()
+    B.us_spmv(ctx, g, x, y)
+    B.us_spmv_noalloc(ctx, g, x, y2)
+    assert torch.equal(bits(y2), bits(y))
+    g.free()
