@@ -108,3 +108,49 @@ def assert_product(y, yref, scale, nterms, what=""):
     e, p = rel_err(y, yref, scale, nterms), plain_rel_err(y, yref)
     print(f"{what}: floored rel. error {e:.3e}, plain max |y-yref|/|yref| {p:.3e}")
     assert e <= TOL, f"{what}: floored rel. error {e:.3e} > {TOL} (plain {p:.3e})"
+
+
+def check_spmm_all_rows(ctx, parts, m, X, what, slab=1 << 17):
+    """Y = sum of parts * X on the GPU; EVERY element of Y is compared with the fp64 product, a slab of rows at a
+    time.  The reference of a slab is the definition Y = A X evaluated by a library matmul (scipy CSR in fp64, built
+    from the original COO); the first 2,000 rows, the 20 longest rows and a random sample of rows are also computed
+    with the oracle's own spmm_coo, which the matmul has to agree with to 1e-12 of the row's absolute sum."""
+    import scipy.sparse as sp
+    import torch
+    from progress import say
+    N = X.shape[1]
+    Y = torch.full((m.nrows, N), -5.0, device="cuda")
+    Xd = dev(X)
+    for k, g in enumerate(parts):
+        B.us_spmm(ctx, g, Xd, Y, accumulate=k > 0)
+    torch.cuda.synchronize()
+    say(f"{what}: product done on the GPU, building the fp64 reference")
+    A = sp.csr_matrix((m.val.astype(np.float64), (m.row, m.col)), shape=(m.nrows, m.ncols))
+    Aabs = abs(A)
+    X64, Xabs = X.astype(np.float64), np.abs(X).astype(np.float64)
+    nt = np.diff(A.indptr).astype(np.float64)
+    # the matmul against the oracle on a sample of rows
+    rng = np.random.default_rng(5)
+    sample = np.unique(np.concatenate([np.arange(min(2000, m.nrows)), np.argsort(nt)[-20:],
+                                       rng.choice(m.nrows, min(2000, m.nrows), replace=False)]))
+    sel = np.isin(m.row, sample)
+    local = np.searchsorted(sample, m.row[sel])
+    Yo = O.spmm_coo(sample.size, m.ncols, local, m.col[sel], m.val[sel], X64)
+    So = (Aabs[sample] @ Xabs)
+    assert np.max(np.abs(A[sample] @ X64 - Yo) / np.maximum(So, 1e-300)) <= 1e-12, what
+    worst, worst_plain, at = 0.0, 0.0, -1
+    for r0 in range(0, m.nrows, slab):
+        r1 = min(r0 + slab, m.nrows)
+        ref = A[r0:r1] @ X64
+        den = np.maximum(np.abs(ref), error_floor(Aabs[r0:r1] @ Xabs, nt[r0:r1, None]))
+        den[den == 0] = 1.0
+        got = host(Y[r0:r1]).astype(np.float64)
+        e = np.abs(got - ref) / den
+        k = int(np.argmax(e))
+        if e.flat[k] > worst:
+            worst, at = float(e.flat[k]), r0 + k // N
+        worst_plain = max(worst_plain, plain_rel_err(got, ref))
+        say(f"{what}: rows {r0}..{r1} checked, worst floored rel. error so far {worst:.3e}")
+    print(f"{what}: all {m.nrows} x {N} outputs: floored rel. error {worst:.3e} (row {at}), plain {worst_plain:.3e}")
+    assert worst <= TOL, (what, worst, at)
+    return Y

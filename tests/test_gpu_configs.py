@@ -6,6 +6,7 @@ import torch
 
 from oracle import unisparse_oracle as O
 from paper_2403_05802_amd import workloads as W
+import helpers as H
 
 pytestmark = pytest.mark.gpu
 
@@ -30,53 +31,6 @@ def check_spmv(ctx, parts, m, x, what="spmv"):
     yref = O.spmv_coo(m.nrows, m.ncols, m.row, m.col, m.val, x)
     assert_product(host(y), yref, O.abs_row_sums(m.nrows, m.row, m.col, m.val, x), row_terms(m.nrows, m.row), what)
     return y
-
-
-def check_spmm_all_rows(ctx, parts, m, X, what, slab=1 << 17):
-    """Y = sum of parts * X on the GPU; EVERY element of Y is compared with the fp64 product, a slab of rows at a
-    time.  The reference of a slab is the definition Y = A X evaluated by a library matmul (scipy CSR in fp64, built
-    from the original COO); the first 2,000 rows, the 20 longest rows and a random sample of rows are also computed
-    with the oracle's own spmm_coo, which the matmul has to agree with to 1e-12 of the row's absolute sum."""
-    import scipy.sparse as sp
-    from paper_2403_05802_amd import binding as B
-    from helpers import TOL, dev, error_floor, host, plain_rel_err
-    from progress import say
-    N = X.shape[1]
-    Y = torch.full((m.nrows, N), -5.0, device="cuda")
-    Xd = dev(X)
-    for k, g in enumerate(parts):
-        B.us_spmm(ctx, g, Xd, Y, accumulate=k > 0)
-    torch.cuda.synchronize()
-    say(f"{what}: product done on the GPU, building the fp64 reference")
-    A = sp.csr_matrix((m.val.astype(np.float64), (m.row, m.col)), shape=(m.nrows, m.ncols))
-    Aabs = abs(A)
-    X64, Xabs = X.astype(np.float64), np.abs(X).astype(np.float64)
-    nt = np.diff(A.indptr).astype(np.float64)
-    # the matmul against the oracle on a sample of rows
-    rng = np.random.default_rng(5)
-    sample = np.unique(np.concatenate([np.arange(min(2000, m.nrows)), np.argsort(nt)[-20:],
-                                       rng.choice(m.nrows, min(2000, m.nrows), replace=False)]))
-    sel = np.isin(m.row, sample)
-    local = np.searchsorted(sample, m.row[sel])
-    Yo = O.spmm_coo(sample.size, m.ncols, local, m.col[sel], m.val[sel], X64)
-    So = (Aabs[sample] @ Xabs)
-    assert np.max(np.abs(A[sample] @ X64 - Yo) / np.maximum(So, 1e-300)) <= 1e-12, what
-    worst, worst_plain, at = 0.0, 0.0, -1
-    for r0 in range(0, m.nrows, slab):
-        r1 = min(r0 + slab, m.nrows)
-        ref = A[r0:r1] @ X64
-        den = np.maximum(np.abs(ref), error_floor(Aabs[r0:r1] @ Xabs, nt[r0:r1, None]))
-        den[den == 0] = 1.0
-        got = host(Y[r0:r1]).astype(np.float64)
-        e = np.abs(got - ref) / den
-        k = int(np.argmax(e))
-        if e.flat[k] > worst:
-            worst, at = float(e.flat[k]), r0 + k // N
-        worst_plain = max(worst_plain, plain_rel_err(got, ref))
-        say(f"{what}: rows {r0}..{r1} checked, worst floored rel. error so far {worst:.3e}")
-    print(f"{what}: all {m.nrows} x {N} outputs: floored rel. error {worst:.3e} (row {at}), plain {worst_plain:.3e}")
-    assert worst <= TOL, (what, worst, at)
-    return Y
 
 
 # ------------------------------------------------------------------ scaled-down versions, full comparison
@@ -132,7 +86,7 @@ def test_cfg4_small_bcsr_spmm(ctx):
     assert_same_layout(g, o, "cfg4s BCSR")
     assert np.array_equal(o.levels[1].ptr, 24 * np.arange(m.nrows // 4 + 1))   # closed form
     X = W.dense_operand(4, (m.ncols, 64))
-    check_spmm_all_rows(ctx, [g], m, X, "cfg4 small spmm", slab=1000)
+    H.check_spmm_all_rows(ctx, [g], m, X, "cfg4 small spmm", slab=1000)
     check_spmv(ctx, [g], m, W.dense_operand(4, m.ncols))
 
 
@@ -146,7 +100,7 @@ def test_cfg5_small_ell_coo_spmm(ctx):
     assert_same_layout(ga, oa, "cfg5s ELL part")
     assert_same_layout(gb, ob, "cfg5s COO part")
     X = W.dense_operand(5, (m.ncols, 128))
-    check_spmm_all_rows(ctx, [ga, gb], m, X, "cfg5 small spmm", slab=7001)
+    H.check_spmm_all_rows(ctx, [ga, gb], m, X, "cfg5 small spmm", slab=7001)
     check_spmv(ctx, [ga, gb], m, W.dense_operand(5, m.ncols))
     # rank split into other format pairs, and with a fixed width
     for da, db, pred in ((O.ELL(), O.CSR(), P90_PRED), (O.CSR(), O.DCSR(), P90_PRED),
@@ -231,7 +185,7 @@ def test_cfg4_full(ctx):
     assert torch.equal(g2.val().view(torch.int32), g.val().view(torch.int32))
     g2.free()
     del o
-    check_spmm_all_rows(ctx, [g], m, W.dense_operand(4, (m.ncols, 64)), "cfg4 spmm N=64")
+    H.check_spmm_all_rows(ctx, [g], m, W.dense_operand(4, (m.ncols, 64)), "cfg4 spmm N=64")
 
 
 def test_cfg5_full(ctx):
@@ -250,7 +204,7 @@ def test_cfg5_full(ctx):
     assert_same_layout(ga, oa, "cfg5 ELL part")
     assert_same_layout(gb, ob, "cfg5 COO part")
     del oa, ob
-    check_spmm_all_rows(ctx, [ga, gb], m, W.dense_operand(5, (m.ncols, 128)), "cfg5 spmm N=128")
+    H.check_spmm_all_rows(ctx, [ga, gb], m, W.dense_operand(5, (m.ncols, 128)), "cfg5 spmm N=128")
     # SpMV over the same hybrid (the extra data point the benchmark times), every row
     check_spmv(ctx, [ga, gb], m, W.dense_operand(5, m.ncols), "cfg5 hybrid spmv")
 
