@@ -62,7 +62,9 @@ class Expr:
     div   : (c0*d0 + c1*d1 + c) / factor       (floor)
     mod   : (c0*d0 + c1*d1 + c) % factor       (non-negative)
     enum  : indirect level: rank of the entry inside its group (group key = the affine
-            part, e.g. d0) when the group is traversed by ascending `traverse` dim
+            part / factor, e.g. d0, or d0/bh for blocked ELL) when the group is traversed by
+            ascending `traverse` dim / traverse_factor; entries that agree in that key share
+            a rank (the blocks of a block row are numbered, not their entries)
     sched : indirect level: the partition (0..factor-1) that the entry's group (key = the
             affine part, e.g. d0) is scheduled to: groups ordered by size, largest first
             (sum + reorder queries), then dealt to `factor` partitions (schedule query)
@@ -73,6 +75,7 @@ class Expr:
     c: int = 0
     factor: int = 1
     traverse: int = 1  # for ENUM: logical dim that orders the group (1 = d1)
+    traverse_factor: int = 1  # for ENUM: the group is traversed by (traverse dim) / traverse_factor
 
 
 def d0() -> Expr: return Expr(AFFINE, 1, 0)
@@ -110,6 +113,14 @@ def BDIA(b: int) -> FormatDesc:
     return FormatDesc((div(0, b), diag(), mod(0, b)), (1, 1), (0,))
 def ELL(width: int = 0) -> FormatDesc:
     return FormatDesc((enum_by_row(), d0(), d1()), (0, 0), (0,), ell_width=width)
+def BELL(bh: int, bw: Optional[int] = None, width: int = 0) -> FormatDesc:
+    """Blocked ELL (the BELL of Section 7.2.2; its encoding sits in a figure that is not available, so this is a
+    reading): ELL's map with rows and columns replaced by block rows and block columns, and the two in-block
+    indices below -- (indirect(d1/bw), d0/bh, d1/bw, d0%bh, d1%bw), merge(0), trim(0,0).  The indirect level
+    numbers the blocks of a block row by ascending block column."""
+    bw = bh if bw is None else bw
+    return FormatDesc((Expr(ENUM, 1, 0, 0, bh, traverse=1, traverse_factor=bw), div(0, bh), div(1, bw), mod(0, bh), mod(1, bw)),
+                      (0, 0), (0,), ell_width=width)
 def CISR_PLUS(n: int) -> FormatDesc:
     """Section 7.2.4: (indirect(d0), d0, d1), merge(0,1), trim(1,2), n partitions."""
     return FormatDesc((sched_rows(n), d0(), d1()), (1, 2), (0, 1))
@@ -153,17 +164,23 @@ def _affine_range(e: Expr, nrows: int, ncols: int) -> Tuple[int, int]:
 
 def _group_rank(group: np.ndarray, order_key: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     """enum query: rank of every entry inside its group when the group is traversed by
-    ascending order_key; also returns the group sizes aligned with the entries."""
+    ascending order_key, entries with equal order_key sharing a rank (with unique (group, order_key)
+    pairs, as in ELL, that is the position in the group); also returns, aligned with the entries,
+    the number of distinct order_key values of their group."""
     n = group.shape[0]
     order = np.lexsort((order_key, group))
-    g = group[order]
-    starts = np.flatnonzero(np.concatenate(([True], g[1:] != g[:-1]))) if n else np.empty(0, np.int64)
-    lens = np.diff(np.concatenate((starts, [n])))
-    rank_sorted = np.arange(n, dtype=np.int64) - np.repeat(starts, lens)
+    g, k = group[order], order_key[order]
+    new_group = np.concatenate(([True], g[1:] != g[:-1])) if n else np.empty(0, bool)
+    new_key = (new_group | np.concatenate(([True], k[1:] != k[:-1]))) if n else np.empty(0, bool)
+    distinct_before = np.cumsum(new_key) - 1                       # running count of distinct (group, key) pairs
+    group_start = np.flatnonzero(new_group)
+    lens = np.diff(np.concatenate((group_start, [n])))
+    rank_sorted = distinct_before - np.repeat(distinct_before[group_start], lens) if n else np.empty(0, np.int64)
+    size_sorted = np.repeat(np.add.reduceat(new_key.astype(np.int64), group_start), lens) if n else np.empty(0, np.int64)
     rank = np.empty(n, dtype=np.int64)
     rank[order] = rank_sorted
     size = np.empty(n, dtype=np.int64)
-    size[order] = np.repeat(lens, lens)
+    size[order] = size_sorted
     return rank, size
 
 
@@ -197,7 +214,8 @@ def eval_index_map(desc: FormatDesc, nrows: int, ncols: int, row: np.ndarray, co
         elif e.kind == MOD:
             out.append(np.mod(a, e.factor))
         elif e.kind == ENUM:
-            rank, _ = _group_rank(a, c if e.traverse == 1 else r)
+            rank, _ = _group_rank(np.floor_divide(a, e.factor),
+                                  np.floor_divide(c if e.traverse == 1 else r, e.traverse_factor))
             out.append(rank)
         elif e.kind == SCHED:
             out.append(_scheduled_partition(a, e.factor))
@@ -231,14 +249,17 @@ def infer_level_kinds(desc: FormatDesc) -> List[str]:
     kinds = []
     S, E = desc.trim if desc.trim is not None else (1, 0)
     enum_traverse = None
+    enum_factor = 1
     deepest_merge = max(desc.merge) if desc.merge else -1   # merge(L) fuses whole paths root..L
     for L, e in enumerate(desc.levels):
         if e.kind == ENUM:
             kinds.append("dense")  # slots 0..K-1 are contiguous from 0: a size, not an idx
-            enum_traverse = e.traverse
+            enum_traverse, enum_factor = e.traverse, e.traverse_factor
             continue
-        is_traversed_dim = (enum_traverse is not None and e.kind == AFFINE and e.c == 0 and
-                            (e.c0, e.c1) == ((0, 1) if enum_traverse == 1 else (1, 0)))
+        # the level that holds the key the groups were traversed by: d1 (ELL) or d1/bw (blocked ELL)
+        is_traversed_dim = (enum_traverse is not None and e.c == 0 and
+                            (e.c0, e.c1) == ((0, 1) if enum_traverse == 1 else (1, 0)) and
+                            ((e.kind == AFFINE and enum_factor == 1) or (e.kind == DIV and e.factor == enum_factor)))
         if is_traversed_dim:
             kinds.append("payload")
         elif S <= L <= E:

@@ -194,3 +194,86 @@ def _last_write_wins(nr, r, c, v, X):
 def test_spmm_coo_pin_catches(name):
     with pytest.raises(AssertionError):
         pin_spmm_coo(SPMM_MUTANTS[name])
+
+
+# ------------------------------------------------------------------ blocked ELL (BELL), by hand and by plain loops
+# Matrix A with 2 x 2 blocks.  Block rows: 0 = rows 0-1 holds block column 0 {(0,0)=1, (1,1)=2}; 1 = rows 2-3 holds
+# block columns 0 {(2,1)=3} and 1 {(2,2)=4, (2,3)=5}; 2 = rows 4-5 holds block column 1 {(4,3)=6}.  The indirect level
+# numbers the blocks of a block row by ascending block column, so K = 2 slots; levels (slot, block row) are sizes 2 and
+# 3, the block-column level holds one index per (slot, block row), slot-major, -1 where a block row has no such block;
+# values node-major, row-major inside a block (Section 5.1 and the value access of Figure 9).
+BELL_EXAMPLE = dict(K=2, nbr=3, bcol=[0, 0, 1, -1, 1, -1],
+                    val=[1, 0, 0, 2,  0, 3, 0, 0,  0, 6, 0, 0,  0, 0, 0, 0,  4, 5, 0, 0,  0, 0, 0, 0])
+
+
+def pin_bell_example(convert, example_A):
+    r = np.array(example_A["d0"], np.int32); c = np.array(example_A["d1"], np.int32)
+    v = np.array(example_A["val"], np.float32)
+    for seed in range(3):
+        p = np.random.default_rng(seed).permutation(r.size)
+        f = convert(5, 4, r[p], c[p], v[p], O.BELL(2))
+        assert [l.kind for l in f.levels] == ["dense", "dense", "payload", "dense", "dense"]
+        assert [f.levels[L].size for L in (0, 1, 3, 4)] == [BELL_EXAMPLE["K"], BELL_EXAMPLE["nbr"], 2, 2]
+        assert f.levels[2].idx.tolist() == BELL_EXAMPLE["bcol"] and f.levels[2].ptr is None
+        assert f.val.tolist() == BELL_EXAMPLE["val"]
+
+
+def test_bell_example_by_hand(example_A):
+    pin_bell_example(O.convert, example_A)
+    r = np.array(example_A["d0"], np.int32); c = np.array(example_A["d1"], np.int32)
+    v = np.array(example_A["val"], np.float32)
+    f = O.convert(5, 4, r, c, v, O.BELL(2))
+    A = np.zeros((5, 4)); A[r, c] = v
+    assert np.array_equal(O.to_dense(f), A)
+    assert O.spmv(f, np.array([1, 10, 100, 1000.0])).tolist() == [1, 20, 5430, 0, 6000]
+    rr, cc, vv = O.to_coo(f)
+    assert (rr.tolist(), cc.tolist(), vv.tolist()) == (example_A["d0"], example_A["d1"], example_A["val"])
+    assert O.convert(5, 4, r, c, v, O.BELL(2, width=3)).levels[0].size == 3      # a fixed width pads further
+    with pytest.raises(O.OracleError):
+        O.convert(5, 4, r, c, v, O.BELL(2, width=1))                             # block row 1 holds two blocks
+
+
+def _bell_slab_major_swapped(f):   # block-row-major instead of slot-major
+    K, nbr = f.levels[0].size, f.levels[1].size
+    f.levels[2].idx = f.levels[2].idx.reshape(K, nbr).T.reshape(-1).copy()
+def _bell_rank_per_entry(f):       # slots numbered by entries instead of blocks: K grows to the longest row's entries
+    f.levels[0].size = 3
+def _bell_pad_zero(f): f.levels[2].idx = np.where(f.levels[2].idx < 0, 0, f.levels[2].idx)
+def _bell_block_transposed(f): f.val = f.val.reshape(-1, 2, 2).transpose(0, 2, 1).reshape(-1).copy()
+
+
+BELL_MUTANTS = {"block-row-major slab": _bell_slab_major_swapped, "one slot per entry": _bell_rank_per_entry,
+                "pad block column 0": _bell_pad_zero, "blocks stored column-major": _bell_block_transposed}
+
+
+@pytest.mark.parametrize("name", sorted(BELL_MUTANTS))
+def test_bell_pin_catches(name, example_A):
+    with pytest.raises(AssertionError):
+        pin_bell_example(_mutated_convert(BELL_MUTANTS[name]), example_A)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_bell_brute_force(seed):
+    rng = np.random.default_rng(100 + seed)
+    nr, nc = int(rng.integers(1, 30)), int(rng.integers(1, 30))
+    bh, bw = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+    r, c, v = random_coo(rng, nr, nc, int(rng.integers(0, nr * nc // 2 + 1)))
+    f = O.convert(nr, nc, r, c, v, O.BELL(bh, bw))
+    nbr = -(-nr // bh)
+    blocks = [sorted({int(cc) // bw for rr, cc in zip(r, c) if int(rr) // bh == br}) for br in range(nbr)]
+    K = max((len(b) for b in blocks), default=0)
+    assert [f.levels[L].size for L in (0, 1, 3, 4)] == [K, nbr, bh, bw]
+    bcol = [[-1] * nbr for _ in range(K)]
+    val = np.zeros((K, nbr, bh, bw), np.float32)
+    for br in range(nbr):
+        for k, bc in enumerate(blocks[br]):
+            bcol[k][br] = bc
+    for rr, cc, vv in zip(r, c, v):
+        br, bc = int(rr) // bh, int(cc) // bw
+        val[blocks[br].index(bc), br, int(rr) % bh, int(cc) % bw] = vv
+    assert f.levels[2].idx.tolist() == [x for row in bcol for x in row]
+    assert np.array_equal(f.val, val.reshape(-1))
+    A = np.zeros((nr, nc)); A[r, c] = v
+    assert np.array_equal(O.to_dense(f), A)
+    x = rng.uniform(-1, 1, nc)
+    np.testing.assert_allclose(O.spmv(f, x), A @ x, atol=1e-12)
