@@ -433,6 +433,17 @@ def other_workloads(B, W, torch, ctx, up, K, Wm, with_oracle, op_frac):
             # whole-array digit passes only (blocked tuples finish inside LDS by default); COO -> ELL of Table 5 both ways
             variant("config4_bcsr_whole_array_passes_only",
                     lambda: [B.us_convert(ctx, m.nrows, m.ncols, w.r, w.c, w.v, P(B.US_F_BCSR, 4, 4))], None, 0, finish=False)
+            # the same matrix as blocked ELL (4 x 4 blocks, 24 slots per block row): conversion and the MFMA product
+            bell = [B.us_convert(ctx, m.nrows, m.ncols, w.r, w.c, w.v, P(B.US_F_BELL, 4, 4))]
+            ms, sd = timed(torch, lambda: B.us_convert(ctx, m.nrows, m.ncols, w.r, w.c, w.v, P(B.US_F_BELL, 4, 4)).free(), K, Wm)
+            msq = timed_stream(torch, lambda: w.spmm(bell), 2 * K, Wm)
+            res["config4_bell_spmm64"] = {
+                "nnz": m.nnz, "slots_per_block_row": int(bell[0].size(0)),
+                "convert": {"ms": round(ms, 4), "ms_std": round(sd, 4), "mnnz_s": round(m.nnz / ms / 1e3, 1),
+                            "op_frac": frac(w.conv_bytes(bell), ms)},
+                "spmm": {"N": w.N, "ms": round(msq, 4), "gflop_s": round(2.0 * m.nnz * w.N / msq / 1e6, 1),
+                         "op_frac": frac(w.spmm_bytes(bell), msq)}}
+            bell[0].free()
             variant("config4_coo_to_ell", lambda: [B.us_convert(ctx, m.nrows, m.ncols, w.r, w.c, w.v, P(B.US_F_ELL))], None, 0)
             variant("config4_coo_to_ell_lds_finish",
                     lambda: [B.us_convert(ctx, m.nrows, m.ncols, w.r, w.c, w.v, P(B.US_F_ELL))], None, 0, finish=True)
@@ -501,15 +512,22 @@ def label_propagation(B, W, torch, ctx, up, iters=20, N=1000):
             for k, p in enumerate(parts):
                 B.us_spmm(ctx, p, src, dst, accumulate=k > 0)
 
+    # blocked ELL (4 x 4 blocks) + COO, the hybrid of the paper's case study: blocks holding at least 3 entries
+    pb = B.make_predicate([B.expr(B.US_E_DIV, 1, 0, 0, 4), B.expr(B.US_E_DIV, 0, 1, 0, 4)], B.US_P_SUM_GE_ABS, abs_=3)
+    BELL = B.us_desc_preset(B.US_F_BELL, 4, 4)
     out = {"nrows": m.nrows, "nnz": m.nnz, "N": N, "iterations": iters}
     for name, conv in (("csr", lambda: [B.us_convert(ctx, m.nrows, m.ncols, r, c, v, CSR)]),
-                       ("ell_coo", lambda: list(B.us_decompose(ctx, m.nrows, m.ncols, r, c, v, ELL, COO, pr)))):
+                       ("ell_coo", lambda: list(B.us_decompose(ctx, m.nrows, m.ncols, r, c, v, ELL, COO, pr))),
+                       ("bell_coo", lambda: list(B.us_decompose(ctx, m.nrows, m.ncols, r, c, v, BELL, COO, pb)))):
         ms_conv, _ = timed(torch, lambda: [p.free() for p in conv()], 5, 2)
         parts = conv()
         ms_loop = timed_stream(torch, lambda: loop(parts), 3, 1)
         out[name] = {"preprocess_ms": round(ms_conv, 3), "kernels_ms": round(ms_loop, 3),
                      "total_ms": round(ms_conv + ms_loop, 3),
-                     "gflop_s": round(2.0 * m.nnz * N * iters / ms_loop / 1e6, 1)}
+                     "gflop_s": round(2.0 * m.nnz * N * iters / ms_loop / 1e6, 1),
+                     "entries_per_part": [int(p.nnz) for p in parts]}
+        if name == "bell_coo":
+            out[name]["bell_slots_per_block_row"] = int(parts[0].size(0))
         for p in parts:
             p.free()
     return out

@@ -87,14 +87,16 @@ typedef struct us_coo {
 
 /* One destination expression of an index map (Figure 5a): e = c0*d0 + c1*d1 + c, optionally
  * followed by "/ factor" (floor) or "% factor", or the indirect function of ELL (Figure 7:
- * sum + enum grouped by the affine part, traversed by the other dimension), or the indirect function
- * of CISR-plus (Section 7.2.4: sum + reorder + schedule of the groups of the affine part into `factor`
- * partitions). */
+ * sum + enum grouped by the affine part / factor, traversed by the other dimension / factor2: factor = factor2 = 1
+ * numbers the entries of a row, ELL; factor = bh, factor2 = bw numbers the blocks of a block row, blocked ELL), or
+ * the indirect function of CISR-plus (Section 7.2.4: sum + reorder + schedule of the groups of the affine part into
+ * `factor` partitions). */
 enum { US_E_AFFINE = 0, US_E_DIV = 1, US_E_MOD = 2, US_E_INDIRECT_ENUM = 3, US_E_INDIRECT_SCHEDULE = 4 };
 typedef struct us_expr {
   int32_t kind;
   int32_t c0, c1, c;
   int32_t factor;
+  int32_t factor2; /* US_E_INDIRECT_ENUM only (0 is read as 1) */
 } us_expr;
 
 /* Format encoding: index map (major level first) + trim(S,E) + merge(L...), Section 4.1.
@@ -104,6 +106,11 @@ typedef struct us_expr {
  *   DIA  (d1-d0,d0) merge(0) trim(0,0)  DIA variant (d1-d0,d1)
  *   BCSR (d0/bh,d1/bw,d0%bh,d1%bw) merge(0,1) trim(1,1), 1 <= bh,bw <= 16
  *   ELL  (indirect(d1),d0,d1) merge(0) trim(0,0)
+ *   BELL (indirect(d1/bw),d0/bh,d1/bw,d0%bh,d1%bw) merge(0) trim(0,0), 1 <= bh,bw <= 16: blocked ELL, the BELL of
+ *        Section 7.2.2 (its encoding is in a figure that is not available: this library's reading).  The indirect
+ *        level numbers the blocks of a block row by ascending block column: a size K (the most blocks a block row
+ *        holds, or ell_width if > 0), a size ceil(nrows/bh), one block column per (slot, block row) (slot-major,
+ *        -1 = no block), then the dense bh x bw inner levels: val[((k*nbr + br)*bh + r)*bw + c]
  *   BDIA (d0/b,d1-d0,d0%b) merge(0) trim(1,1), 1 <= b <= 16 (the blocked DIA of Figure 3c)
  *   CSB  (d0/bh,d1/bw,d0%bh,d1%bw) merge(1) trim(2,3), 1 <= bh,bw <= 65536 and fewer than 2^31 blocks:
  *        a dense grid of blocks (two sizes), one ptr over the blocks, (d0%bh, d1%bw) per entry
@@ -114,15 +121,15 @@ typedef struct us_expr {
  *        indices ascending inside a partition) and a column level (ptr over the stored rows, column indices) */
 typedef struct us_format_desc {
   int32_t nlevels;
-  us_expr level[4];
+  us_expr level[5];
   int32_t trim_s, trim_e; /* -1,-1 = no trim */
   uint32_t merge_mask;    /* bit L set = merge(L) */
-  int64_t ell_width;      /* ELL only: 0 = longest row, >0 = fixed number of slots */
+  int64_t ell_width;      /* ELL, BELL: 0 = longest (block) row, >0 = fixed number of slots */
 } us_format_desc;
 
-enum { US_F_COO = 0, US_F_CSR, US_F_DCSR, US_F_CSC, US_F_DCSC, US_F_DIA, US_F_DIA_VARIANT, US_F_BCSR, US_F_ELL, US_F_BDIA, US_F_CSB, US_F_CISR_PLUS };
+enum { US_F_COO = 0, US_F_CSR, US_F_DCSR, US_F_CSC, US_F_DCSC, US_F_DIA, US_F_DIA_VARIANT, US_F_BCSR, US_F_ELL, US_F_BDIA, US_F_CSB, US_F_CISR_PLUS, US_F_BELL };
 /* Fill *out with the encoding of Figure 7 (Figure 3c for BDIA) for `format`; b0,b1 = block
- * height,width (BCSR, CSB), b0 = block height (BDIA), b0 = fixed width (ELL, 0 = longest row) or b0 = number of
+ * height,width (BCSR, CSB, BELL), b0 = block height (BDIA), b0 = fixed width (ELL, 0 = longest row) or b0 = number of
  * partitions (CISR-plus).  host pointers. */
 us_status us_desc_preset(int32_t format, int64_t b0, int64_t b1, us_format_desc *out);
 
@@ -138,7 +145,7 @@ us_status us_desc_preset(int32_t format, int64_t b0, int64_t b1, us_format_desc 
  * group maps supported: (d1-d0), (d0), (d1) for the sum predicates; (d0) for the rank ones;
  * (d0/b, d1-d0) with US_P_SUM_GE_ABS (the #sum query of Figure 3c) and (d0/bh, d1/bw) with US_P_SUM_GE_ABS
  * (entries per block, the threshold of the BELL/COO case study of Section 7.2.2), 1 <= b, bh, bw <= 16;
- * a part A stored as BDIA(b) / BCSR(bh,bw) then needs no second sort. */
+ * a part A stored as BDIA(b) / BCSR(bh,bw) / BELL(bh,bw) then needs no second sort. */
 enum { US_P_SUM_GE_ABS = 0, US_P_SUM_GE_FRAC_OF_CAPACITY = 1, US_P_RANK_LT_ABS = 2, US_P_RANK_LT_PERCENTILE = 3 };
 typedef struct us_predicate {
   us_expr group[2];
@@ -172,7 +179,7 @@ us_status us_decompose(const us_ctx *ctx, const us_coo *coo, const us_format_des
 /* y = A x (accumulate = 0) or y += A x (accumulate != 0; the generic op of Figure 3c reads Y).
  * x: ncols floats, y: nrows floats, both device.  For a hybrid call it on part A, then on
  * part B with accumulate = 1.
- * Row-grouped layouts (COO, CSR, DCSR, CISR-plus, DIA and its variant, BCSR, BDIA, ELL) add in a fixed order: two
+ * Row-grouped layouts (COO, CSR, DCSR, CISR-plus, DIA and its variant, BCSR, BDIA, ELL, BELL) add in a fixed order: two
  * calls give the same bits.  Layouts whose leaves are not grouped by output row (CSC, DCSC, column-major
  * COO, CSB) scatter with fp32 atomics, so the last bits may differ from call to call; this holds for
  * us_spmm as well. */

@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "US_OK", -1: "US_ERR_NULL", -2: "US_ERR_SHAPE", -3: "US_ERR_I
                 -7: "US_ERR_OVERFLOW", -8: "US_ERR_HIP", -9: "US_ERR_FORMAT_MISMATCH", -10: "US_ERR_SCRATCH_LIMIT"}
 US_E_AFFINE, US_E_DIV, US_E_MOD, US_E_INDIRECT_ENUM, US_E_INDIRECT_SCHEDULE = 0, 1, 2, 3, 4
 (US_F_COO, US_F_CSR, US_F_DCSR, US_F_CSC, US_F_DCSC, US_F_DIA, US_F_DIA_VARIANT, US_F_BCSR, US_F_ELL,
- US_F_BDIA, US_F_CSB, US_F_CISR_PLUS) = range(12)
+ US_F_BDIA, US_F_CSB, US_F_CISR_PLUS, US_F_BELL) = range(13)
 US_P_SUM_GE_ABS, US_P_SUM_GE_FRAC_OF_CAPACITY, US_P_RANK_LT_ABS, US_P_RANK_LT_PERCENTILE = range(4)
 US_A_SIZE, US_A_PTR, US_A_IDX, US_A_VAL = range(4)
 US_T_NONE, US_T_INT32, US_T_FLOAT32 = range(3)
@@ -57,11 +57,11 @@ class us_coo(C.Structure):
 
 class us_expr(C.Structure):
     _fields_ = [("kind", C.c_int32), ("c0", C.c_int32), ("c1", C.c_int32), ("c", C.c_int32),
-                ("factor", C.c_int32)]
+                ("factor", C.c_int32), ("factor2", C.c_int32)]
 
 
 class us_format_desc(C.Structure):
-    _fields_ = [("nlevels", C.c_int32), ("level", us_expr * 4), ("trim_s", C.c_int32),
+    _fields_ = [("nlevels", C.c_int32), ("level", us_expr * 5), ("trim_s", C.c_int32),
                 ("trim_e", C.c_int32), ("merge_mask", C.c_uint32), ("ell_width", C.c_int64)]
 
 
@@ -229,8 +229,8 @@ def us_desc_preset(fmt: int, b0: int = 0, b1: int = 0) -> us_format_desc:
     return d
 
 
-def expr(kind: int, c0: int = 0, c1: int = 0, c: int = 0, factor: int = 1) -> us_expr:
-    return us_expr(kind, c0, c1, c, factor)
+def expr(kind: int, c0: int = 0, c1: int = 0, c: int = 0, factor: int = 1, factor2: int = 1) -> us_expr:
+    return us_expr(kind, c0, c1, c, factor, factor2)
 
 
 def make_desc(levels, trim, merge, ell_width: int = 0) -> us_format_desc:

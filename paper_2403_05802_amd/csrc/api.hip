@@ -24,7 +24,7 @@ const char *us_status_str(us_status s) {
 
 static us_expr mk(int kind, int c0, int c1, int factor) {
   us_expr e{};
-  e.kind = kind; e.c0 = c0; e.c1 = c1; e.c = 0; e.factor = factor;
+  e.kind = kind; e.c0 = c0; e.c1 = c1; e.c = 0; e.factor = factor; e.factor2 = 1;
   return e;
 }
 
@@ -66,6 +66,14 @@ us_status us_desc_preset(int32_t format, int64_t b0, int64_t b1, us_format_desc 
       d.nlevels = 3;
       d.level[0] = mk(US_E_INDIRECT_ENUM, 1, 0, 1); d.level[1] = r; d.level[2] = c;
       d.trim_s = 0; d.trim_e = 0; d.merge_mask = 1; d.ell_width = b0;
+      break;
+    case US_F_BELL:
+      if (b0 < 1 || b1 < 1 || b0 > 16 || b1 > 16) return US_ERR_UNSUPPORTED_DESC;
+      d.nlevels = 5;
+      d.level[0] = mk(US_E_INDIRECT_ENUM, 1, 0, (int)b0); d.level[0].factor2 = (int)b1;
+      d.level[1] = mk(US_E_DIV, 1, 0, (int)b0); d.level[2] = mk(US_E_DIV, 0, 1, (int)b1);
+      d.level[3] = mk(US_E_MOD, 1, 0, (int)b0); d.level[4] = mk(US_E_MOD, 0, 1, (int)b1);
+      d.trim_s = 0; d.trim_e = 0; d.merge_mask = 1; d.ell_width = 0;
       break;
     case US_F_CISR_PLUS:
       if (b0 < 1 || b0 > 65536) return US_ERR_UNSUPPORTED_DESC;

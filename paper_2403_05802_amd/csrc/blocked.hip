@@ -82,6 +82,22 @@ __global__ __launch_bounds__(BE_T) void bcsr_emit_kernel(const uint64_t *key, co
   }
 }
 
+// Blocked ELL from the block lists of BCSR: block b of block row br sits in slot k = b - ptr[br] (the enum query over
+// the blocks of a block row, ascending block column); its block column goes to ecol[k * nbr + br] and its values to
+// the slot-major slab.  A thread per value; slab and ecol start out as padding (0 and -1).
+__global__ __launch_bounds__(256) void bell_fill_kernel(const int32_t *ptr, const int32_t *blk_row, const int32_t *blk_col,
+                                                       const float *bval, int64_t nvals, int bsz, int64_t nbr, int64_t K,
+                                                       int32_t *ecol, float *eval, Flags *flags) {
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (e >= nvals) return;
+  const int64_t b = e / bsz;
+  const int in = (int)(e - b * bsz);
+  const int64_t br = blk_row[b], k = b - ptr[br];
+  if (k >= K) { flags->ell_overflow = 1; return; }   // a block row with more blocks than a fixed width allows
+  if (in == 0) ecol[k * nbr + br] = blk_col[b];
+  eval[(k * nbr + br) * bsz + in] = bval[e];
+}
+
 // Key layout of the two blocked families: BCSR (d0/bh, d1/bw, d0%bh, d1%bw) and BDIA
 // (d0/bh, d1-d0 biased by nrows-1, d0%bh).
 KeySpec blocked_keyspec(const Plan &plan, int64_t nrows, int64_t ncols) {
@@ -115,6 +131,46 @@ us_status emit_blocked(Env &env, const Plan &plan, const us_format_desc &desc, i
   const int64_t nblk = h.scalar[0], bsz = plan.bh * plan.bw;
   if (nblk * bsz >= (1ll << 31)) return US_ERR_OVERFLOW;
   const bool bdia = plan.pattern == P_BDIA;
+  if (plan.pattern == P_BELL) {
+    // the block lists of BCSR in temporaries, the most blocks a block row holds, then the slot-major slabs
+    int32_t *ptr = env.temp<int32_t>(nbr + 1), *bidx = env.temp<int32_t>(nblk), *blk_row = env.temp<int32_t>(nblk);
+    float *bval = env.temp<float>(nblk * bsz);
+    if (!env.ok()) return env.status;
+    if (nblk * bsz != n) fill_u32(env, (uint32_t *)bval, nblk * bsz, 0u);
+    if (n > 0)
+      US_LAUNCH(env, "bcsr_emit", 12.0 * n + 4.0 * n, bcsr_emit_kernel, nb, BE_T, skey, sval, n, ks, (int32_t)0,
+                (const uint32_t *)partial, blk_row, bidx, bval);
+    lower_bound_ptr(env, blk_row, nblk, nbr, ptr);
+    int64_t K = plan.ell_width;
+    if (K == 0) {
+      fill_u32(env, (uint32_t *)&flags->scalar[1], 1, 0u);
+      max_group_len(env, ptr, nbr, &flags->scalar[1]);
+      if (!read_flags(env, flags, &h)) return env.status;
+      K = h.scalar[1];
+    }
+    if (K * nbr * bsz >= (1ll << 31)) return US_ERR_OVERFLOW;
+    us_formatted *f = new us_formatted();
+    f->desc = desc; f->pattern = P_BELL;
+    f->nrows = nrows; f->ncols = ncols; f->nnz = n;
+    f->nlevels = 5;
+    f->level[0].size = K; f->level[1].size = nbr; f->level[3].size = plan.bh; f->level[4].size = plan.bw;
+    const int64_t nslots = K * nbr;
+    if (env.one_result) env.reserve_out(Env::granule(4 * (size_t)nslots) + Env::granule(4 * (size_t)(nslots * bsz)));
+    f->level[2].idx = env.owned<int32_t>(nslots); f->level[2].nidx = nslots;
+    f->val = env.owned<float>(nslots * bsz); f->nval = nslots * bsz;
+    f->nmajor = K; f->bh = plan.bh; f->bw = plan.bw; f->nblk = nbr;
+    if (!env.ok()) { free_formatted(env, f); return env.status; }
+    fill_u32(env, (uint32_t *)f->level[2].idx, nslots, 0xFFFFFFFFu);
+    fill_u32(env, (uint32_t *)f->val, nslots * bsz, 0u);
+    if (nblk > 0)
+      US_LAUNCH(env, "bell_fill", 8.0 * nblk * bsz + 12.0 * nblk, bell_fill_kernel, ceil_div<int64_t>(nblk * bsz, 256), 256,
+                (const int32_t *)ptr, (const int32_t *)blk_row, (const int32_t *)bidx, (const float *)bval, nblk * bsz,
+                (int)bsz, nbr, K, f->level[2].idx, f->val, flags);
+    if (!read_flags(env, flags, &h)) { free_formatted(env, f); return env.status; }
+    if (flag_status(h) != US_OK) { free_formatted(env, f); return flag_status(h); }
+    *out = f;
+    return US_OK;
+  }
   us_formatted *f = new us_formatted();
   f->desc = desc; f->pattern = plan.pattern;
   f->nrows = nrows; f->ncols = ncols; f->nnz = n;

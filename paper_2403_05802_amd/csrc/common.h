@@ -132,7 +132,7 @@ struct LaunchScope {
   } while (0)
 
 // ------------------------------------------------------------------ formatted tensor
-enum Pattern { P_COO = 0, P_CSR, P_DCSR, P_DIA, P_BCSR, P_ELL, P_BDIA, P_CSB, P_CISR };
+enum Pattern { P_COO = 0, P_CSR, P_DCSR, P_DIA, P_BCSR, P_ELL, P_BDIA, P_CSB, P_CISR, P_BELL };
 
 struct LevelStore {
   int64_t size = -1;      // extent of a dense level, -1 if none
@@ -148,12 +148,13 @@ struct us_formatted {
   bool swapped = false;  // map (d1,d0): CSC / DCSC; DIA: slab indexed by d1 (DIA variant)
   int64_t nrows = 0, ncols = 0, nnz = 0;
   int nlevels = 0;
-  us::LevelStore level[4];
+  us::LevelStore level[5];
   float *val = nullptr; int64_t nval = 0;
   // derived sizes
   int64_t nmajor = 0;   // CSR: rows (cols if swapped); DCSR, CISR-plus: stored rows; DIA: ndiag; BCSR/BDIA: block rows; ELL: K
   int64_t bh = 1, bw = 1, nblk = 0;   // BDIA: bh = block height, bw = 1, nblk = (block row, diagonal) nodes;
-                                      // CSB: nblk = nmajor = blocks of the dense grid, level[1].size = blocks per block row
+                                      // CSB: nblk = nmajor = blocks of the dense grid, level[1].size = blocks per block row;
+                                      // BELL: nmajor = K slots, nblk = block rows
   // CSR / DCSR / CISR-plus (and CSC / DCSC by columns): where every tile starts on the merge path of row ends and non-zeros
   // (rows consumed before step t * tile), computed once at conversion
   int32_t *mp_split = nullptr; int64_t mp_tiles = 0;

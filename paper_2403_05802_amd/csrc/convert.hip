@@ -58,10 +58,21 @@ bool match_desc(const us_format_desc &d, Plan *p) {
     }
     return false;
   }
+  if (d.nlevels == 5) {
+    const us_expr &e = d.level[0];
+    int64_t f1, f2, f3, f4;
+    if (e.kind == US_E_INDIRECT_ENUM && e.c0 == 1 && e.c1 == 0 && e.c == 0 && tile(d.level[1], US_E_DIV, 0, &f1) &&
+        tile(d.level[2], US_E_DIV, 1, &f2) && tile(d.level[3], US_E_MOD, 0, &f3) && tile(d.level[4], US_E_MOD, 1, &f4) &&
+        f1 == f3 && f2 == f4 && e.factor == f1 && e.factor2 == f2 && S == 0 && E == 0 && m == 1 && d.ell_width >= 0) {
+      p->pattern = P_BELL; p->bh = f1; p->bw = f2; p->ell_width = d.ell_width;
+      return true;
+    }
+    return false;
+  }
   if (d.nlevels == 3) {
     const us_expr &e = d.level[0];
-    if (e.kind == US_E_INDIRECT_ENUM && e.c0 == 1 && e.c1 == 0 && e.c == 0 && aff(d.level[1], 1, 0) &&
-        aff(d.level[2], 0, 1) && S == 0 && E == 0 && m == 1 && d.ell_width >= 0) {
+    if (e.kind == US_E_INDIRECT_ENUM && e.c0 == 1 && e.c1 == 0 && e.c == 0 && e.factor <= 1 && e.factor2 <= 1 &&
+        aff(d.level[1], 1, 0) && aff(d.level[2], 0, 1) && S == 0 && E == 0 && m == 1 && d.ell_width >= 0) {
       p->pattern = P_ELL; p->ell_width = d.ell_width;
       return true;
     }
@@ -282,7 +293,7 @@ void free_formatted(Env &env, us_formatted *f) {
   auto drop = [&](void *p) {   // arrays inside the result's own block go with the block
     if (p && !(s0 && (const char *)p >= s0 && (const char *)p < s1)) env.free_raw(p);
   };
-  for (int l = 0; l < 4; ++l) {
+  for (int l = 0; l < 5; ++l) {
     drop(f->level[l].ptr);
     drop(f->level[l].idx);
   }
@@ -516,14 +527,14 @@ us_status convert_with_plan(Env &env, const us_coo &coo, const Plan &plan, const
   } else if (plan.pattern == P_DIA) {   // counters, flags, positions and slab indices of the diagonals, scan sums
     const size_t nbins = (size_t)(coo.nrows + coo.ncols);
     env.reserve(4 * Env::granule(4 * nbins) + Env::granule(4 * (nbins / 1024 + 64)) + 8 * Env::granule(256));
-  } else if (plan.pattern == P_BCSR || plan.pattern == P_BDIA) {   // sorted keys and values, block counts per tile
+  } else if (plan.pattern == P_BCSR || plan.pattern == P_BDIA || plan.pattern == P_BELL) {   // sorted keys and values, block counts per tile
     env.reserve(Env::granule(8 * (size_t)n) + Env::granule(4 * (size_t)n) + Env::granule(4 * ((size_t)n / 1024 + 64)) +
                 8 * Env::granule(256));
   }
   Flags *flags = new_flags(env);
   if (!env.ok()) return env.status;
   if (plan.pattern == P_DIA) return convert_dia(env, coo, plan, desc, flags, out);
-  if (plan.pattern == P_BCSR || plan.pattern == P_BDIA) return convert_blocked(env, coo, plan, desc, flags, out);
+  if (plan.pattern == P_BCSR || plan.pattern == P_BDIA || plan.pattern == P_BELL) return convert_blocked(env, coo, plan, desc, flags, out);
   if (plan.pattern == P_CSB) return convert_csb(env, coo, plan, desc, flags, out);
   if (plan.pattern == P_CISR) return convert_cisr(env, coo, plan, desc, flags, out);
   // COO / CSR / DCSR / ELL: sort by (major, minor), then build
@@ -612,6 +623,14 @@ __device__ __forceinline__ bool slot_entry(const SrcView &v, int64_t s, int32_t 
       *r = (int32_t)i; *c = v.idx[s]; *x = val;
       return true;
     }
+    case P_BELL: {   // slot node = (slot, block row); TileUnion: d0 = br*bh + r, d1 = bc*bw + c
+      const int64_t bsz = v.bh * v.bw, node = s / bsz, in = s - node * bsz, ri = in / v.bw, ci = in - ri * v.bw;
+      const int64_t nbr = (v.nrows + v.bh - 1) / v.bh, br = node % nbr, bc = v.idx[node];
+      const int64_t row = br * v.bh + ri, col = bc * v.bw + ci;
+      if (bc < 0 || val == 0.f || row >= v.nrows || col >= v.ncols) return false;
+      *r = (int32_t)row; *c = (int32_t)col; *x = val;
+      return true;
+    }
     default: return false;
   }
   *r = (int32_t)(v.swapped ? b : a); *c = (int32_t)(v.swapped ? a : b); *x = val;
@@ -685,7 +704,8 @@ us_status convert_formatted_impl(Env &env, const us_formatted &src, const us_for
     case P_DIA: v.idx0 = src.level[0].idx; break;
     case P_BCSR:
     case P_BDIA: v.ptr = src.level[1].ptr; v.idx = src.level[1].idx; break;
-    case P_ELL: v.idx = src.level[2].idx; break;
+    case P_ELL:
+    case P_BELL: v.idx = src.level[2].idx; break;
     case P_CSB: v.ptr = src.level[2].ptr; v.idx0 = src.level[2].idx; v.idx = src.level[3].idx; break;
     case P_CISR:   // below the partition level it reads like DCSR: stored rows, ptr over them, columns
       v.pattern = P_DCSR; v.idx0 = src.level[1].idx; v.ptr = src.level[2].ptr; v.idx = src.level[2].idx; break;

@@ -301,7 +301,7 @@ static us_status decompose_blocked(Env &env, const us_coo &coo, const Plan &pa, 
   const KeySpec ks = blocked_keyspec(pg, coo.nrows, coo.ncols);
   const int inner_bits = ks.ih_bits + ks.iw_bits;
   // part A keeps the sorted order when it is stored by the very tuple the groups were cut by
-  const bool direct = pa.pattern == pg.pattern && pa.bh == pg.bh && pa.bw == pg.bw;
+  const bool direct = (pa.pattern == pg.pattern || (pa.pattern == P_BELL && pg.pattern == P_BCSR)) && pa.bh == pg.bh && pa.bw == pg.bw;
   uint64_t *skey = env.temp<uint64_t>(n);
   float *sval = env.temp<float>(n);
   int32_t *keep = env.temp<int32_t>(n), *pos_a = env.temp<int32_t>(n);

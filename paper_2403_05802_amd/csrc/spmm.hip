@@ -106,6 +106,81 @@ __global__ __launch_bounds__(256) void bcsr44_spmm_mfma_kernel(const int32_t *pt
   }
 }
 
+// Blocked ELL with 4x4 blocks on the matrix cores: a wavefront owns one block row and 64 columns of X, as above; the
+// blocks of a block row sit in the slots 0, 1, ... (slot-major slab, nbr blocks apart), so the block column is one
+// scalar load per slot and every lane reads the row of the block that it feeds to the 4x4x1 product (lanes with
+// equal lane % 4 read the same 16 bytes).  Two slots are in flight together: eight gathered rows of X.
+__global__ __launch_bounds__(256) void bell44_spmm_mfma_kernel(const int32_t *ecol, const float *val, int64_t K,
+                                                              int64_t nbr, int64_t per_xcd, int64_t nrows, int64_t ncols,
+                                                              const float *X, int64_t N, int64_t ldx, float *Y,
+                                                              int64_t ldy, int accumulate) {
+  const int lane = lane_id();
+  const int64_t br = xcd_tile(blockIdx.x, per_xcd) * 4 + wave_id();
+  if (br >= nbr) return;
+  const int64_t c = (int64_t)blockIdx.y * 64 + lane;
+  const bool col_ok = c < N;
+  const uint32_t xoff = (uint32_t)(col_ok ? c : N - 1);   // clamped: loads stay in bounds, stores are guarded
+  const uint32_t aoff = (uint32_t)(lane & 3) * 4u;
+  float4v acc = {0.f, 0.f, 0.f, 0.f};
+  for (int64_t k0 = 0; k0 < K; k0 += 2) {
+    int32_t bc[2];
+    float4v av[2];
+    float xv[2][4];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      bc[u] = k0 + u < K ? __builtin_amdgcn_readfirstlane(ecol[(k0 + u) * nbr + br]) : -1;
+      av[u] = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) xv[u][kk] = 0.f;
+      if (bc[u] >= 0) {   // (scalar)
+        av[u] = *reinterpret_cast<const float4v *>(val + ((k0 + u) * nbr + br) * 16 + aoff);
+        const int64_t xr = (int64_t)bc[u] * 4;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+          if (xr + kk < ncols) xv[u][kk] = X[(xr + kk) * ldx + xoff];
+      }
+    }
+    if (bc[0] < 0) break;   // slots fill from the front
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) acc = __builtin_amdgcn_mfma_f32_4x4x1f32(av[u][kk], xv[u][kk], acc, 0, 0, 0);
+  }
+  if (col_ok) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int64_t row = br * 4 + r;
+      if (row < nrows) {
+        float *yp = Y + row * ldy + c;
+        *yp = (accumulate ? *yp : 0.f) + acc[r];
+      }
+    }
+  }
+}
+
+// blocked ELL of any block size: one wavefront per (row, 64 columns), plain FMAs
+__global__ __launch_bounds__(256) void bell_spmm_kernel(const int32_t *ecol, const float *val, int64_t K, int64_t nbr,
+                                                       int bh, int bw, int64_t nrows, int64_t ncols, const float *X,
+                                                       int64_t N, int64_t ldx, float *Y, int64_t ldy, int accumulate) {
+  const int64_t i = (int64_t)blockIdx.x * 4 + wave_id();
+  if (i >= nrows) return;
+  const int64_t c = (int64_t)blockIdx.y * 64 + lane_id();
+  if (c >= N) return;
+  const int64_t br = i / bh;
+  const int ri = (int)(i - br * bh);
+  float s = accumulate ? Y[i * ldy + c] : 0.f;
+  for (int64_t k = 0; k < K; ++k) {
+    const int64_t bc = ecol[k * nbr + br];
+    if (bc < 0) break;
+    const float *v = val + ((k * nbr + br) * bh + ri) * bw;
+    for (int q = 0; q < bw; ++q) {
+      const int64_t j = bc * bw + q;
+      if (j < ncols) s += v[q] * X[j * ldx + c];
+    }
+  }
+  Y[i * ldy + c] = s;
+}
+
 // any block size: one wavefront per (block row, 64 columns), plain FMAs
 __global__ __launch_bounds__(256) void bcsr_spmm_kernel(const int32_t *ptr, const int32_t *idx, const float *val,
                                                        int64_t nbr, int bh, int bw, int64_t nrows, int64_t ncols,
@@ -490,6 +565,24 @@ us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, 
       }
       return env.status;
     }
+    case P_BELL:
+      if (env.ok()) {
+        const double bytes = 4.0 * A.nval + 4.0 * A.level[2].nidx + xy;
+        if (A.bh == 4 && A.bw == 4) {
+          LaunchScope ls(env, "spmm_bell44_mfma", bytes);
+          const int64_t tiles = ceil_div<int64_t>(A.nblk, 4), per_xcd = ceil_div<int64_t>(tiles, 8);
+          hipLaunchKernelGGL(bell44_spmm_mfma_kernel, dim3((unsigned)(per_xcd * 8), (unsigned)ncb), dim3(256), 0, env.stream,
+                             (const int32_t *)A.level[2].idx, (const float *)A.val, A.nmajor, A.nblk, per_xcd, A.nrows,
+                             A.ncols, X, N, ldx, Y, ldy, acc);
+        } else {
+          LaunchScope ls(env, "spmm_bell", bytes);
+          hipLaunchKernelGGL(bell_spmm_kernel, dim3((unsigned)ceil_div<int64_t>(A.nrows, 4), (unsigned)ncb), dim3(256), 0,
+                             env.stream, (const int32_t *)A.level[2].idx, (const float *)A.val, A.nmajor, A.nblk, (int)A.bh,
+                             (int)A.bw, A.nrows, A.ncols, X, N, ldx, Y, ldy, acc);
+        }
+        env.check(hipGetLastError());
+      }
+      return env.status;
     case P_ELL:
       if (env.ok()) {
         LaunchScope ls(env, "spmm_ell", 8.0 * A.nval + xy);

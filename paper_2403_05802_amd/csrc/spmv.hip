@@ -390,6 +390,28 @@ __global__ __launch_bounds__(256) void bdia_spmv_kernel(const int32_t *ptr, cons
   y[i] = s;
 }
 
+// Blocked ELL: a thread per row walks the slots of its block row (they fill from the front); the values of a slot are
+// contiguous over (block row, row in block, column in block), so neighbouring threads read neighbouring runs of bw.
+__global__ __launch_bounds__(256) void bell_spmv_kernel(const int32_t *ecol, const float *val, int64_t K, int64_t nbr,
+                                                       int bh, int bw, int64_t nrows, int64_t ncols, const float *x,
+                                                       float *y, int accumulate) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= nrows) return;
+  const int64_t br = i / bh;
+  const int ri = (int)(i - br * bh);
+  float s = accumulate ? y[i] : 0.f;
+  for (int64_t k = 0; k < K; ++k) {
+    const int64_t bc = ecol[k * nbr + br];
+    if (bc < 0) break;
+    const float *v = val + ((k * nbr + br) * bh + ri) * bw;
+    for (int c = 0; c < bw; ++c) {
+      const int64_t j = bc * bw + c;
+      if (j < ncols) s += v[c] * x[j];
+    }
+  }
+  y[i] = s;
+}
+
 // CSB: one thread per entry; its block (hence its row and column origin) is found in ptr.  Entries of a
 // block row interleave rows, so sums go through fp32 atomics (like the column-major layouts).
 __global__ __launch_bounds__(256) void csb_spmv_atomic_kernel(const int32_t *ptr, const int32_t *in_row,
@@ -476,6 +498,11 @@ us_status spmv_impl(Env &env, const us_formatted &A, const float *x, float *y, b
       US_LAUNCH(env, "spmv_bcsr", 4.0 * A.nval + 4.0 * A.nblk + 8.0 * A.nrows, bcsr_spmv_kernel,
                 ceil_div<int64_t>(A.nmajor, 4), 256, (const int32_t *)A.level[1].ptr, (const int32_t *)A.level[1].idx,
                 (const float *)A.val, A.nmajor, (int)A.bh, (int)A.bw, A.nrows, A.ncols, x, y, accumulate ? 1 : 0);
+      return env.status;
+    case P_BELL:
+      US_LAUNCH(env, "spmv_bell", 4.0 * A.nval + 4.0 * A.level[2].nidx + 8.0 * A.nrows + 4.0 * A.ncols, bell_spmv_kernel,
+                ceil_div<int64_t>(A.nrows, 256), 256, (const int32_t *)A.level[2].idx, (const float *)A.val, A.nmajor, A.nblk,
+                (int)A.bh, (int)A.bw, A.nrows, A.ncols, x, y, accumulate ? 1 : 0);
       return env.status;
     case P_CSB:
       if (!accumulate) fill_u32(env, (uint32_t *)y, A.nrows, 0u);

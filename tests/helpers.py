@@ -12,7 +12,7 @@ PRED = {O.SUM_GE_ABS: B.US_P_SUM_GE_ABS, O.SUM_GE_FRAC_OF_CAPACITY: B.US_P_SUM_G
 
 
 def us_expr_of(e: O.Expr):
-    return B.expr(KIND[e.kind], e.c0, e.c1, e.c, e.factor)
+    return B.expr(KIND[e.kind], e.c0, e.c1, e.c, e.factor, e.traverse_factor)
 
 
 def us_desc_of(d: O.FormatDesc):

@@ -16,6 +16,7 @@ FORMATS = [
     ("BCSR2x3", O.BCSR(2, 3)), ("BCSR8", O.BCSR(8)), ("ELL", O.ELL()), ("BDIA3", O.BDIA(3)), ("BDIA16", O.BDIA(16)),
     ("CSB2", O.CSB(2)), ("CSB5x3", O.CSB(5, 3)), ("CSB64x128", O.CSB(64, 128)),
     ("CISRplus1", O.CISR_PLUS(1)), ("CISRplus3", O.CISR_PLUS(3)), ("CISRplus256", O.CISR_PLUS(256)),
+    ("BELL4", O.BELL(4)), ("BELL2x3", O.BELL(2, 3)), ("BELL16x1", O.BELL(16, 1)),
 ]
 
 
@@ -142,7 +143,7 @@ def test_error_paths(ctx):
     from paper_2403_05802_amd import binding as B
     from helpers import dev, us_desc_of
     r = np.array([0, 1, 1], np.int32); c = np.array([0, 2, 2], np.int32); v = np.ones(3, np.float32)
-    for d in (O.CSR(), O.COO(), O.DCSR(), O.BCSR(2), O.ELL(), O.DIA(), O.BDIA(3), O.CSB(2)):
+    for d in (O.CSR(), O.COO(), O.DCSR(), O.BCSR(2), O.ELL(), O.DIA(), O.BDIA(3), O.CSB(2), O.BELL(2)):
         with pytest.raises(B.UnisparseError) as ei:
             B.us_convert(ctx, 3, 3, dev(r), dev(c), dev(v), us_desc_of(d))
         assert ei.value.code == "US_ERR_DUPLICATE", d
@@ -160,9 +161,13 @@ def test_error_paths(ctx):
         B.us_convert(ctx, 3, 3, dev(np.array([1, 1], np.int32)), dev(np.array([0, 2], np.int32)), dev(v[:2]),
                      us_desc_of(O.ELL(1)))
     assert ei.value.code == "US_ERR_SHAPE"
+    with pytest.raises(B.UnisparseError) as ei:   # a block row with more blocks than the fixed blocked-ELL width
+        B.us_convert(ctx, 3, 3, dev(np.array([1, 1], np.int32)), dev(np.array([0, 2], np.int32)), dev(v[:2]),
+                     us_desc_of(O.BELL(2, width=1)))
+    assert ei.value.code == "US_ERR_SHAPE"
     # allocator failure leaves nothing behind, whichever of a call's allocations is the first to fail
     before = ctx.live_bytes()
-    for d in (O.CSR(), O.COO(), O.DCSR(), O.DCSC(), O.ELL(), O.BCSR(2), O.DIA(), O.CISR_PLUS(2)):
+    for d in (O.CSR(), O.COO(), O.DCSR(), O.DCSC(), O.ELL(), O.BCSR(2), O.DIA(), O.CISR_PLUS(2), O.BELL(2)):
         failed = 0
         for k in range(12):
             ctx.fail_alloc_after = ctx._nalloc + k

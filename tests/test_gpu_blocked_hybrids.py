@@ -146,13 +146,13 @@ def clustered_blocks(nr, nc, seed, bh, bw, dense_blocks, fill, extra):
 @pytest.mark.parametrize("bh,bw,thld", [(4, 4, 8), (2, 3, 4), (8, 8, 1), (16, 2, 33), (4, 4, 0)])
 def test_block_threshold_hybrid(ctx, bh, bw, thld):
     """Decomposition of the BELL/COO case study (Section 7.2.2): blocks holding at least `thld` entries go to
-    the blocked part (stored as BCSR here), the rest stays COO; SpMM over the hybrid."""
+    the blocked part (stored as BCSR, as two other formats, and as blocked ELL), the rest stays COO; SpMM over the hybrid."""
     from paper_2403_05802_amd import binding as B
     from helpers import assert_product, row_terms, assert_same_layout, dev, host, us_desc_of, us_pred_of
     nr, nc = 1003, 2050
     r, c, v = clustered_blocks(nr, nc, seed=bh * 10 + bw, bh=bh, bw=bw, dense_blocks=1500, fill=0.8, extra=20_000)
     pred = O.Predicate((O.div(0, bh), O.div(1, bw)), O.SUM_GE_ABS, abs=thld)
-    for da, db in ((O.BCSR(bh, bw), O.COO()), (O.CSR(), O.DCSR())):
+    for da, db in ((O.BCSR(bh, bw), O.COO()), (O.CSR(), O.DCSR()), (O.BELL(bh, bw), O.COO())):
         oa, ob, mask = O.decompose(nr, nc, r, c, v, da, db, pred)
         ga, gb = B.us_decompose(ctx, nr, nc, dev(r), dev(c), dev(v), us_desc_of(da), us_desc_of(db), us_pred_of(pred))
         assert_same_layout(ga, oa, "A"); assert_same_layout(gb, ob, "B")

@@ -332,7 +332,8 @@ def test_spmm_with_row_strides(ctx):
     ref = O.spmm_coo(nr, nc, r, c, v, Xw[:, :N])
     S = O.spmm_coo(nr, nc, r, c, np.abs(v), np.abs(Xw[:, :N]))
     nt = row_terms(nr, r)[:, None]
-    for d in (O.CSR(), O.DCSR(), O.COO(), O.CSC(), O.ELL(), O.BCSR(4), O.BCSR(2, 3), O.BDIA(3), O.CSB(16), O.CISR_PLUS(5)):
+    for d in (O.CSR(), O.DCSR(), O.COO(), O.CSC(), O.ELL(), O.BCSR(4), O.BCSR(2, 3), O.BDIA(3), O.CSB(16), O.CISR_PLUS(5),
+              O.BELL(4), O.BELL(3, 2)):
         g = B.us_convert(ctx, nr, nc, dev(r), dev(c), dev(v), us_desc_of(d))
         for acc in (False, True):
             Xd, Yd = dev(Xw), dev(Yw0)

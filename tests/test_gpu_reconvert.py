@@ -10,7 +10,7 @@ pytestmark = pytest.mark.gpu
 
 FORMATS = [("COO", O.COO()), ("CSR", O.CSR()), ("DCSR", O.DCSR()), ("CSC", O.CSC()), ("DCSC", O.DCSC()),
            ("DIA", O.DIA()), ("DIAv", O.DIA_VARIANT()), ("BCSR4", O.BCSR(4)), ("BCSR2x3", O.BCSR(2, 3)), ("ELL", O.ELL()),
-           ("BDIA3", O.BDIA(3)), ("CSB8x4", O.CSB(8, 4)), ("CISRplus5", O.CISR_PLUS(5))]
+           ("BDIA3", O.BDIA(3)), ("CSB8x4", O.CSB(8, 4)), ("CISRplus5", O.CISR_PLUS(5)), ("BELL4x2", O.BELL(4, 2))]
 
 
 @pytest.fixture(scope="module")
