@@ -769,7 +769,10 @@ static bool sort_generic(Env &env, int in_mode, const int32_t *row, const int32_
   bool finish_local = false;
   // by default for blocked tuples only: block rows of FEM-like matrices fill evenly, while the rows of a
   // power-law graph do not (a heavy row's bucket needs extra splitting levels and the finish loses)
-  const bool want_finish = env.lds_finish > 0 || (env.lds_finish < 0 && ks.mode != 0);
+  // ... and for lists of at most RS_SMALL tiles whatever the tuple: there every launch costs more than the work it
+  // does, and one digit pass + the finish is 9 launches where five digit passes are 15 (a row heavy enough to send
+  // such a list back to the plain passes costs a tenth of a millisecond)
+  const bool want_finish = env.lds_finish > 0 || (env.lds_finish < 0 && (ks.mode != 0 || nnz <= (int64_t)RS_SMALL * RS_TILE));
   if (want_finish && in_mode == IN_COO && final_mode != OUT_KEY32 && nnz >= 4096) {
     const int want = bits_for((uint64_t)(nnz - 1) / 2048);
     high_bits = want < total_bits ? want : total_bits;

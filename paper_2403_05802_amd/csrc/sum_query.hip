@@ -232,9 +232,21 @@ void free_lists(Env &env, CooLists &l) {
 // DIA from per-diagonal flags (flags->scalar[1] already holds the number of flagged entries).
 // If `rest` is given, the entries of the unflagged diagonals are collected into it in the same
 // pass (its arrays are allocated here; the caller owns them afterwards) and *nrest is their number.
+// verify_later != null: the last read of the flags (coordinates in range, no value carrying the empty pattern, as
+// many occupied slots as entries) is left to the caller, who enqueues more work first and then calls
+// dia_verify with *verify_later: the host then waits once for both instead of twice.
+struct DiaPending { Flags *flags = nullptr; int64_t na = 0; };
+
+static us_status dia_verify(Env &env, const DiaPending &p) {
+  Flags h{};
+  if (!read_flags(env, p.flags, &h)) return env.status;
+  if (flag_status(h) != US_OK) return flag_status(h);
+  return h.scalar[3] != p.na ? US_ERR_DUPLICATE : US_OK;
+}
+
 static us_status dia_from_flags(Env &env, const us_coo &coo, const Plan &plan, const us_format_desc &desc,
                                 Flags *flags, const int32_t *flag, us_formatted **out, CooLists *rest,
-                                int64_t *nrest) {
+                                int64_t *nrest, DiaPending *verify_later = nullptr) {
   const int64_t nbins = coo.nrows + coo.ncols - 1, n = coo.nnz;
   const int64_t L = plan.swapped ? coo.ncols : coo.nrows;
   int32_t *pos = env.temp<int32_t>(nbins), *gmap = env.temp<int32_t>(nbins);
@@ -275,9 +287,14 @@ static us_status dia_from_flags(Env &env, const us_coo &coo, const Plan &plan, c
     US_LAUNCH(env, "count_marks", 1.0 * ndiag * L, count_marks_kernel, one_counter_grid(nvec, 256), 256, (const uint4 *)slotmap, nvec, &flags->scalar[3]);
   else if (nslab4 > 0)
     US_LAUNCH(env, "dia_finish", 4.0 * ndiag * L, dia_finish_kernel, one_counter_grid(nslab4, 256), 256, (uint4 *)f->val, nslab4, ndiag * L, &flags->scalar[3]);
-  if (!read_flags(env, flags, &h)) { free_formatted(env, f); return env.status; }
-  if (flag_status(h) != US_OK) { free_formatted(env, f); return flag_status(h); }
-  if (h.scalar[3] != na) { free_formatted(env, f); return US_ERR_DUPLICATE; }
+  if (verify_later) {
+    verify_later->flags = flags; verify_later->na = na;
+    if (!env.ok()) { free_formatted(env, f); return env.status; }
+    *out = f;
+    return US_OK;
+  }
+  const us_status st = dia_verify(env, DiaPending{flags, na});
+  if (st != US_OK) { free_formatted(env, f); return st; }
   *out = f;
   return US_OK;
 }
@@ -327,9 +344,12 @@ us_status decompose_sum(Env &env, const us_coo &coo, const Plan &pa, const us_fo
   CooLists la, lb;
   int64_t na = 0, nb = 0;
   us_status st;
+  DiaPending pending;
   if (gkind == G_DIAG && pa.pattern == P_DIA) {
-    // part A goes straight into the slab while part B is collected, in one pass over the input
-    st = dia_from_flags(env, coo, pa, da, flags, g.flag, oa, &lb, &nb);
+    // part A goes straight into the slab while part B is collected, in one pass over the input; its flags are read
+    // after part B's conversion has been enqueued (and has read its own): an input that fails them (a coordinate
+    // out of range reaches no slab slot and no list; a duplicate is a slot written twice) is reported then
+    st = dia_from_flags(env, coo, pa, da, flags, g.flag, oa, &lb, &nb, &pending);
   } else {
     Flags h{};
     if (!read_flags(env, flags, &h)) return env.status;
@@ -356,6 +376,10 @@ us_status decompose_sum(Env &env, const us_coo &coo, const Plan &pa, const us_fo
   if (st == US_OK) {
     us_coo cb{coo.nrows, coo.ncols, nb, lb.r, lb.c, lb.v};
     st = convert_with_plan(env, cb, pb, db, ob);
+  }
+  if (pending.flags) {   // part A's own verdict comes first: part B may have failed only because of what it reports
+    const us_status sa = dia_verify(env, pending);
+    if (sa != US_OK) st = sa;
   }
   env.sync();
   free_lists(env, la);

@@ -95,9 +95,18 @@ def zipf_lengths(rng, n: int, s: float, max_len: int, target_nnz: int) -> np.nda
     cdf = np.cumsum(k ** (-s))
     cdf /= cdf[-1]
     z = np.searchsorted(cdf, rng.random(n), side="left").astype(np.int64) + 1
-    c = float(target_nnz) / float(z.sum())
-    lens = np.floor(c * z + rng.random(n)).astype(np.int64)
-    return np.clip(lens, 1, max_len)
+    u = rng.random(n)
+    # the scale that makes the lengths add up to target_nnz AFTER the clipping to [1, max_len] (bisection: the
+    # clipped sum grows with the scale)
+    lo, hi = 0.0, 4.0 * float(target_nnz) / float(z.sum()) + 1.0
+    for _ in range(60):
+        c = 0.5 * (lo + hi)
+        total = int(np.clip(np.floor(c * z + u).astype(np.int64), 1, max_len).sum())
+        if total < target_nnz:
+            lo = c
+        else:
+            hi = c
+    return np.clip(np.floor(hi * z + u).astype(np.int64), 1, max_len)
 
 
 # --------------------------------------------------------------------------- config 1
