@@ -32,6 +32,10 @@ listed in the design notes of the repository):
     (the enum query of Figure 7), exposed as a size K (K = longest row unless a width is
     fixed); the column level that follows holds one index per (slot,row) with pad = -1
     and pad value +0.0;
+  * blocked ELL (the BELL of Section 7.2.2, whose encoding is in a figure that is not available): ELL's
+    map over block rows and block columns with the two in-block indices below it,
+    (indirect(d1/bw), d0/bh, d1/bw, d0%bh, d1%bw), merge(0), trim(0,0); the enum query numbers the
+    blocks of a block row (entries of one block share a number);
   * CISR-plus (Section 7.2.4, its printed encoding): the indirect level is built from three
     queries -- sum (entries per row), reorder (rows with the most entries first; equal rows in
     ascending row order) and schedule into N partitions; the text asks only that the assignment be balanced,
@@ -39,8 +43,9 @@ listed in the design notes of the repository):
     partition k mod N.  The level is untouched by trim(1,2), hence a size N; rows and columns
     below it are compressed levels (a row level with a ptr over the N partitions);
   * parity unpinned by the paper: the pad column (-1), percentile-based ELL width, the
-    "fraction of the in-bounds diagonal length" predicate and the dealing rule of schedule
-    are this repository's readings, pinned only by brute-force tests.
+    "fraction of the in-bounds diagonal length" predicate, the dealing rule of schedule and the
+    blocked ELL encoding are this repository's readings, pinned only by hand-derived layouts and
+    brute-force tests.
 """
 from __future__ import annotations
 

@@ -130,7 +130,7 @@ def draw_decomposition(seed):
         pred, da, db = O.Predicate((O.div(0, b1), O.diag()), O.SUM_GE_ABS, abs=int(rng.integers(1, b1 + 2))), O.BDIA(b1), pick()
     else:
         pred = O.Predicate((O.div(0, b1), O.div(1, b2)), O.SUM_GE_ABS, abs=int(rng.integers(1, b1 * b2 + 2)))
-        da, db = O.BCSR(b1, b2), pick()
+        da, db = (O.BELL(b1, b2) if seed % 2 else O.BCSR(b1, b2)), pick()   # blocked ELL for every other seed
     return nr, nc, r, c, v, da, db, pred, [None, True, False][seed % 3]
 
 
