@@ -473,6 +473,7 @@ struct LocalArgs {
   uint32_t nbuckets, n;
   int low_bits;          // bits left to sort, <= 32
   int b_bits;            // OUT_UNPACK: minor index width
+  int inner_bits;        // blocked tuples: key bits below the node (block row, block column | diagonal), the in-block indices
   // extra split of the big buckets
   uint32_t *counters;    // [0] big buckets, [1] their tiles, [2] groups
   BigBucket *big; uint32_t big_cap;
@@ -677,6 +678,158 @@ __device__ __forceinline__ void lds_sort(uint32_t cnt, int bits, uint32_t *s_key
   }
 }
 
+// The same result for the keys of a blocked tuple without sorting the entries: the entries of a bucket share few
+// nodes (a block holds up to bh * bw of them), so the nodes are told apart with a hash table in LDS, only the
+// distinct node keys are sorted, and an entry's place follows from its node's rank and from the entries of the
+// node that come before it, counted in a bit map of the occupied in-block positions:
+//   place = (entries of all nodes of lower rank) + (occupied positions of its node below its own).
+// The ballot ranking of lds_sort costs ~80 VALU instructions per entry and 8-bit digit; here an entry costs one
+// probe, two LDS atomics and a few population counts, whatever the width of the key.  Returns false (the same for
+// every thread, LDS contents undefined) when the bucket holds more than RK_NODES nodes or its bit map does not
+// fit: the caller then sorts the entries.  Two entries with one key share a bit: reported as a duplicate.
+constexpr uint32_t RK_NODES = LS_CAP / 2;        // distinct nodes a bucket may hold; the table has twice as many slots
+constexpr uint32_t RK_BITS = 32u * RK_NODES;      // bit map: RK_NODES words of LDS
+
+__device__ __forceinline__ uint32_t rk_count(const uint32_t *bm, uint32_t node, int ib, uint32_t below) {
+  // occupied positions of `node` below position `below` (below == 1 << ib: all of them)
+  if (ib <= 5) {
+    const uint32_t at = node << ib, w = bm[at >> 5] >> (at & 31u);
+    return __popc(below >= 32u ? w : (w & ((1u << below) - 1u)));
+  }
+  const uint32_t base = node << (ib - 5), full = below >> 5;
+  uint32_t c = 0;
+  for (uint32_t q = 0; q < full; ++q) c += __popc(bm[base + q]);
+  if (below & 31u) c += __popc(bm[base + full] & ((1u << (below & 31u)) - 1u));
+  return c;
+}
+
+template <int IPT>
+__device__ __forceinline__ bool rank_sort(const Rec *src, uint32_t first, uint32_t cnt, uint32_t low_mask, int low_bits,
+                                          int ib, uint32_t *s_key, uint32_t *s_val, uint32_t (*s_cnt)[RS_BINS],
+                                          uint32_t *s_start, uint32_t *s_wave, uint32_t *s_misc, Flags *flags) {
+  constexpr uint32_t EMPTY = 0xFFFFFFFFu;   // node keys have at most 31 bits
+  uint32_t *tab = s_key, *dkey = s_val, *dslot = s_val + RK_NODES;
+  static_assert(LS_CAP % (4 * LS_T) == 0, "table cleared with 16-byte stores");
+  for (uint32_t i = threadIdx.x; i < (uint32_t)LS_CAP / 4; i += LS_T)
+    reinterpret_cast<uint4 *>(tab)[i] = make_uint4(EMPTY, EMPTY, EMPTY, EMPTY);
+  if (threadIdx.x == 0) { s_misc[0] = 0; s_misc[1] = 0; }
+  s_start[threadIdx.x] = 0;   // ranks of up to LS_T nodes
+  static_assert(RS_BINS == LS_T, "one rank per thread");
+  uint32_t key[IPT], val[IPT], aux[IPT];
+#pragma unroll
+  for (int j = 0; j < IPT; ++j) {
+    const uint32_t i = threadIdx.x + j * LS_T;
+    key[j] = 0; val[j] = 0; aux[j] = 0;
+    if (i < cnt) {
+      const Rec r = src[first + i];
+      key[j] = r.lo & low_mask;
+      val[j] = r.val;
+    }
+  }
+  __syncthreads();
+  // every entry finds (or claims) the slot of its node; a claim also appends the node to the list of distinct
+  // ones.  Slots are never given up, so a probe ends at the node's slot or at a free one, and the table cannot
+  // fill: claims stop at RK_NODES + one per thread < LS_CAP
+#pragma unroll
+  for (int j = 0; j < IPT; ++j) {
+    if (threadIdx.x + j * LS_T < cnt) {
+      const uint32_t node = key[j] >> ib;
+      uint32_t h = (node * 0x9E3779B1u) >> 20;   // 12 bits: LS_CAP slots
+      while (__hip_atomic_load(&s_misc[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) == 0u) {
+        const uint32_t cur = __hip_atomic_load(&tab[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (cur == node) break;
+        if (cur == EMPTY) {
+          const uint32_t old = atomicCAS(&tab[h], EMPTY, node);
+          if (old == EMPTY) {
+            const uint32_t at = atomicAdd(&s_misc[0], 1u);
+            if (at < RK_NODES) { dkey[at] = node; dslot[at] = h; }
+            else __hip_atomic_store(&s_misc[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            break;
+          }
+          if (old == node) break;
+        }
+        h = (h + 1u) & (uint32_t)(LS_CAP - 1);
+      }
+      aux[j] = h;
+    }
+  }
+  __syncthreads();
+  const uint32_t nodes = s_misc[0];
+  if (s_misc[1] != 0u || ((uint64_t)nodes << ib) > (uint64_t)RK_BITS) return false;
+  // rank of every node among the distinct ones, left in its table slot
+  if (nodes <= (uint32_t)LS_T) {
+    // few: count the smaller keys.  A wavefront takes a quarter of the list against every node (one node per lane:
+    // all lanes read the same word, a broadcast) and adds its count to the node's rank
+    const uint32_t quarter = (nodes + 3u) / 4u, k0 = wave_id() * quarter, k1 = min(k0 + quarter, nodes);
+    for (uint32_t n = lane_id(); n < nodes; n += 64) {
+      const uint32_t mine = dkey[n];
+      uint32_t r = 0;
+#pragma unroll 8
+      for (uint32_t k = k0; k < k1; ++k) r += dkey[k] < mine;
+      if (r) atomicAdd(&s_start[n], r);
+    }
+    __syncthreads();
+    if (threadIdx.x < nodes) tab[dslot[threadIdx.x]] = s_start[threadIdx.x];
+  } else {
+    const int nbits = low_bits > ib ? low_bits - ib : 1;
+    if (nodes <= 2 * LS_T) lds_sort<LS_T, 2>(nodes, nbits, dkey, dslot, s_cnt, s_start, s_wave);
+    else if (nodes <= 4 * LS_T) lds_sort<LS_T, 4>(nodes, nbits, dkey, dslot, s_cnt, s_start, s_wave);
+    else lds_sort<LS_T, 8>(nodes, nbits, dkey, dslot, s_cnt, s_start, s_wave);
+    for (uint32_t r = threadIdx.x; r < nodes; r += LS_T) tab[dslot[r]] = r;
+  }
+  __syncthreads();
+  // (the list is no longer needed: its place takes a bit map of the occupied in-block positions, 1 << ib bits per
+  // node, and the number of entries before every node)
+  uint32_t *bm = s_val, *nstart = s_val + RK_NODES;
+  const uint32_t nwords = ((nodes << ib) + 31u) >> 5;
+  for (uint32_t w = threadIdx.x; w < nwords; w += LS_T) bm[w] = 0;
+#pragma unroll
+  for (int j = 0; j < IPT; ++j) aux[j] = tab[aux[j]];
+  __syncthreads();
+  const uint32_t imask = (1u << ib) - 1u;
+  bool dup = false;
+#pragma unroll
+  for (int j = 0; j < IPT; ++j) {
+    if (threadIdx.x + j * LS_T < cnt) {
+      const uint32_t bit = (aux[j] << ib) | (key[j] & imask);
+      dup |= (atomicOr(&bm[bit >> 5], 1u << (bit & 31u)) >> (bit & 31u)) & 1u;
+    }
+  }
+  if (dup) flags->duplicate = 1;
+  __syncthreads();
+  // entries before every node: consecutive nodes per thread, one if that covers them all
+  constexpr int NPT = RK_NODES / LS_T;
+  const int npt = nodes <= (uint32_t)LS_T ? 1 : NPT;
+  uint32_t c[NPT], sum = 0, total;
+#pragma unroll
+  for (int k = 0; k < NPT; ++k) {
+    const uint32_t r = threadIdx.x * npt + k;
+    c[k] = (k < npt && r < nodes) ? rk_count(bm, r, ib, 1u << ib) : 0u;
+    sum += c[k];
+  }
+  uint32_t run = block_exclusive_sum<LS_T>(sum, s_wave, &total);
+#pragma unroll
+  for (int k = 0; k < NPT; ++k) {
+    if (k < npt) nstart[threadIdx.x * npt + k] = run;
+    run += c[k];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < IPT; ++j)
+    if (threadIdx.x + j * LS_T < cnt) aux[j] = nstart[aux[j]] + rk_count(bm, aux[j], ib, key[j] & imask);
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < IPT; ++j) {
+    // (places collide only under a duplicate, which has been flagged; they stay below cnt either way)
+    if (threadIdx.x + j * LS_T < cnt && aux[j] < cnt) {
+      s_key[aux[j]] = key[j];
+      s_val[aux[j]] = val[j];
+    }
+  }
+  __syncthreads();
+  return true;
+}
+
 template <int OUT>
 __device__ __forceinline__ void local_emit(const LocalArgs &a, uint32_t bucket, uint32_t g, uint32_t k, uint32_t v) {
   const uint64_t full = ((uint64_t)bucket << a.low_bits) | (uint64_t)k;
@@ -689,14 +842,16 @@ __device__ __forceinline__ void local_emit(const LocalArgs &a, uint32_t bucket, 
   a.val_out[g] = v;
 }
 
-// workgroup i < nbuckets: bucket i if it is small enough; workgroup nbuckets + g: group g of a split bucket
-template <int OUT>
+// workgroup i < nbuckets: bucket i if it is small enough; workgroup nbuckets + g: group g of a split bucket.
+// BLOCKED: keys of a blocked tuple, placed by node rank where the bucket allows it (rank_sort)
+template <int OUT, bool BLOCKED>
 __global__ __launch_bounds__(LS_T, 4) void local_sort_kernel(LocalArgs a) {
   __shared__ uint32_t s_key[LS_CAP];
   __shared__ uint32_t s_val[LS_CAP];
   __shared__ uint32_t s_cnt[LS_T / 64][RS_BINS];
   __shared__ uint32_t s_start[RS_BINS];
   __shared__ uint32_t s_wave[LS_T / 64 + 1];
+  __shared__ uint32_t s_misc[2];
   uint32_t first, cnt, bucket;
   const Rec *src;
   if (blockIdx.x < a.nbuckets) {
@@ -712,17 +867,25 @@ __global__ __launch_bounds__(LS_T, 4) void local_sort_kernel(LocalArgs a) {
     src = a.rec_split;
   }
   const uint32_t low_mask = a.low_bits >= 32 ? 0xFFFFFFFFu : ((1u << a.low_bits) - 1u);
-  for (uint32_t i = threadIdx.x; i < cnt; i += LS_T) {
-    const Rec r = src[first + i];
-    s_key[i] = r.lo & low_mask;
-    s_val[i] = r.val;
+  bool placed = false;
+  if (BLOCKED) {
+    if (cnt <= 4 * LS_T) placed = rank_sort<4>(src, first, cnt, low_mask, a.low_bits, a.inner_bits, s_key, s_val, s_cnt, s_start, s_wave, s_misc, a.flags);
+    else if (cnt <= 8 * LS_T) placed = rank_sort<8>(src, first, cnt, low_mask, a.low_bits, a.inner_bits, s_key, s_val, s_cnt, s_start, s_wave, s_misc, a.flags);
+    else placed = rank_sort<16>(src, first, cnt, low_mask, a.low_bits, a.inner_bits, s_key, s_val, s_cnt, s_start, s_wave, s_misc, a.flags);
   }
-  __syncthreads();
-  if (cnt <= LS_T) lds_sort<LS_T, 1>(cnt, a.low_bits, s_key, s_val, s_cnt, s_start, s_wave);
-  else if (cnt <= 2 * LS_T) lds_sort<LS_T, 2>(cnt, a.low_bits, s_key, s_val, s_cnt, s_start, s_wave);
-  else if (cnt <= 4 * LS_T) lds_sort<LS_T, 4>(cnt, a.low_bits, s_key, s_val, s_cnt, s_start, s_wave);
-  else if (cnt <= 8 * LS_T) lds_sort<LS_T, 8>(cnt, a.low_bits, s_key, s_val, s_cnt, s_start, s_wave);
-  else lds_sort<LS_T, 16>(cnt, a.low_bits, s_key, s_val, s_cnt, s_start, s_wave);
+  if (!placed) {
+    for (uint32_t i = threadIdx.x; i < cnt; i += LS_T) {
+      const Rec r = src[first + i];
+      s_key[i] = r.lo & low_mask;
+      s_val[i] = r.val;
+    }
+    __syncthreads();
+    if (cnt <= LS_T) lds_sort<LS_T, 1>(cnt, a.low_bits, s_key, s_val, s_cnt, s_start, s_wave);
+    else if (cnt <= 2 * LS_T) lds_sort<LS_T, 2>(cnt, a.low_bits, s_key, s_val, s_cnt, s_start, s_wave);
+    else if (cnt <= 4 * LS_T) lds_sort<LS_T, 4>(cnt, a.low_bits, s_key, s_val, s_cnt, s_start, s_wave);
+    else if (cnt <= 8 * LS_T) lds_sort<LS_T, 8>(cnt, a.low_bits, s_key, s_val, s_cnt, s_start, s_wave);
+    else lds_sort<LS_T, 16>(cnt, a.low_bits, s_key, s_val, s_cnt, s_start, s_wave);
+  }
   bool dup = false;
   for (uint32_t i = threadIdx.x; i < cnt; i += LS_T) {
     const uint32_t k = s_key[i];
@@ -899,10 +1062,15 @@ static bool sort_generic(Env &env, int in_mode, const int32_t *row, const int32_
   US_LAUNCH(env, "seg_hist", 0.0, seg_hist_kernel, la.tile_cap, RS_T, la);
   US_LAUNCH(env, "seg_scan", 0.0, seg_scan_kernel, la.big_cap, RS_BINS, la);
   US_LAUNCH(env, "seg_scatter", 0.0, seg_scatter_kernel, la.tile_cap, RS_T, la);
+  // blocked tuples with in-block indices in the key (node keys of at most 31 bits): placement by node rank
+  la.inner_bits = ks.mode == 1 ? ks.ih_bits + ks.iw_bits : (ks.mode == 2 ? ks.ih_bits : 0);
+  const bool by_rank = la.inner_bits >= 1 && la.inner_bits <= 16;
   if (final_mode == OUT_UNPACK)
-    US_LAUNCH(env, "local_sort", 24.0 * nnz, (local_sort_kernel<OUT_UNPACK>), nbuckets + la.work_cap, LS_T, la);
+    US_LAUNCH(env, "local_sort", 24.0 * nnz, (local_sort_kernel<OUT_UNPACK, false>), nbuckets + la.work_cap, LS_T, la);
+  else if (by_rank)
+    US_LAUNCH(env, "local_sort", 24.0 * nnz, (local_sort_kernel<OUT_KEY64, true>), nbuckets + la.work_cap, LS_T, la);
   else
-    US_LAUNCH(env, "local_sort", 24.0 * nnz, (local_sort_kernel<OUT_KEY64>), nbuckets + la.work_cap, LS_T, la);
+    US_LAUNCH(env, "local_sort", 24.0 * nnz, (local_sort_kernel<OUT_KEY64, false>), nbuckets + la.work_cap, LS_T, la);
   return true;
 }
 
