@@ -138,3 +138,53 @@ def test_scaled_workloads_and_hybrids(ctx):
         ga, gb = B.us_decompose(ctx, m.nrows, m.ncols, *coo_to_dev(m), us_desc_of(O.ELL()), us_desc_of(O.COO()),
                                 us_pred_of(pred))
     assert_same_layout(ga, oa, "ELL part"); assert_same_layout(gb, ob, "COO part")
+
+
+def blocks_matrix(rng, nr, nc, bh, bw, nblocks, fill):
+    """`nblocks` distinct bh x bw blocks at random places, `fill` entries in each (at random in-block positions)."""
+    nbr, nbc = -(-nr // bh), -(-nc // bw)
+    blk = rng.choice(nbr * nbc, size=nblocks, replace=False)
+    rows, cols = [], []
+    for b in blk:
+        at = rng.choice(bh * bw, size=min(fill, bh * bw), replace=False)
+        rows.append((b // nbc) * bh + at // bw)
+        cols.append((b % nbc) * bw + at % bw)
+    r, c = np.concatenate(rows), np.concatenate(cols)
+    keep = (r < nr) & (c < nc)
+    return distinct(nr, nc, r[keep], c[keep])
+
+
+# (bh, bw, entries per block, blocks): few nodes per bucket (counted ranks), hundreds (sorted ranks), more than the
+# table takes or a bit map that does not fit (the bucket's entries are sorted instead), multi-word bit maps (8x8, 16x16),
+# block shapes that are no powers of two, a block height of one
+RANK_CASES = [(4, 4, 16, 12_000), (4, 4, 5, 40_000), (4, 4, 2, 90_000), (4, 4, 1, 150_000), (4, 4, 1, 260_000), (2, 2, 3, 60_000),
+              (8, 8, 40, 5_000), (8, 8, 3, 60_000), (16, 16, 200, 1_000), (16, 16, 2, 90_000), (3, 5, 9, 20_000),
+              (5, 3, 2, 80_000), (1, 4, 3, 60_000), (16, 1, 7, 25_000)]
+
+
+@pytest.mark.parametrize("bh,bw,fill,nblocks", RANK_CASES)
+def test_blocked_tuples_placed_by_node_rank(ctx, bh, bw, fill, nblocks):
+    rng = np.random.default_rng(1000 + 37 * bh + 5 * bw + fill)
+    nr, nc = 30_011, 41_003
+    r, c = blocks_matrix(rng, nr, nc, bh, bw, nblocks, fill)
+    r, c, v = shuffled(rng, r, c)
+    descs = [O.BCSR(bh, bw)] + ([O.BELL(bh, bw)] if bh * bw <= 64 else []) + ([O.BDIA(bh)] if bw == 1 or bh == bw else [])
+    check(ctx, nr, nc, r, c, v, descs)
+
+
+@pytest.mark.parametrize("bh,bw,fill,nblocks", [(4, 4, 16, 12_000), (4, 4, 2, 90_000), (4, 4, 1, 260_000), (8, 8, 40, 5_000),
+                                                (16, 16, 2, 90_000)])
+def test_duplicates_are_found_whichever_way_a_bucket_is_finished(ctx, bh, bw, fill, nblocks):
+    from paper_2403_05802_amd import binding as B
+    from helpers import dev, us_desc_of
+    rng = np.random.default_rng(2000 + 37 * bh + fill)
+    nr, nc = 30_011, 41_003
+    r, c = blocks_matrix(rng, nr, nc, bh, bw, nblocks, fill)
+    r, c, v = shuffled(rng, r, c)
+    for at in (0, r.size // 2, r.size - 1):
+        r2 = np.append(r, r[at]); c2 = np.append(c, c[at]); v2 = np.append(v, np.float32(1))
+        p = rng.permutation(r2.size)
+        for d in (O.BCSR(bh, bw), O.BDIA(bh)):
+            with lds_finish(ctx), pytest.raises(B.UnisparseError) as ei:
+                B.us_convert(ctx, nr, nc, dev(r2[p]), dev(c2[p]), dev(v2[p]), us_desc_of(d))
+            assert ei.value.code == "US_ERR_DUPLICATE"
