@@ -237,7 +237,7 @@ class Workload:
             nr = nc = cut
             what = f"the leading {cut} x {cut} block of the matrix"
         else:
-            nr, nc = m.nrows // 16, m.ncols
+            nr, nc = m.nrows // 4, m.ncols
             sel = m.row < nr
             what = f"the first {nr} rows of the matrix (all columns)"
         r, c, v = m.row[sel], m.col[sel], m.val[sel]
