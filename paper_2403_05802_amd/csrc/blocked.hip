@@ -9,6 +9,7 @@ namespace us {
 // After sorting by (d0/bh, d1/bw, d0%bh, d1%bw) the entries of a block are contiguous.
 // Merge(0,1): head flag where the block prefix changes, scan -> block id.
 constexpr int BE_T = 256, BE_IPT = 8, BE_TILE = BE_T * BE_IPT;
+static_assert(BE_TILE == NODE_TILE, "the sort counts nodes per tile of the emit kernel");
 
 __global__ __launch_bounds__(BE_T) void bcsr_count_kernel(const uint64_t *key, int64_t n, int inner_bits,
                                                          uint32_t *partial, Flags *flags) {
@@ -118,12 +119,14 @@ KeySpec blocked_keyspec(const Plan &plan, int64_t nrows, int64_t ncols) {
 // Sorted keys -> ptr/idx of the merged node level and the zero-filled dense inner levels.
 us_status emit_blocked(Env &env, const Plan &plan, const us_format_desc &desc, int64_t nrows, int64_t ncols,
                        const KeySpec &ks, const uint64_t *skey, const float *sval, int64_t n, Flags *flags,
-                       us_formatted **out) {
+                       us_formatted **out, uint32_t *node_count) {
   const int64_t nbr = ceil_div<int64_t>(nrows, plan.bh);
   const int64_t nb = ceil_div<int64_t>(n > 0 ? n : 1, BE_TILE);
-  uint32_t *partial = env.temp<uint32_t>(nb);
+  // nodes that start in every tile: counted by the sort already (node_count), or here (which also looks for equal keys)
+  uint32_t *partial = node_count ? node_count : env.temp<uint32_t>(nb);
   if (!env.ok()) return env.status;
-  US_LAUNCH(env, "bcsr_count", 8.0 * n, bcsr_count_kernel, nb, BE_T, skey, n, ks.ih_bits + ks.iw_bits, partial, flags);
+  if (!node_count)
+    US_LAUNCH(env, "bcsr_count", 8.0 * n, bcsr_count_kernel, nb, BE_T, skey, n, ks.ih_bits + ks.iw_bits, partial, flags);
   scan_partials_launch(env, partial, nb, &flags->scalar[0]);
   Flags h{};
   if (!read_flags(env, flags, &h)) return env.status;
@@ -206,11 +209,14 @@ us_status convert_blocked(Env &env, const us_coo &coo, const Plan &plan, const u
   if (ks.total_bits > 64) return US_ERR_OVERFLOW;
   uint64_t *skey = env.temp<uint64_t>(n);
   float *sval = env.temp<float>(n);
+  uint32_t *node_count = env.temp<uint32_t>(ceil_div<int64_t>(n > 0 ? n : 1, BE_TILE));
   if (!env.ok()) return env.status;
   SortOut so{};
-  so.key64 = skey; so.val = sval;
-  sort_coo(env, coo.row, coo.col, coo.val, n, ks, so, flags);
-  return emit_blocked(env, plan, desc, coo.nrows, coo.ncols, ks, skey, sval, n, flags, out);
+  bool counted = false;
+  so.key64 = skey; so.val = sval; so.node_count = node_count; so.node_counted = &counted;
+  const bool dups_checked = sort_coo(env, coo.row, coo.col, coo.val, n, ks, so, flags);
+  return emit_blocked(env, plan, desc, coo.nrows, coo.ncols, ks, skey, sval, n, flags, out,
+                      counted && dups_checked ? node_count : nullptr);
 }
 
 // CSB (Section 2.1: a dense collection of blocks stored compressed): the entries in BCSR tuple order, a ptr

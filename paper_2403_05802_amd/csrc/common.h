@@ -226,7 +226,13 @@ struct SortOut {
   // the last step of the sort are enqueued (an allocation made then costs no idle time on the GPU).  After a
   // failure inside it (Env::status) nothing more is launched.
   std::function<void(SortOut &)> late;
+  // Blocked tuples, packed output: node_count[t] (zeroed by the sort) receives the number of entries of output tile
+  // t (NODE_TILE consecutive entries) whose node key -- the key without its in-block bits -- differs from their
+  // predecessor's, i.e. the nodes that start in the tile.  Only the finish inside LDS counts them (it has the sorted
+  // keys at hand): *node_counted says whether it did.
+  uint32_t *node_count = nullptr; bool *node_counted = nullptr;
 };
+constexpr int NODE_TILE_SHIFT = 11, NODE_TILE = 1 << NODE_TILE_SHIFT;
 bool sort_coo(Env &env, const int32_t *row, const int32_t *col, const float *val, int64_t nnz,
               const KeySpec &ks, const SortOut &out, Flags *flags_dev);
 // what a whole-array sort of nnz entries takes from Env::temp (for Env::reserve by a caller with temporaries of its own)

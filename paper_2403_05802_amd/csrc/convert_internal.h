@@ -62,7 +62,7 @@ KeySpec blocked_keyspec(const Plan &plan, int64_t nrows, int64_t ncols);
 // from entries sorted by the blocked tuple (keys built with ks)
 us_status emit_blocked(Env &env, const Plan &plan, const us_format_desc &desc, int64_t nrows, int64_t ncols,
                        const KeySpec &ks, const uint64_t *skey, const float *sval, int64_t n, Flags *flags,
-                       us_formatted **out);
+                       us_formatted **out, uint32_t *node_count = nullptr);   // node_count: SortOut::node_count when the sort filled it
 us_status convert_blocked(Env &env, const us_coo &coo, const Plan &plan, const us_format_desc &desc, Flags *flags,
                           us_formatted **out);
 us_status convert_csb(Env &env, const us_coo &coo, const Plan &plan, const us_format_desc &desc, Flags *flags,

@@ -474,6 +474,7 @@ struct LocalArgs {
   int low_bits;          // bits left to sort, <= 32
   int b_bits;            // OUT_UNPACK: minor index width
   int inner_bits;        // blocked tuples: key bits below the node (block row, block column | diagonal), the in-block indices
+  uint32_t *node_count;  // per NODE_TILE output entries: nodes that start there (SortOut::node_count), or null
   // extra split of the big buckets
   uint32_t *counters;    // [0] big buckets, [1] their tiles, [2] groups
   BigBucket *big; uint32_t big_cap;
@@ -703,10 +704,27 @@ __device__ __forceinline__ uint32_t rk_count(const uint32_t *bm, uint32_t node, 
   return c;
 }
 
+// A wavefront adds the nodes it has seen start in the (at most three) output tiles its work item touches to
+// their counters: which[lane] = 0..2 for a lane that holds the first entry of a node, 3 otherwise.
+__device__ __forceinline__ void add_heads(uint32_t which, uint32_t *h) {
+  h[0] += (uint32_t)__popcll(__ballot(which == 0u));
+  h[1] += (uint32_t)__popcll(__ballot(which == 1u));
+  h[2] += (uint32_t)__popcll(__ballot(which == 2u));
+}
+__device__ __forceinline__ void flush_heads(uint32_t *tile_count, const uint32_t *h) {
+  // (a tile with heads holds entries of this work item, so its index is below the number of tiles)
+  if (lane_id() == 0) {
+    if (h[0]) atomicAdd(&tile_count[0], h[0]);
+    if (h[1]) atomicAdd(&tile_count[1], h[1]);
+    if (h[2]) atomicAdd(&tile_count[2], h[2]);
+  }
+}
+
 template <int IPT>
 __device__ __forceinline__ bool rank_sort(const Rec *src, uint32_t first, uint32_t cnt, uint32_t low_mask, int low_bits,
                                           int ib, uint32_t *s_key, uint32_t *s_val, uint32_t (*s_cnt)[RS_BINS],
-                                          uint32_t *s_start, uint32_t *s_wave, uint32_t *s_misc, Flags *flags) {
+                                          uint32_t *s_start, uint32_t *s_wave, uint32_t *s_misc, uint32_t *tile_count,
+                                          Flags *flags) {
   constexpr uint32_t EMPTY = 0xFFFFFFFFu;   // node keys have at most 31 bits
   uint32_t *tab = s_key, *dkey = s_val, *dslot = s_val + RK_NODES;
   static_assert(LS_CAP % (4 * LS_T) == 0, "table cleared with 16-byte stores");
@@ -814,6 +832,14 @@ __device__ __forceinline__ bool rank_sort(const Rec *src, uint32_t first, uint32
     run += c[k];
   }
   __syncthreads();
+  if (tile_count) {   // nodes that start in each of the output tiles the bucket touches
+    uint32_t h[3] = {0, 0, 0};
+    for (uint32_t base = 0; base < nodes; base += LS_T) {
+      const uint32_t r = base + threadIdx.x;
+      add_heads(r < nodes ? ((first + nstart[r]) >> NODE_TILE_SHIFT) - (first >> NODE_TILE_SHIFT) : 3u, h);
+    }
+    flush_heads(tile_count, h);
+  }
 #pragma unroll
   for (int j = 0; j < IPT; ++j)
     if (threadIdx.x + j * LS_T < cnt) aux[j] = nstart[aux[j]] + rk_count(bm, aux[j], ib, key[j] & imask);
@@ -867,11 +893,13 @@ __global__ __launch_bounds__(LS_T, 4) void local_sort_kernel(LocalArgs a) {
     src = a.rec_split;
   }
   const uint32_t low_mask = a.low_bits >= 32 ? 0xFFFFFFFFu : ((1u << a.low_bits) - 1u);
+  // a work item of at most LS_CAP entries touches at most three output tiles, the first of them this one
+  uint32_t *tile_count = (BLOCKED && a.node_count) ? a.node_count + (first >> NODE_TILE_SHIFT) : nullptr;
   bool placed = false;
   if (BLOCKED) {
-    if (cnt <= 4 * LS_T) placed = rank_sort<4>(src, first, cnt, low_mask, a.low_bits, a.inner_bits, s_key, s_val, s_cnt, s_start, s_wave, s_misc, a.flags);
-    else if (cnt <= 8 * LS_T) placed = rank_sort<8>(src, first, cnt, low_mask, a.low_bits, a.inner_bits, s_key, s_val, s_cnt, s_start, s_wave, s_misc, a.flags);
-    else placed = rank_sort<16>(src, first, cnt, low_mask, a.low_bits, a.inner_bits, s_key, s_val, s_cnt, s_start, s_wave, s_misc, a.flags);
+    if (cnt <= 4 * LS_T) placed = rank_sort<4>(src, first, cnt, low_mask, a.low_bits, a.inner_bits, s_key, s_val, s_cnt, s_start, s_wave, s_misc, tile_count, a.flags);
+    else if (cnt <= 8 * LS_T) placed = rank_sort<8>(src, first, cnt, low_mask, a.low_bits, a.inner_bits, s_key, s_val, s_cnt, s_start, s_wave, s_misc, tile_count, a.flags);
+    else placed = rank_sort<16>(src, first, cnt, low_mask, a.low_bits, a.inner_bits, s_key, s_val, s_cnt, s_start, s_wave, s_misc, tile_count, a.flags);
   }
   if (!placed) {
     for (uint32_t i = threadIdx.x; i < cnt; i += LS_T) {
@@ -887,12 +915,24 @@ __global__ __launch_bounds__(LS_T, 4) void local_sort_kernel(LocalArgs a) {
     else lds_sort<LS_T, 16>(cnt, a.low_bits, s_key, s_val, s_cnt, s_start, s_wave);
   }
   bool dup = false;
-  for (uint32_t i = threadIdx.x; i < cnt; i += LS_T) {
-    const uint32_t k = s_key[i];
-    dup |= i > 0 && s_key[i - 1] == k;
-    local_emit<OUT>(a, bucket, first + i, k, s_val[i]);
+  uint32_t h[3] = {0, 0, 0};
+  const bool count_here = BLOCKED && tile_count && !placed;   // (rank_sort has counted its nodes itself)
+  for (uint32_t base = 0; base < cnt; base += LS_T) {
+    const uint32_t i = base + threadIdx.x;
+    uint32_t which = 3u;
+    if (i < cnt) {
+      const uint32_t k = s_key[i];
+      dup |= i > 0 && s_key[i - 1] == k;
+      local_emit<OUT>(a, bucket, first + i, k, s_val[i]);
+      // (the first entry of a work item starts a node: bucket and piece are told apart by bits of the node key,
+      // which the host has checked before asking for the counts)
+      if (count_here && (i == 0 || (k >> a.inner_bits) != (s_key[i - 1] >> a.inner_bits)))
+        which = ((first + i) >> NODE_TILE_SHIFT) - (first >> NODE_TILE_SHIFT);
+    }
+    if (count_here) add_heads(which, h);
   }
   if (dup) a.flags->duplicate = 1;
+  if (count_here) flush_heads(tile_count, h);
 }
 
 template <int IN>
@@ -919,6 +959,7 @@ static void launch_scatter_out(Env &env, const PassArgs &a, int out_mode, double
 static bool sort_generic(Env &env, int in_mode, const int32_t *row, const int32_t *col, const uint32_t *key32_in,
                          const float *val, int64_t nnz, const KeySpec &ks, const SortOut &out_in, Flags *flags) {
   SortOut out = out_in;
+  if (out.node_counted) *out.node_counted = false;
   if (nnz <= 0 || !env.ok()) {
     if (out.late && env.ok()) out.late(out);   // the caller still gets its (empty) arrays
     return false;
@@ -1065,6 +1106,12 @@ static bool sort_generic(Env &env, int in_mode, const int32_t *row, const int32_
   // blocked tuples with in-block indices in the key (node keys of at most 31 bits): placement by node rank
   la.inner_bits = ks.mode == 1 ? ks.ih_bits + ks.iw_bits : (ks.mode == 2 ? ks.ih_bits : 0);
   const bool by_rank = la.inner_bits >= 1 && la.inner_bits <= 16;
+  // nodes per output tile on the way: the first entry of every bucket and of every piece of a split bucket must
+  // start a node, i.e. the bits that tell buckets and pieces apart must all belong to the node key
+  const bool count_nodes = out.node_count && by_rank && final_mode == OUT_KEY64 && low_bits - RS_MAXBITS >= la.inner_bits;
+  la.node_count = count_nodes ? out.node_count : nullptr;
+  if (count_nodes) fill_u32(env, out.node_count, (uint64_t)ceil_div<int64_t>(nnz, NODE_TILE), 0u);
+  if (out.node_counted) *out.node_counted = count_nodes;
   if (final_mode == OUT_UNPACK)
     US_LAUNCH(env, "local_sort", 24.0 * nnz, (local_sort_kernel<OUT_UNPACK, false>), nbuckets + la.work_cap, LS_T, la);
   else if (by_rank)

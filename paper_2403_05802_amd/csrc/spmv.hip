@@ -176,7 +176,8 @@ static void spmv_compressed(Env &env, const us_formatted &A, const int32_t *ptr,
   if (!env.ok()) return;
   int32_t *carry_row = (int32_t *)ws;
   float *carry_val = (float *)(ws + half);
-  const double bytes = 8.0 * nnz + 4.0 * (nrows_stored + 1) + 4.0 * nnz /*x gather*/ + 4.0 * nrows_stored;
+  // (x counted once, as its length: what the gathers re-read is traffic, not algorithmic bytes)
+  const double bytes = 8.0 * nnz + 4.0 * (nrows_stored + 1) + 4.0 * (A.swapped ? A.nrows : A.ncols) + 4.0 * nrows_stored;
   if (row_ids) {
     US_LAUNCH(env, "spmv_csr", bytes, (csr_spmv_kernel<true>), nb, MP_T, ptr, idx, val, row_ids,
               (const int32_t *)A.mp_split, nrows_stored, nnz,
