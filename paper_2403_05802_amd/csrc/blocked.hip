@@ -127,7 +127,9 @@ us_status emit_blocked(Env &env, const Plan &plan, const us_format_desc &desc, i
   if (!env.ok()) return env.status;
   if (!node_count)
     US_LAUNCH(env, "bcsr_count", 8.0 * n, bcsr_count_kernel, nb, BE_T, skey, n, ks.ih_bits + ks.iw_bits, partial, flags);
-  scan_partials_launch(env, partial, nb, &flags->scalar[0]);
+  // (one workgroup scanning 24,576 tile counts took 29 us; reduce + scan of the sums + apply takes three short launches)
+  if (nb > 8192) exclusive_scan_i32(env, (const int32_t *)partial, (int32_t *)partial, nb, &flags->scalar[0]);
+  else scan_partials_launch(env, partial, nb, &flags->scalar[0]);
   Flags h{};
   if (!read_flags(env, flags, &h)) return env.status;
   if (flag_status(h) != US_OK) return flag_status(h);

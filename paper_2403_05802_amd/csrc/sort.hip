@@ -494,6 +494,9 @@ __device__ __forceinline__ uint32_t split_digit(const LocalArgs &a, uint32_t lo)
   return a.low_bits > RS_MAXBITS ? (low >> (a.low_bits - RS_MAXBITS)) : low;   // top 8 of the low bits
 }
 
+// off[b] = first record whose prefix (key >> low_bits) is >= b, by bisection.  (A search that probes 64 places per
+// step, one wavefront per bucket, ends after 3-5 rounds of loads instead of 26, but fetches 10 M scattered lines where
+// the bisections share their upper levels: 41 us against 22 for the 32,769 buckets of 50 M records.)
 __global__ __launch_bounds__(256) void bucket_offsets_kernel(const Rec *rec, uint32_t n, int low_bits, uint32_t nbuckets,
                                                             uint32_t *off) {
   const uint32_t b = blockIdx.x * 256 + threadIdx.x;
@@ -530,17 +533,23 @@ __global__ __launch_bounds__(256) void big_list_kernel(LocalArgs a) {
   for (uint32_t j = 0; j < ntiles; ++j) a.tilemap[tb + j] = k;
 }
 
+// (the three kernels of the extra split walk their items with a stride of the grid: most inputs have no bucket to
+// split, and a launch of one workgroup per possible tile then costs ~13 us of workgroups that start and leave)
+constexpr uint32_t SEG_GRID = 1024;
+
 __global__ __launch_bounds__(RS_T) void seg_hist_kernel(LocalArgs a) {
   __shared__ uint32_t s_hist[RS_BINS];
-  const uint32_t t = blockIdx.x;
-  if (t >= min(a.counters[1], a.tile_cap)) return;
-  for (int i = threadIdx.x; i < RS_BINS; i += RS_T) s_hist[i] = 0;
-  __syncthreads();
-  const BigBucket B = a.big[min(a.tilemap[t], a.big_cap - 1)];
-  const uint32_t begin = (t - B.tile_base) * RS_TILE, end = min(begin + (uint32_t)RS_TILE, B.size);
-  for (uint32_t i = begin + threadIdx.x; i < end; i += RS_T) atomicAdd(&s_hist[split_digit(a, a.rec_in[B.first + i].lo)], 1u);
-  __syncthreads();
-  for (uint32_t d = threadIdx.x; d < RS_BINS; d += RS_T) a.shist[(size_t)t * RS_BINS + d] = s_hist[d];
+  const uint32_t ntiles = min(a.counters[1], a.tile_cap);
+  for (uint32_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    for (int i = threadIdx.x; i < RS_BINS; i += RS_T) s_hist[i] = 0;
+    __syncthreads();
+    const BigBucket B = a.big[min(a.tilemap[t], a.big_cap - 1)];
+    const uint32_t begin = (t - B.tile_base) * RS_TILE, end = min(begin + (uint32_t)RS_TILE, B.size);
+    for (uint32_t i = begin + threadIdx.x; i < end; i += RS_T) atomicAdd(&s_hist[split_digit(a, a.rec_in[B.first + i].lo)], 1u);
+    __syncthreads();
+    for (uint32_t d = threadIdx.x; d < RS_BINS; d += RS_T) a.shist[(size_t)t * RS_BINS + d] = s_hist[d];
+    __syncthreads();
+  }
 }
 
 // one workgroup per big bucket: prefixes of the (tile, digit) counts, piece starts, bundling into groups
@@ -548,10 +557,10 @@ __global__ __launch_bounds__(RS_BINS) void seg_scan_kernel(LocalArgs a) {
   __shared__ uint32_t s_wave[RS_BINS / 64 + 1];
   __shared__ uint32_t s_pos[RS_BINS + 1];    // piece starts, then group starts
   __shared__ uint32_t s_base;
-  const uint32_t k = blockIdx.x;
-  if (k >= min(a.counters[0], a.big_cap)) return;
+  const uint32_t nbig = min(a.counters[0], a.big_cap), d = threadIdx.x;
+  for (uint32_t k = blockIdx.x; k < nbig; k += gridDim.x) {
   const BigBucket B = a.big[k];
-  const uint32_t ntiles = (B.size + RS_TILE - 1) / RS_TILE, d = threadIdx.x;
+  const uint32_t ntiles = (B.size + RS_TILE - 1) / RS_TILE;
   uint32_t run = 0;
   for (uint32_t j = 0; j < ntiles; ++j) {
     uint32_t *h = a.shist + (size_t)(B.tile_base + j) * RS_BINS + d;
@@ -580,23 +589,27 @@ __global__ __launch_bounds__(RS_BINS) void seg_scan_kernel(LocalArgs a) {
     if (g < a.work_cap) a.work[g] = WorkItem{B.first + start, gsize, B.bucket};
     else a.flags->retry = RETRY_SORT_LDS;
   }
+  __syncthreads();   // s_pos and s_base are reused by the next bucket
+  }
 }
 
 __global__ __launch_bounds__(RS_T) void seg_scatter_kernel(LocalArgs a) {
   __shared__ uint32_t s_next[RS_BINS];
-  const uint32_t t = blockIdx.x;
-  if (t >= min(a.counters[1], a.tile_cap)) return;
-  const uint32_t k = min(a.tilemap[t], a.big_cap - 1);
-  const BigBucket B = a.big[k];
-  for (uint32_t d = threadIdx.x; d < RS_BINS; d += RS_T)
-    s_next[d] = B.first + a.sdig[(size_t)k * RS_BINS + d] + a.shist[(size_t)t * RS_BINS + d];
-  __syncthreads();
-  const uint32_t begin = (t - B.tile_base) * RS_TILE, end = min(begin + (uint32_t)RS_TILE, B.size);
-  for (uint32_t i = begin + threadIdx.x; i < end; i += RS_T) {
-    const Rec r = a.rec_in[B.first + i];
-    // the order inside a piece is settled by the full sort of its group, so any free slot will do
-    const uint32_t at = atomicAdd(&s_next[split_digit(a, r.lo)], 1u);
-    if (at < a.n) a.rec_split[at] = r;
+  const uint32_t ntiles = min(a.counters[1], a.tile_cap);
+  for (uint32_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    const uint32_t k = min(a.tilemap[t], a.big_cap - 1);
+    const BigBucket B = a.big[k];
+    for (uint32_t d = threadIdx.x; d < RS_BINS; d += RS_T)
+      s_next[d] = B.first + a.sdig[(size_t)k * RS_BINS + d] + a.shist[(size_t)t * RS_BINS + d];
+    __syncthreads();
+    const uint32_t begin = (t - B.tile_base) * RS_TILE, end = min(begin + (uint32_t)RS_TILE, B.size);
+    for (uint32_t i = begin + threadIdx.x; i < end; i += RS_T) {
+      const Rec r = a.rec_in[B.first + i];
+      // the order inside a piece is settled by the full sort of its group, so any free slot will do
+      const uint32_t at = atomicAdd(&s_next[split_digit(a, r.lo)], 1u);
+      if (at < a.n) a.rec_split[at] = r;
+    }
+    __syncthreads();
   }
 }
 
@@ -878,6 +891,8 @@ __global__ __launch_bounds__(LS_T, 4) void local_sort_kernel(LocalArgs a) {
   __shared__ uint32_t s_start[RS_BINS];
   __shared__ uint32_t s_wave[LS_T / 64 + 1];
   __shared__ uint32_t s_misc[2];
+  // (one workgroup per possible group although most inputs have none: walking the groups with a stride instead put a
+  // loop around the body that cost the common path a quarter of its speed, 329 -> 407 us on the FEM-like matrix)
   uint32_t first, cnt, bucket;
   const Rec *src;
   if (blockIdx.x < a.nbuckets) {
@@ -1093,16 +1108,25 @@ static bool sort_generic(Env &env, int in_mode, const int32_t *row, const int32_
   la.off = off;
   la.major_out = out.major; la.minor_out = out.minor; la.key64_out = out.key64; la.val_out = (uint32_t *)out.val;
   la.flags = flags;
-  fill_u32(env, la.counters, 4, 0u);
-  // entries that a garbage input (coordinates out of range) leaves unwritten must still index safely
-  fill_u32(env, (uint32_t *)la.big, (uint64_t)la.big_cap * 4, 0u);
-  fill_u32(env, la.tilemap, la.tile_cap, 0u);
+  // counters start at zero, and entries of `big` and `tilemap` that a garbage input (coordinates out of range) leaves
+  // unwritten must still index safely: one fill when the three sit next to each other (carved from one block), else three
+  {
+    char *c0 = (char *)la.counters, *c1 = (char *)la.big, *c2 = (char *)la.tilemap;
+    const size_t b0 = Env::granule(4 * sizeof(uint32_t)), b1 = Env::granule(sizeof(BigBucket) * la.big_cap);
+    if (c1 == c0 + b0 && c2 == c1 + b1) {
+      fill_u32(env, la.counters, (b0 + b1) / 4 + la.tile_cap, 0u);
+    } else {
+      fill_u32(env, la.counters, 4, 0u);
+      fill_u32(env, (uint32_t *)la.big, (uint64_t)la.big_cap * 4, 0u);
+      fill_u32(env, la.tilemap, la.tile_cap, 0u);
+    }
+  }
   US_LAUNCH(env, "bucket_offsets", 4.0 * nbuckets, bucket_offsets_kernel, ceil_div<uint32_t>(nbuckets + 1, 256u), 256,
             la.rec_in, la.n, low_bits, nbuckets, off);
   US_LAUNCH(env, "big_list", 8.0 * nbuckets, big_list_kernel, ceil_div<uint32_t>(nbuckets, 256u), 256, la);
-  US_LAUNCH(env, "seg_hist", 0.0, seg_hist_kernel, la.tile_cap, RS_T, la);
-  US_LAUNCH(env, "seg_scan", 0.0, seg_scan_kernel, la.big_cap, RS_BINS, la);
-  US_LAUNCH(env, "seg_scatter", 0.0, seg_scatter_kernel, la.tile_cap, RS_T, la);
+  US_LAUNCH(env, "seg_hist", 0.0, seg_hist_kernel, min(la.tile_cap, SEG_GRID), RS_T, la);
+  US_LAUNCH(env, "seg_scan", 0.0, seg_scan_kernel, min(la.big_cap, SEG_GRID), RS_BINS, la);
+  US_LAUNCH(env, "seg_scatter", 0.0, seg_scatter_kernel, min(la.tile_cap, SEG_GRID), RS_T, la);
   // blocked tuples with in-block indices in the key (node keys of at most 31 bits): placement by node rank
   la.inner_bits = ks.mode == 1 ? ks.ih_bits + ks.iw_bits : (ks.mode == 2 ? ks.ih_bits : 0);
   const bool by_rank = la.inner_bits >= 1 && la.inner_bits <= 16;
