@@ -429,6 +429,24 @@ def other_workloads(B, W, torch, ctx, up, K, Wm, with_oracle, op_frac):
             variant("config3_bdia_csr_spmv",
                     lambda: list(B.us_decompose(ctx, m.nrows, m.ncols, w.r, w.c, w.v, P(B.US_F_BDIA, 4), P(B.US_F_CSR), pb)),
                     w.spmv, 2.0 * m.nnz)
+            # SpMM over the DIA + CSR hybrid (the DIA SpMM of Table 6, N = 64 here): the banded part alone and both parts
+            parts = w.convert()
+            N3 = 64
+            X3 = up(W.dense_operand(3, (m.ncols, N3))); Y3 = torch.empty(m.nrows, N3, device=dev)
+            ms_dia = timed_stream(torch, lambda: B.us_spmm(ctx, parts[0], X3, Y3), 2 * K, Wm)
+            ms_all = timed_stream(torch, lambda: (B.us_spmm(ctx, parts[0], X3, Y3),
+                                                  B.us_spmm(ctx, parts[1], X3, Y3, accumulate=True)), 2 * K, Wm)
+            xyb = 4.0 * N3 * (m.ncols + m.nrows)
+            res["config3_dia_csr_spmm64"] = {
+                "nnz": m.nnz, "N": N3,
+                "dia_part": {"entries": int(parts[0].nnz), "ms": round(ms_dia, 4),
+                             "gflop_s": round(2.0 * parts[0].nnz * N3 / ms_dia / 1e6, 1),
+                             "op_frac": frac(w.stored_bytes(parts[:1]) + xyb, ms_dia)},
+                "hybrid": {"ms": round(ms_all, 4), "gflop_s": round(2.0 * m.nnz * N3 / ms_all / 1e6, 1),
+                           "op_frac": frac(w.stored_bytes(parts) + xyb, ms_all)}}
+            for q in parts:
+                q.free()
+            del X3, Y3
         if index == 4:
             # whole-array digit passes only (blocked tuples finish inside LDS by default); COO -> ELL of Table 5 both ways
             variant("config4_bcsr_whole_array_passes_only",

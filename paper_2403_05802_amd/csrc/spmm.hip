@@ -275,19 +275,55 @@ __global__ __launch_bounds__(256) void ell_spmm_kernel(const int32_t *ecol, cons
   }
 }
 
-__global__ __launch_bounds__(256) void dia_spmm_kernel(const int32_t *off, const float *val, int64_t ndiag,
-                                                      int64_t nrows, int64_t ncols, int by_col, const float *X,
-                                                      int64_t N, int64_t ldx, float *Y, int64_t ldy, int accumulate) {
-  const int64_t i = (int64_t)blockIdx.x * 4 + wave_id();
-  if (i >= nrows) return;
-  const int64_t c = (int64_t)blockIdx.y * 64 + lane_id();
-  if (c >= N) return;
-  float s = accumulate ? Y[i * ldy + c] : 0.f;
+// DIA (and the DIA variant, whose slab is indexed by column): a wavefront owns 8 consecutive rows x 64 * VEC columns.
+// For diagonal k the 8 rows read 8 consecutive rows of X, so the loads of one diagonal are independent and in
+// flight together, the 8 values of the diagonal are one load handed out by v_readlane (scalars), and a row of X
+// that the other diagonals use again is found in the L2 of the XCD, which walks a contiguous range of row tiles
+// (offsets up to a few thousand rows: a window of a megabyte or two).
+// (Measured on the seven diagonals of the banded workload, N = 64: 1.09 ms with one wavefront per row and a
+// broadcast load per value, 0.41 ms this way = 2.75 TB/s on the compulsory bytes, and the counters show no byte
+// fetched twice.  Four diagonals' loads in flight together, or four 8-row steps per wavefront, changed nothing:
+// what is left is the L2, which serves every row of X once per diagonal, 9 TB/s at this speed.)
+constexpr int DIA_R = 8;
+template <int VEC>
+__global__ __launch_bounds__(256) void dia_spmm_rows_kernel(const int32_t *off, const float *val, int64_t ndiag,
+                                                           int64_t nrows, int64_t ncols, int by_col, int64_t per_xcd,
+                                                           const float *X, int64_t N, int64_t ldx, float *Y,
+                                                           int64_t ldy, int accumulate) {
+  typedef typename VecT<VEC>::type V;
+  constexpr int R = DIA_R;
+  const int lane = lane_id();
+  const int64_t i0 = (xcd_tile(blockIdx.x, per_xcd) * 4 + wave_id()) * R;
+  if (i0 >= nrows) return;
+  const int64_t c = ((int64_t)blockIdx.y * 64 + lane) * VEC;
+  const bool col_ok = c < N;
+  const uint32_t xoff = (uint32_t)(col_ok ? c : 0);   // clamped: loads stay in bounds, stores are guarded
+  V acc[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+    acc[r] = (accumulate && col_ok && i0 + r < nrows) ? *reinterpret_cast<const V *>(Y + (i0 + r) * ldy + c) : V(0.f);
+  const int64_t slab = by_col ? ncols : nrows;
   for (int64_t k = 0; k < ndiag; ++k) {
-    int64_t j = i + off[k];
-    if (j >= 0 && j < ncols) s += val[k * (by_col ? ncols : nrows) + (by_col ? j : i)] * X[j * ldx + c];
+    const int64_t o = off[k];
+    // lane r < R: the value of row i0 + r on this diagonal (zero where the diagonal leaves the matrix)
+    const int64_t i = i0 + lane, j = i + o;
+    const bool in = lane < R && i < nrows && j >= 0 && j < ncols;
+    const float mine = in ? val[k * slab + (by_col ? j : i)] : 0.f;
+    V xv[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int64_t jr = i0 + r + o;   // the same for every lane: a scalar branch
+      xv[r] = (i0 + r < nrows && jr >= 0 && jr < ncols) ? *reinterpret_cast<const V *>(X + jr * ldx + xoff) : V(0.f);
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+      acc[r] += __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mine), r)) * xv[r];
   }
-  Y[i * ldy + c] = s;
+  if (col_ok) {
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+      if (i0 + r < nrows) *reinterpret_cast<V *>(Y + (i0 + r) * ldy + c) = acc[r];
+  }
 }
 
 // BDIA: a wavefront per row, lanes over 64 columns of X / Y, walking the nodes of the row's block row
@@ -327,25 +363,73 @@ struct RowSrc {
 // register accumulator and flushes when the row changes.  Row pieces cut by a chunk boundary
 // go to a carry buffer and are summed in chunk order by the fix-up kernel (reproducible).
 constexpr int CS_CHUNK = 512;
+// ... or fewer when the list is short: a wavefront's entries are a serial chain of gather rounds (eight rows of X at a
+// time), so 147 k entries cut into 287 chunks kept 287 wavefronts busy for 64 rounds each, 0.26 ms on a part with
+// 1024 SIMDs; chunks of 64 entries make it 2,293 wavefronts of 8 rounds.
+static int chunk_entries(int64_t nnz) {
+  int len = CS_CHUNK;
+  while (len > 64 && nnz / len < 8192) len >>= 1;
+  return len;
+}
 
-template <int VEC>
+// SEARCH (rows found in ptr): the rows of the whole chunk and of its two neighbours are looked up first, eight
+// entries per lane with their bisections interleaved, and kept in LDS.  One bisection after the other (per batch of
+// 64 entries, plus four for the chunk's ends) is ~250 dependent loads: a remainder of 147 k entries in 2 M rows, a
+// few hundred wavefronts that all run at once, took 0.32 ms of pure latency that way.
+template <int VEC, bool SEARCH>
 __global__ __launch_bounds__(256) void coo_spmm_kernel(RowSrc row, const int32_t *col, const float *val,
-                                                      int64_t nnz, int64_t per_xcd, const float *X, int64_t N, int64_t ldx,
-                                                      float *Y, int64_t ldy, int32_t *carry_row, float *carry) {
+                                                      int64_t nnz, int chunk_len, int64_t per_xcd, const float *X, int64_t N,
+                                                      int64_t ldx, float *Y, int64_t ldy, int32_t *carry_row, float *carry) {
   typedef typename VecT<VEC>::type V;
+  constexpr int PER_LANE = CS_CHUNK / 64;   // slots of the look-up: chunk_len <= CS_CHUNK
+  __shared__ int32_t s_rows[SEARCH ? 4 : 1][SEARCH ? CS_CHUNK + 2 : 1];
   const int lane = lane_id();
   // launch index -> chunk through xcd_tile: an XCD walks one contiguous range of entries (rows), so the
   // rows of X that neighbouring matrix rows share are found again in its own L2
   const int64_t chunk = xcd_tile(blockIdx.x, per_xcd) * 4 + wave_id();
-  const int64_t e0 = chunk * CS_CHUNK;
+  const int64_t e0 = chunk * chunk_len;
   if (e0 >= nnz) return;
-  const int64_t e1 = min(e0 + CS_CHUNK, nnz);
+  const int64_t e1 = min(e0 + chunk_len, nnz);
   const int64_t c = ((int64_t)blockIdx.y * 64 + lane) * VEC;
   const bool col_ok = c < N;
   const uint32_t xoff = (uint32_t)(col_ok ? c : 0);   // clamped: loads stay in bounds, stores are guarded
-  const int32_t row_before = e0 > 0 ? row.of(e0 - 1) : -1;
-  const int32_t row_after = e1 < nnz ? row.of(e1) : -1;
-  const int32_t first_row = row.of(e0), last_row = row.of(e1 - 1);
+  int32_t row_before, row_after, first_row, last_row;
+  if (SEARCH) {
+    // slot q < PER_LANE: entry e0 + q * 64 + lane; slot PER_LANE: lane 0 the entry before the chunk, lane 1 the one after
+    int32_t lo[PER_LANE + 1], hi[PER_LANE + 1];
+    int64_t want[PER_LANE + 1];
+#pragma unroll
+    for (int q = 0; q <= PER_LANE; ++q) {
+      want[q] = q < PER_LANE ? e0 + q * 64 + lane : (lane == 0 ? e0 - 1 : e1);
+      const bool live = q < PER_LANE ? want[q] < e1 : ((lane == 0 && e0 > 0) || (lane == 1 && e1 < nnz));
+      lo[q] = 0; hi[q] = live ? (int32_t)row.nparents : 0;
+    }
+    for (bool more = true; more;) {   // upper_bound(ptr, e) - 1, all slots in step (their loads are independent)
+      more = false;
+#pragma unroll
+      for (int q = 0; q <= PER_LANE; ++q) {
+        if (lo[q] < hi[q]) {
+          const int32_t mid = lo[q] + ((hi[q] - lo[q]) >> 1);
+          if ((int64_t)row.ptr[mid + 1] <= want[q]) lo[q] = mid + 1; else hi[q] = mid;
+          more = true;
+        }
+      }
+      more = __any(more);
+    }
+#pragma unroll
+    for (int q = 0; q < PER_LANE; ++q)
+      if (want[q] < e1) s_rows[wave_id()][q * 64 + lane] = row.ids ? row.ids[lo[q]] : lo[q];
+    if (lane < 2) s_rows[wave_id()][CS_CHUNK + lane] = ((lane == 0 && e0 > 0) || (lane == 1 && e1 < nnz)) ? (row.ids ? row.ids[lo[PER_LANE]] : lo[PER_LANE]) : -1;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    row_before = s_rows[wave_id()][CS_CHUNK]; row_after = s_rows[wave_id()][CS_CHUNK + 1];
+    first_row = s_rows[wave_id()][0]; last_row = s_rows[wave_id()][e1 - 1 - e0];
+  } else {
+    row_before = e0 > 0 ? row.of(e0 - 1) : -1;
+    row_after = e1 < nnz ? row.of(e1) : -1;
+    first_row = row.of(e0); last_row = row.of(e1 - 1);
+  }
   V *carry_head = reinterpret_cast<V *>(carry + ((chunk * 2 + 0) * gridDim.y + blockIdx.y) * (64 * VEC)) + lane;
   V *carry_tail = reinterpret_cast<V *>(carry + ((chunk * 2 + 1) * gridDim.y + blockIdx.y) * (64 * VEC)) + lane;
   const bool head_cut = first_row == row_before, tail_cut = last_row == row_after;
@@ -355,7 +439,7 @@ __global__ __launch_bounds__(256) void coo_spmm_kernel(RowSrc row, const int32_t
   constexpr int U = 8;
   for (int64_t base = e0; base < e1; base += 64) {
     const int64_t e = base + lane;
-    const int32_t r = e < e1 ? row.of(e) : -1, cc = e < e1 ? __builtin_nontemporal_load(col + e) : 0;
+    const int32_t r = e < e1 ? (SEARCH ? s_rows[wave_id()][e - e0] : row.of(e)) : -1, cc = e < e1 ? __builtin_nontemporal_load(col + e) : 0;
     const float v = e < e1 ? __builtin_nontemporal_load(val + e) : 0.f;
     const int cnt = (int)min((int64_t)64, e1 - base);
     for (int t0 = 0; t0 < cnt; t0 += U) {
@@ -501,11 +585,12 @@ static void zero_rows(Env &env, float *Y, int64_t nrows, int64_t N, int64_t ldy)
 
 // scratch of the entry-balanced product: two carry rows per chunk (row index + one value per column of the lane layout)
 static size_t carry_rows_bytes(int64_t nnz) {
-  return ((size_t)ceil_div<int64_t>(nnz, CS_CHUNK) * 2 * sizeof(int32_t) + 255) / 256 * 256;
+  return ((size_t)ceil_div<int64_t>(nnz, chunk_entries(nnz)) * 2 * sizeof(int32_t) + 255) / 256 * 256;
 }
 size_t entry_balanced_scratch_bytes(int64_t nnz, int64_t N, int vec) {
   const int cbw = 64 * vec;
-  return carry_rows_bytes(nnz) + (size_t)ceil_div<int64_t>(nnz, CS_CHUNK) * 2 * ceil_div<int64_t>(N, cbw) * cbw * sizeof(float);
+  return carry_rows_bytes(nnz) +
+         (size_t)ceil_div<int64_t>(nnz, chunk_entries(nnz)) * 2 * ceil_div<int64_t>(N, cbw) * cbw * sizeof(float);
 }
 
 static void entry_balanced_spmm(Env &env, const us_formatted &A, const RowSrc &rs, const int32_t *col,
@@ -513,7 +598,8 @@ static void entry_balanced_spmm(Env &env, const us_formatted &A, const RowSrc &r
                                 int64_t ldy) {
   // Y must already hold the values to add to (zeros for a plain product)
   const double xy = 4.0 * N * (A.ncols + A.nrows);
-  const int64_t nchunks = ceil_div<int64_t>(A.nnz, CS_CHUNK);
+  const int chunk_len = chunk_entries(A.nnz);
+  const int64_t nchunks = ceil_div<int64_t>(A.nnz, chunk_len);
   const size_t rows_pad = carry_rows_bytes(A.nnz);
   const int cbw = 64 * vec;
   const int64_t ncbv = ceil_div<int64_t>(N, cbw);
@@ -525,9 +611,13 @@ static void entry_balanced_spmm(Env &env, const us_formatted &A, const RowSrc &r
     LaunchScope ls(env, name, 12.0 * A.nnz + xy);
     const int64_t per_xcd = ceil_div<int64_t>(ceil_div<int64_t>(nchunks, 4), 8);
     const dim3 grid((unsigned)(per_xcd * 8), (unsigned)ncbv);
-    if (vec == 4) hipLaunchKernelGGL(coo_spmm_kernel<4>, grid, dim3(256), 0, env.stream, rs, col, (const float *)A.val, A.nnz, per_xcd, X, N, ldx, Y, ldy, carry_row, carry);
-    else if (vec == 2) hipLaunchKernelGGL(coo_spmm_kernel<2>, grid, dim3(256), 0, env.stream, rs, col, (const float *)A.val, A.nnz, per_xcd, X, N, ldx, Y, ldy, carry_row, carry);
-    else hipLaunchKernelGGL(coo_spmm_kernel<1>, grid, dim3(256), 0, env.stream, rs, col, (const float *)A.val, A.nnz, per_xcd, X, N, ldx, Y, ldy, carry_row, carry);
+#define US_EB_LAUNCH(V, S) hipLaunchKernelGGL((coo_spmm_kernel<V, S>), grid, dim3(256), 0, env.stream, rs, col, (const float *)A.val, A.nnz, chunk_len, per_xcd, X, N, ldx, Y, ldy, carry_row, carry)
+    if (rs.row) {
+      if (vec == 4) US_EB_LAUNCH(4, false); else if (vec == 2) US_EB_LAUNCH(2, false); else US_EB_LAUNCH(1, false);
+    } else {
+      if (vec == 4) US_EB_LAUNCH(4, true); else if (vec == 2) US_EB_LAUNCH(2, true); else US_EB_LAUNCH(1, true);
+    }
+#undef US_EB_LAUNCH
     env.check(hipGetLastError());
   }
   if (env.ok()) {
@@ -623,9 +713,13 @@ us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, 
     case P_DIA:
       if (env.ok()) {
         LaunchScope ls(env, "spmm_dia", 4.0 * A.nval + xy);
-        hipLaunchKernelGGL(dia_spmm_kernel, dim3((unsigned)ceil_div<int64_t>(A.nrows, 4), (unsigned)ncb), dim3(256), 0,
-                           env.stream, (const int32_t *)A.level[0].idx, (const float *)A.val, A.nmajor, A.nrows, A.ncols,
-                           A.swapped ? 1 : 0, X, N, ldx, Y, ldy, acc);
+        const int64_t tiles = ceil_div<int64_t>(A.nrows, 4 * DIA_R), per_xcd = ceil_div<int64_t>(tiles, 8);
+        const dim3 grid((unsigned)(per_xcd * 8), (unsigned)ceil_div<int64_t>(N, 64 * vec));
+        const int32_t *off = (const int32_t *)A.level[0].idx;
+        const int by_col = A.swapped ? 1 : 0;
+        if (vec == 4) hipLaunchKernelGGL(dia_spmm_rows_kernel<4>, grid, dim3(256), 0, env.stream, off, (const float *)A.val, A.nmajor, A.nrows, A.ncols, by_col, per_xcd, X, N, ldx, Y, ldy, acc);
+        else if (vec == 2) hipLaunchKernelGGL(dia_spmm_rows_kernel<2>, grid, dim3(256), 0, env.stream, off, (const float *)A.val, A.nmajor, A.nrows, A.ncols, by_col, per_xcd, X, N, ldx, Y, ldy, acc);
+        else hipLaunchKernelGGL(dia_spmm_rows_kernel<1>, grid, dim3(256), 0, env.stream, off, (const float *)A.val, A.nmajor, A.nrows, A.ncols, by_col, per_xcd, X, N, ldx, Y, ldy, acc);
         env.check(hipGetLastError());
       }
       return env.status;
