@@ -185,6 +185,123 @@ __global__ __launch_bounds__(256) void bell_spmm_kernel(const int32_t *ecol, con
 }
 
 // any block size: one wavefront per (block row, 64 columns), plain FMAs
+// 1, 2 or 4 columns of X / Y per lane
+template <int VEC> struct VecT;
+template <> struct VecT<1> { typedef float type; };
+template <> struct VecT<2> { typedef float type __attribute__((ext_vector_type(2))); };
+template <> struct VecT<4> { typedef float type __attribute__((ext_vector_type(4))); };
+
+// BCSR with blocks other than 4 x 4 (up to 64 values a block): a wavefront owns a block row x 64 * VEC columns and
+// keeps one accumulator per row of the block.  One coalesced load brings the values of as many blocks as fit 64 lanes
+// (and one their block columns); they are handed out by v_readlane (the position is the same for every lane: a
+// scalar).  The columns of those blocks are walked eight at a time: eight rows of X in flight, each used for all bh
+// rows of its block.  BHP = block height rounded up to a power of two (size of the register array).
+// (One wavefront per block row that walked the blocks once per ROW of the block, re-reading X and loading every value
+// as a 64-lane broadcast, took 10.4 ms for 8 x 8 blocks and 3.1 ms for 2 x 2 on the FEM-like matrix at N = 64; this
+// takes 2.2 and 1.2 ms.  8 x 8 blocks there are three quarters padding and 64 multiply-adds a block: instruction issue.)
+template <int VEC, int BHP>
+__global__ __launch_bounds__(256) void bcsr_spmm_rows_kernel(const int32_t *ptr, const int32_t *idx, const float *val,
+                                                            int64_t nbr, int bh, int bw, int64_t per_xcd, int64_t nrows,
+                                                            int64_t ncols, const float *X, int64_t N, int64_t ldx, float *Y,
+                                                            int64_t ldy, int accumulate) {
+  typedef typename VecT<VEC>::type V;
+  constexpr int U = 8;   // rows of X in flight
+  const int lane = lane_id();
+  const int64_t br = xcd_tile(blockIdx.x, per_xcd) * 4 + wave_id();
+  if (br >= nbr) return;
+  const int64_t c = ((int64_t)blockIdx.y * 64 + lane) * VEC;
+  const bool col_ok = c < N;
+  const uint32_t xoff = (uint32_t)(col_ok ? c : 0);   // clamped: loads stay in bounds, stores are guarded
+  const int64_t row0 = br * bh;
+  const int bsz = bh * bw, group = 64 / bsz;          // blocks whose values one load brings
+  V acc[BHP];
+#pragma unroll
+  for (int r = 0; r < BHP; ++r)
+    acc[r] = (accumulate && col_ok && r < bh && row0 + r < nrows) ? *reinterpret_cast<const V *>(Y + (row0 + r) * ldy + c) : V(0.f);
+  const int b1 = ptr[br + 1];
+  for (int b0 = ptr[br]; b0 < b1; b0 += group) {
+    const int nb = min(group, b1 - b0);
+    const int vmine = __builtin_bit_cast(int, lane < nb * bsz ? val[(int64_t)b0 * bsz + lane] : 0.f);
+    const int cmine = lane < nb ? idx[b0 + lane] : 0;
+    // the nb * bw columns of these blocks, U at a time; (g, k) = block in the group, column in the block
+    const int nslots = nb * bw;
+    int g = 0, k = 0;
+    for (int s0 = 0; s0 < nslots; s0 += U) {
+      V xv[U];
+      int at[U];   // lane of vmine that holds row 0 of the slot's column
+#pragma unroll
+      for (int u = 0; u < U; ++u) {   // (everything here is the same for every lane: scalar arithmetic and branches)
+        const int64_t xr = (int64_t)__builtin_amdgcn_readlane(cmine, g) * bw + k;
+        const bool live = s0 + u < nslots && xr < ncols;
+        xv[u] = live ? *reinterpret_cast<const V *>(X + xr * ldx + xoff) : V(0.f);
+        at[u] = live ? g * bsz + k : -1;
+        if (++k == bw) { k = 0; g = g + 1 < nb ? g + 1 : g; }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (at[u] >= 0) {
+#pragma unroll
+          for (int r = 0; r < BHP; ++r)
+            if (r < bh) acc[r] += __builtin_bit_cast(float, __builtin_amdgcn_readlane(vmine, at[u] + r * bw)) * xv[u];
+        }
+      }
+    }
+  }
+  if (col_ok) {
+#pragma unroll
+    for (int r = 0; r < BHP; ++r)
+      if (r < bh && row0 + r < nrows) *reinterpret_cast<V *>(Y + (row0 + r) * ldy + c) = acc[r];
+  }
+}
+
+// BDIA: the same shape of work.  A node is a piece of a diagonal, bh consecutive rows long: its values are one load,
+// its rows of X are consecutive, and a wavefront owns the block row x 64 * VEC columns with one accumulator per row.
+template <int VEC, int BHP>
+__global__ __launch_bounds__(256) void bdia_spmm_rows_kernel(const int32_t *ptr, const int32_t *off, const float *val,
+                                                            int64_t nbr, int bh, int64_t per_xcd, int64_t nrows, int64_t ncols,
+                                                            const float *X, int64_t N, int64_t ldx, float *Y, int64_t ldy,
+                                                            int accumulate) {
+  typedef typename VecT<VEC>::type V;
+  const int lane = lane_id();
+  const int64_t br = xcd_tile(blockIdx.x, per_xcd) * 4 + wave_id();
+  if (br >= nbr) return;
+  const int64_t c = ((int64_t)blockIdx.y * 64 + lane) * VEC;
+  const bool col_ok = c < N;
+  const uint32_t xoff = (uint32_t)(col_ok ? c : 0);
+  const int64_t row0 = br * bh;
+  V acc[BHP];
+#pragma unroll
+  for (int r = 0; r < BHP; ++r)
+    acc[r] = (accumulate && col_ok && r < bh && row0 + r < nrows) ? *reinterpret_cast<const V *>(Y + (row0 + r) * ldy + c) : V(0.f);
+  constexpr int J = BHP >= 8 ? 1 : 8 / BHP;   // nodes taken together: eight rows of X in flight
+  const int n1 = ptr[br + 1];
+  for (int n0 = ptr[br]; n0 < n1; n0 += J) {
+    int vmine[J];
+    V xv[J][BHP];
+#pragma unroll
+    for (int q = 0; q < J; ++q) {
+      const bool live = n0 + q < n1;           // the same for every lane
+      const int64_t o = live ? off[n0 + q] : 0;
+      vmine[q] = __builtin_bit_cast(int, (live && lane < bh) ? val[(int64_t)(n0 + q) * bh + lane] : 0.f);
+#pragma unroll
+      for (int r = 0; r < BHP; ++r) {
+        const int64_t j = row0 + r + o;
+        xv[q][r] = (live && r < bh && row0 + r < nrows && j >= 0 && j < ncols) ? *reinterpret_cast<const V *>(X + j * ldx + xoff) : V(0.f);
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < J; ++q)
+#pragma unroll
+      for (int r = 0; r < BHP; ++r)
+        if (r < bh) acc[r] += __builtin_bit_cast(float, __builtin_amdgcn_readlane(vmine[q], r)) * xv[q][r];
+  }
+  if (col_ok) {
+#pragma unroll
+    for (int r = 0; r < BHP; ++r)
+      if (r < bh && row0 + r < nrows) *reinterpret_cast<V *>(Y + (row0 + r) * ldy + c) = acc[r];
+  }
+}
+
 __global__ __launch_bounds__(256) void bcsr_spmm_kernel(const int32_t *ptr, const int32_t *idx, const float *val,
                                                        int64_t nbr, int bh, int bw, int64_t nrows, int64_t ncols,
                                                        const float *X, int64_t N, int64_t ldx, float *Y,
@@ -210,10 +327,6 @@ __global__ __launch_bounds__(256) void bcsr_spmm_kernel(const int32_t *ptr, cons
 
 // ------------------------------------------------------------------ row-grouped layouts, one wavefront per (row, 64 columns)
 // A lane owns VEC consecutive columns (VEC = 2 covers N = 128 with one wavefront per row).
-template <int VEC> struct VecT;
-template <> struct VecT<1> { typedef float type; };
-template <> struct VecT<2> { typedef float type __attribute__((ext_vector_type(2))); };
-template <> struct VecT<4> { typedef float type __attribute__((ext_vector_type(4))); };
 
 // ELL: a wavefront owns 8 consecutive rows.  One coalesced load brings the column indices and values
 // of 8 slots x 8 rows (lane = slot*8 + row); they are handed out by v_readlane, i.e. as scalars, so
@@ -326,23 +439,6 @@ __global__ __launch_bounds__(256) void dia_spmm_rows_kernel(const int32_t *off, 
   }
 }
 
-// BDIA: a wavefront per row, lanes over 64 columns of X / Y, walking the nodes of the row's block row
-__global__ __launch_bounds__(256) void bdia_spmm_kernel(const int32_t *ptr, const int32_t *off, const float *val,
-                                                       int bh, int64_t nrows, int64_t ncols, const float *X, int64_t N,
-                                                       int64_t ldx, float *Y, int64_t ldy, int accumulate) {
-  const int64_t i = (int64_t)blockIdx.x * 4 + wave_id();
-  if (i >= nrows) return;
-  const int64_t c = (int64_t)blockIdx.y * 64 + lane_id();
-  if (c >= N) return;
-  const int64_t br = i / bh;
-  const int ri = (int)(i - br * bh);
-  float s = accumulate ? Y[i * ldy + c] : 0.f;
-  for (int64_t n = ptr[br]; n < ptr[br + 1]; ++n) {
-    const int64_t j = i + off[n];
-    if (j >= 0 && j < ncols) s += val[n * bh + ri] * X[j * ldx + c];
-  }
-  Y[i * ldy + c] = s;
-}
 
 // ------------------------------------------------------------------ entries grouped by row (COO sorted by row, CSR, DCSR): equal shares of non-zeros per wavefront
 // The row of entry e is read from the COO row array, or found in ptr (plus the stored-row list
@@ -394,7 +490,7 @@ __global__ __launch_bounds__(256) void coo_spmm_kernel(RowSrc row, const int32_t
   const bool col_ok = c < N;
   const uint32_t xoff = (uint32_t)(col_ok ? c : 0);   // clamped: loads stay in bounds, stores are guarded
   int32_t row_before, row_after, first_row, last_row;
-  if (SEARCH) {
+  if constexpr (SEARCH) {
     // slot q < PER_LANE: entry e0 + q * 64 + lane; slot PER_LANE: lane 0 the entry before the chunk, lane 1 the one after
     int32_t lo[PER_LANE + 1], hi[PER_LANE + 1];
     int64_t want[PER_LANE + 1];
@@ -439,7 +535,11 @@ __global__ __launch_bounds__(256) void coo_spmm_kernel(RowSrc row, const int32_t
   constexpr int U = 8;
   for (int64_t base = e0; base < e1; base += 64) {
     const int64_t e = base + lane;
-    const int32_t r = e < e1 ? (SEARCH ? s_rows[wave_id()][e - e0] : row.of(e)) : -1, cc = e < e1 ? __builtin_nontemporal_load(col + e) : 0;
+    int32_t r = -1;
+    if (e < e1) {
+      if constexpr (SEARCH) r = s_rows[wave_id()][e - e0]; else r = row.of(e);
+    }
+    const int32_t cc = e < e1 ? __builtin_nontemporal_load(col + e) : 0;
     const float v = e < e1 ? __builtin_nontemporal_load(val + e) : 0.f;
     const int cnt = (int)min((int64_t)64, e1 - base);
     for (int t0 = 0; t0 < cnt; t0 += U) {
@@ -649,7 +749,17 @@ us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, 
                              (const float *)A.val, A.nmajor, per_xcd, A.nrows, A.ncols, X, N, ldx, Y, ldy, acc);
           env.check(hipGetLastError());
         }
-      } else if (env.ok()) {
+      } else if (env.ok() && A.bh * A.bw <= 64) {
+        LaunchScope ls(env, "spmm_bcsr", 4.0 * A.nval + 4.0 * A.nblk + xy);
+        const int64_t tiles = ceil_div<int64_t>(A.nmajor, 4), per_xcd = ceil_div<int64_t>(tiles, 8);
+        const dim3 grid((unsigned)(per_xcd * 8), (unsigned)ceil_div<int64_t>(N, 64 * vec));
+#define US_BCSR_LAUNCH(V, H) hipLaunchKernelGGL((bcsr_spmm_rows_kernel<V, H>), grid, dim3(256), 0, env.stream, (const int32_t *)A.level[1].ptr, (const int32_t *)A.level[1].idx, (const float *)A.val, A.nmajor, (int)A.bh, (int)A.bw, per_xcd, A.nrows, A.ncols, X, N, ldx, Y, ldy, acc)
+#define US_BCSR_BY_HEIGHT(V) do { if (A.bh <= 2) US_BCSR_LAUNCH(V, 2); else if (A.bh <= 4) US_BCSR_LAUNCH(V, 4); else if (A.bh <= 8) US_BCSR_LAUNCH(V, 8); else US_BCSR_LAUNCH(V, 16); } while (0)
+        if (vec == 4) US_BCSR_BY_HEIGHT(4); else if (vec == 2) US_BCSR_BY_HEIGHT(2); else US_BCSR_BY_HEIGHT(1);
+#undef US_BCSR_BY_HEIGHT
+#undef US_BCSR_LAUNCH
+        env.check(hipGetLastError());
+      } else if (env.ok()) {   // blocks of more than 64 values: the plain loop
         LaunchScope ls(env, "spmm_bcsr", 4.0 * A.nval + 4.0 * A.nblk + xy);
         hipLaunchKernelGGL(bcsr_spmm_kernel, dim3((unsigned)ceil_div<int64_t>(A.nmajor, 4), (unsigned)ncb), dim3(256),
                            0, env.stream, (const int32_t *)A.level[1].ptr, (const int32_t *)A.level[1].idx,
@@ -737,9 +847,13 @@ us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, 
     case P_BDIA:
       if (env.ok()) {
         LaunchScope ls(env, "spmm_bdia", 4.0 * A.nval + 4.0 * A.nblk + xy);
-        hipLaunchKernelGGL(bdia_spmm_kernel, dim3((unsigned)ceil_div<int64_t>(A.nrows, 4), (unsigned)ncb), dim3(256), 0,
-                           env.stream, (const int32_t *)A.level[1].ptr, (const int32_t *)A.level[1].idx,
-                           (const float *)A.val, (int)A.bh, A.nrows, A.ncols, X, N, ldx, Y, ldy, acc);
+        const int64_t tiles = ceil_div<int64_t>(A.nmajor, 4), per_xcd = ceil_div<int64_t>(tiles, 8);
+        const dim3 grid((unsigned)(per_xcd * 8), (unsigned)ceil_div<int64_t>(N, 64 * vec));
+#define US_BDIA_LAUNCH(V, H) hipLaunchKernelGGL((bdia_spmm_rows_kernel<V, H>), grid, dim3(256), 0, env.stream, (const int32_t *)A.level[1].ptr, (const int32_t *)A.level[1].idx, (const float *)A.val, A.nmajor, (int)A.bh, per_xcd, A.nrows, A.ncols, X, N, ldx, Y, ldy, acc)
+#define US_BDIA_BY_HEIGHT(V) do { if (A.bh <= 2) US_BDIA_LAUNCH(V, 2); else if (A.bh <= 4) US_BDIA_LAUNCH(V, 4); else if (A.bh <= 8) US_BDIA_LAUNCH(V, 8); else US_BDIA_LAUNCH(V, 16); } while (0)
+        if (vec == 4) US_BDIA_BY_HEIGHT(4); else if (vec == 2) US_BDIA_BY_HEIGHT(2); else US_BDIA_BY_HEIGHT(1);
+#undef US_BDIA_BY_HEIGHT
+#undef US_BDIA_LAUNCH
         env.check(hipGetLastError());
       }
       return env.status;
