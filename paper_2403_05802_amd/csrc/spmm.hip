@@ -645,18 +645,85 @@ __global__ __launch_bounds__(256) void csc_spmm_atomic_kernel(const int32_t *ptr
   for (int e = ptr[j]; e < ptr[j + 1]; ++e) atomicAdd(&Y[(int64_t)idx[e] * ldy + cc], val[e] * xv);
 }
 
-// CSB: one wavefront per (entry, 64 columns of X), block found in ptr, fp32 atomics into Y
-__global__ __launch_bounds__(256) void csb_spmm_atomic_kernel(const int32_t *ptr, const int32_t *in_row,
-                                                             const int32_t *in_col, const float *val, int64_t n,
-                                                             int64_t nblocks, int64_t nbc, int64_t bh, int64_t bw,
-                                                             const float *X, int64_t N, int64_t ldx, float *Y, int64_t ldy) {
-  const int64_t e = (int64_t)blockIdx.x * 4 + wave_id();
-  if (e >= n) return;
-  const int64_t cc = (int64_t)blockIdx.y * 64 + lane_id();
-  if (cc >= N) return;
-  const int64_t blk = parent_of(ptr, nblocks, e);
-  const int64_t row = (blk / nbc) * bh + in_row[e], col = (blk % nbc) * bw + in_col[e];
-  atomicAdd(&Y[row * ldy + cc], val[e] * X[col * ldx + cc]);
+// CSB: the entries lie in (block row, block column, in-block row, in-block column) order, so a wavefront that walks
+// a chunk of consecutive entries meets every row of a block as one run.  It looks up the block of each of its
+// entries first (the blocks of the chunk's two ends by bisection over all blocks, the others between those two),
+// keeps row and column in LDS, then works like the row-major kernel: row, column and value of an entry are scalars,
+// eight rows of X in flight, one accumulator, flushed when the row changes.  Other blocks of the block row (in other
+// chunks) add to the same rows of Y, so a flush is an fp32 atomic add (not bit-reproducible): one per run and column,
+// where one wavefront per entry did one per entry and column and a bisection over all blocks each time (45.7 ms for
+// 50 M entries in 512 x 512 blocks at N = 64).
+template <int VEC>
+__global__ __launch_bounds__(256) void csb_spmm_kernel(const int32_t *ptr, const int32_t *in_row, const int32_t *in_col,
+                                                      const float *val, int64_t n, int chunk_len, int64_t per_xcd,
+                                                      int64_t nblocks, int64_t nbc, int64_t bh, int64_t bw, const float *X,
+                                                      int64_t N, int64_t ldx, float *Y, int64_t ldy) {
+  typedef typename VecT<VEC>::type V;
+  __shared__ int32_t s_row[4][CS_CHUNK], s_col[4][CS_CHUNK];
+  const int lane = lane_id(), w = wave_id();
+  const int64_t chunk = xcd_tile(blockIdx.x, per_xcd) * 4 + w;
+  const int64_t e0 = chunk * chunk_len;
+  if (e0 >= n) return;
+  const int64_t e1 = min(e0 + chunk_len, n);
+  const int64_t c = ((int64_t)blockIdx.y * 64 + lane) * VEC;
+  const bool col_ok = c < N;
+  const uint32_t xoff = (uint32_t)(col_ok ? c : 0);   // clamped: loads stay in bounds, stores are guarded
+  const int64_t blk_first = parent_of(ptr, nblocks, e0), blk_last = parent_of(ptr, nblocks, e1 - 1);
+  for (int64_t e = e0 + lane; e < e1; e += 64) {
+    int64_t lo = blk_first, hi = blk_last;
+    while (lo < hi) {
+      const int64_t mid = (lo + hi) >> 1;
+      if ((int64_t)ptr[mid + 1] <= e) lo = mid + 1; else hi = mid;
+    }
+    s_row[w][e - e0] = (int32_t)((lo / nbc) * bh + in_row[e]);
+    s_col[w][e - e0] = (int32_t)((lo % nbc) * bw + in_col[e]);
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  auto flush = [&](int32_t row, const V &acc) {
+    if (!col_ok) return;
+    float *yp = Y + (int64_t)row * ldy + c;
+    if constexpr (VEC == 1) atomicAdd(yp, acc);
+    else {
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) atomicAdd(yp + i, acc[i]);
+    }
+  };
+  V acc = V(0.f);
+  int32_t cur = s_row[w][0];
+  constexpr int U = 8;
+  for (int64_t base = e0; base < e1; base += 64) {
+    const int64_t e = base + lane;
+    const int32_t r = e < e1 ? s_row[w][e - e0] : -1, cc = e < e1 ? s_col[w][e - e0] : 0;
+    const float v = e < e1 ? __builtin_nontemporal_load(val + e) : 0.f;
+    const int cnt = (int)min((int64_t)64, e1 - base);
+    for (int t0 = 0; t0 < cnt; t0 += U) {
+      int32_t rt[U];
+      float vt[U];
+      V xv[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int t = t0 + u < cnt ? t0 + u : cnt - 1;
+        rt[u] = __builtin_amdgcn_readlane(r, t);
+        vt[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), t));
+        const int64_t ct = __builtin_amdgcn_readlane(cc, t);
+        xv[u] = *reinterpret_cast<const V *>(X + ct * ldx + xoff);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (t0 + u < cnt) {
+          if (rt[u] != cur) {
+            flush(cur, acc);
+            acc = V(0.f);
+            cur = rt[u];
+          }
+          acc += vt[u] * xv[u];
+        }
+      }
+    }
+  }
+  flush(cur, acc);
 }
 
 // scatter form for the column-major COO
@@ -837,10 +904,12 @@ us_status spmm_impl(Env &env, const us_formatted &A, const float *X, int64_t N, 
       if (!accumulate) zero_rows(env, Y, A.nrows, N, ldy);
       if (env.ok() && A.nnz > 0) {
         LaunchScope ls(env, "spmm_csb_atomic", 12.0 * A.nnz + xy);
-        hipLaunchKernelGGL(csb_spmm_atomic_kernel, dim3((unsigned)ceil_div<int64_t>(A.nnz, 4), (unsigned)ncb), dim3(256),
-                           0, env.stream, (const int32_t *)A.level[2].ptr, (const int32_t *)A.level[2].idx,
-                           (const int32_t *)A.level[3].idx, (const float *)A.val, A.nnz, A.nmajor, A.level[1].size, A.bh,
-                           A.bw, X, N, ldx, Y, ldy);
+        const int chunk_len = chunk_entries(A.nnz);
+        const int64_t per_xcd = ceil_div<int64_t>(ceil_div<int64_t>(ceil_div<int64_t>(A.nnz, chunk_len), 4), 8);
+        const dim3 grid((unsigned)(per_xcd * 8), (unsigned)ceil_div<int64_t>(N, 64 * vec));
+#define US_CSB_LAUNCH(V) hipLaunchKernelGGL(csb_spmm_kernel<V>, grid, dim3(256), 0, env.stream, (const int32_t *)A.level[2].ptr, (const int32_t *)A.level[2].idx, (const int32_t *)A.level[3].idx, (const float *)A.val, A.nnz, chunk_len, per_xcd, A.nmajor, A.level[1].size, A.bh, A.bw, X, N, ldx, Y, ldy)
+        if (vec == 4) US_CSB_LAUNCH(4); else if (vec == 2) US_CSB_LAUNCH(2); else US_CSB_LAUNCH(1);
+#undef US_CSB_LAUNCH
         env.check(hipGetLastError());
       }
       return env.status;

@@ -413,17 +413,45 @@ __global__ __launch_bounds__(256) void bell_spmv_kernel(const int32_t *ecol, con
   y[i] = s;
 }
 
-// CSB: one thread per entry; its block (hence its row and column origin) is found in ptr.  Entries of a
-// block row interleave rows, so sums go through fp32 atomics (like the column-major layouts).
-__global__ __launch_bounds__(256) void csb_spmv_atomic_kernel(const int32_t *ptr, const int32_t *in_row,
-                                                             const int32_t *in_col, const float *val, int64_t n,
-                                                             int64_t nblocks, int64_t nbc, int64_t bh, int64_t bw,
-                                                             const float *x, float *y) {
-  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (e >= n) return;
-  const int64_t blk = parent_of(ptr, nblocks, e);
-  const int64_t row = (blk / nbc) * bh + in_row[e], col = (blk % nbc) * bw + in_col[e];
-  atomicAdd(&y[row], val[e] * x[col]);
+// CSB: a lane per entry, 64 consecutive entries at a time, a wavefront per chunk of consecutive entries.  The blocks
+// of the chunk's first and last entries are found by bisection over all blocks (the same search for every lane), a
+// lane's own block between those two.  Entries of a block are sorted by row, so the lanes of one row are neighbours: their products are summed by a
+// segmented scan and the last lane of every run adds the sum to y.  Other blocks of the block row add to the same
+// rows, so that add is an fp32 atomic (not bit-reproducible); one per run instead of one per entry.
+constexpr int CSB_CHUNK = 512;   // entries per wavefront: the two bisections over all blocks are paid once per chunk
+__global__ __launch_bounds__(256) void csb_spmv_kernel(const int32_t *ptr, const int32_t *in_row, const int32_t *in_col,
+                                                      const float *val, int64_t n, int64_t nblocks, int64_t nbc, int64_t bh,
+                                                      int64_t bw, const float *x, float *y) {
+  const int lane = lane_id();
+  const int64_t e0 = ((int64_t)blockIdx.x * 4 + wave_id()) * CSB_CHUNK;
+  if (e0 >= n) return;
+  const int64_t e1 = min(e0 + CSB_CHUNK, n);
+  const int64_t blk_first = parent_of(ptr, nblocks, e0), blk_last = parent_of(ptr, nblocks, e1 - 1);
+  for (int64_t base = e0; base < e1; base += 64) {
+    const int64_t e = base + lane;
+    const bool live = e < e1;
+    int64_t lo = blk_first, hi = blk_last;
+    if (live) {
+      while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if ((int64_t)ptr[mid + 1] <= e) lo = mid + 1; else hi = mid;
+      }
+    }
+    const int64_t row = live ? (lo / nbc) * bh + in_row[e] : -1;
+    float p = live ? val[e] * x[(lo % nbc) * bw + in_col[e]] : 0.f;
+    // runs of one row: head = first lane of a run; a lane's run = number of heads up to it
+    const int64_t prev = __shfl_up(row, 1);
+    const uint64_t heads = __ballot(lane == 0 || prev != row);
+    const int run = __popcll(heads & (lanes_below() | (1ull << lane)));
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const float t = __shfl_up(p, d);
+      const int tr = __shfl_up(run, d);
+      if (lane >= d && tr == run) p += t;
+    }
+    const bool tail = lane == 63 || ((heads >> (lane + 1)) & 1ull);
+    if (live && tail) atomicAdd(&y[row], p);
+  }
 }
 
 static void spmv_coo_rows(Env &env, const us_formatted &A, const float *x, float *y, bool accumulate) {
@@ -508,7 +536,7 @@ us_status spmv_impl(Env &env, const us_formatted &A, const float *x, float *y, b
     case P_CSB:
       if (!accumulate) fill_u32(env, (uint32_t *)y, A.nrows, 0u);
       if (A.nnz > 0)
-        US_LAUNCH(env, "spmv_csb_atomic", 20.0 * A.nnz, csb_spmv_atomic_kernel, ceil_div<int64_t>(A.nnz, 256), 256,
+        US_LAUNCH(env, "spmv_csb_atomic", 20.0 * A.nnz, csb_spmv_kernel, ceil_div<int64_t>(A.nnz, 4 * CSB_CHUNK), 256,
                   (const int32_t *)A.level[2].ptr, (const int32_t *)A.level[2].idx, (const int32_t *)A.level[3].idx,
                   (const float *)A.val, A.nnz, A.nmajor, A.level[1].size, A.bh, A.bw, x, y);
       return env.status;

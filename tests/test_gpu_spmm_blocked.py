@@ -92,3 +92,32 @@ def test_blocked_spmm_accumulate_and_strides(ctx, desc, N, ldx, ldy):
     assert np.array_equal(got[:, N:], Yw0[:, N:])
     H.assert_product(got[:, :N], ref, S, nt, f"strided accumulate N={N}")
     g.free()
+
+
+@pytest.mark.parametrize("bh,bw", [(64, 48), (300, 700), (1, 1), (4000, 4000)])
+@pytest.mark.parametrize("N", [0, 7, 64, 130, 256])
+def test_csb_products_every_output(ctx, bh, bw, N):
+    """CSB: runs of one row inside a block are summed before they reach y / Y (N = 0: SpMV)."""
+    from paper_2403_05802_amd import binding as B
+    rng = np.random.default_rng(8300 + bh + N)
+    nr, nc = 3001, 2203
+    r, c, v = scattered_blocks(rng, nr, nc, 60_000)
+    g = B.us_convert(ctx, nr, nc, H.dev(r), H.dev(c), H.dev(v), H.us_desc_of(O.CSB(bh, bw)))
+    if N == 0:
+        x = rng.uniform(-1, 1, nc).astype(np.float32)
+        ref, S, nt = reference(nr, nc, r, c, v, x[:, None])
+        y = H.dev(np.full(nr, 3.0, np.float32))
+        B.us_spmv(ctx, g, H.dev(x), y)
+        H.assert_product(H.host(y), ref[:, 0], S[:, 0], nt[:, 0], f"CSB {bh}x{bw} SpMV")
+        y0 = rng.uniform(-1, 1, nr).astype(np.float32)
+        ref, S, nt = reference(nr, nc, r, c, v, x[:, None], y0[:, None].astype(np.float64))
+        y = H.dev(y0)
+        B.us_spmv(ctx, g, H.dev(x), y, accumulate=True)
+        H.assert_product(H.host(y), ref[:, 0], S[:, 0], nt[:, 0], f"CSB {bh}x{bw} SpMV accumulate")
+    else:
+        X = rng.uniform(-1, 1, (nc, N)).astype(np.float32)
+        ref, S, nt = reference(nr, nc, r, c, v, X)
+        Y = H.dev(np.full((nr, N), 3.0, np.float32))
+        B.us_spmm(ctx, g, H.dev(X), Y)
+        H.assert_product(H.host(Y), ref, S, nt, f"CSB {bh}x{bw} N={N}")
+    g.free()
