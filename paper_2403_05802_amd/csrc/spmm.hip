@@ -468,17 +468,18 @@ static int chunk_entries(int64_t nnz) {
   return len;
 }
 
-// SEARCH (rows found in ptr): the rows of the whole chunk and of its two neighbours are looked up first, eight
-// entries per lane with their bisections interleaved, and kept in LDS.  One bisection after the other (per batch of
-// 64 entries, plus four for the chunk's ends) is ~250 dependent loads: a remainder of 147 k entries in 2 M rows, a
-// few hundred wavefronts that all run at once, took 0.32 ms of pure latency that way.
+// SEARCH (rows found in ptr): the rows of the whole chunk are looked up first and kept in LDS: the parents of the two
+// entries around the chunk by bisection over all parents, then eight entries per lane with their bisections between
+// those two in step.  One full bisection after the other (per batch of 64 entries, plus four for the chunk's ends) is
+// ~250 dependent loads -- a remainder of 147 k entries in 2 M rows, a few hundred wavefronts that all run at once, took
+// 0.32 ms of pure latency that way -- and twenty scattered loads per entry where the rows of a chunk are a handful.
 template <int VEC, bool SEARCH>
 __global__ __launch_bounds__(256) void coo_spmm_kernel(RowSrc row, const int32_t *col, const float *val,
                                                       int64_t nnz, int chunk_len, int64_t per_xcd, const float *X, int64_t N,
                                                       int64_t ldx, float *Y, int64_t ldy, int32_t *carry_row, float *carry) {
   typedef typename VecT<VEC>::type V;
   constexpr int PER_LANE = CS_CHUNK / 64;   // slots of the look-up: chunk_len <= CS_CHUNK
-  __shared__ int32_t s_rows[SEARCH ? 4 : 1][SEARCH ? CS_CHUNK + 2 : 1];
+  __shared__ int32_t s_rows[SEARCH ? 4 : 1][SEARCH ? CS_CHUNK : 1];
   const int lane = lane_id();
   // launch index -> chunk through xcd_tile: an XCD walks one contiguous range of entries (rows), so the
   // rows of X that neighbouring matrix rows share are found again in its own L2
@@ -491,22 +492,35 @@ __global__ __launch_bounds__(256) void coo_spmm_kernel(RowSrc row, const int32_t
   const uint32_t xoff = (uint32_t)(col_ok ? c : 0);   // clamped: loads stay in bounds, stores are guarded
   int32_t row_before, row_after, first_row, last_row;
   if constexpr (SEARCH) {
-    // slot q < PER_LANE: entry e0 + q * 64 + lane; slot PER_LANE: lane 0 the entry before the chunk, lane 1 the one after
-    int32_t lo[PER_LANE + 1], hi[PER_LANE + 1];
-    int64_t want[PER_LANE + 1];
-#pragma unroll
-    for (int q = 0; q <= PER_LANE; ++q) {
-      want[q] = q < PER_LANE ? e0 + q * 64 + lane : (lane == 0 ? e0 - 1 : e1);
-      const bool live = q < PER_LANE ? want[q] < e1 : ((lane == 0 && e0 > 0) || (lane == 1 && e1 < nnz));
-      lo[q] = 0; hi[q] = live ? (int32_t)row.nparents : 0;
+    // parents of the entries just before and just after the chunk: two bisections over all parents, in step, the same
+    // for every lane (ptr[p] <= e < ptr[p + 1])
+    const int64_t eb = e0 > 0 ? e0 - 1 : e0, ea = e1 < nnz ? e1 : e1 - 1;
+    int32_t blo = 0, bhi = (int32_t)row.nparents, alo = 0, ahi = (int32_t)row.nparents;
+    while (blo < bhi || alo < ahi) {
+      if (blo < bhi) {
+        const int32_t mid = blo + ((bhi - blo) >> 1);
+        if ((int64_t)row.ptr[mid + 1] <= eb) blo = mid + 1; else bhi = mid;
+      }
+      if (alo < ahi) {
+        const int32_t mid = alo + ((ahi - alo) >> 1);
+        if ((int64_t)row.ptr[mid + 1] <= ea) alo = mid + 1; else ahi = mid;
+      }
     }
-    for (bool more = true; more;) {   // upper_bound(ptr, e) - 1, all slots in step (their loads are independent)
+    // every entry of the chunk has its parent between those two: PER_LANE entries per lane, their bisections over
+    // that range in step (a chunk inside one long row needs none, 96-entry rows three steps instead of twenty)
+    int32_t lo[PER_LANE], hi[PER_LANE];
+#pragma unroll
+    for (int q = 0; q < PER_LANE; ++q) {
+      const bool live = e0 + q * 64 + lane < e1;
+      lo[q] = blo; hi[q] = live ? alo : blo;
+    }
+    for (bool more = true; more;) {
       more = false;
 #pragma unroll
-      for (int q = 0; q <= PER_LANE; ++q) {
+      for (int q = 0; q < PER_LANE; ++q) {
         if (lo[q] < hi[q]) {
           const int32_t mid = lo[q] + ((hi[q] - lo[q]) >> 1);
-          if ((int64_t)row.ptr[mid + 1] <= want[q]) lo[q] = mid + 1; else hi[q] = mid;
+          if ((int64_t)row.ptr[mid + 1] <= e0 + q * 64 + lane) lo[q] = mid + 1; else hi[q] = mid;
           more = true;
         }
       }
@@ -514,12 +528,12 @@ __global__ __launch_bounds__(256) void coo_spmm_kernel(RowSrc row, const int32_t
     }
 #pragma unroll
     for (int q = 0; q < PER_LANE; ++q)
-      if (want[q] < e1) s_rows[wave_id()][q * 64 + lane] = row.ids ? row.ids[lo[q]] : lo[q];
-    if (lane < 2) s_rows[wave_id()][CS_CHUNK + lane] = ((lane == 0 && e0 > 0) || (lane == 1 && e1 < nnz)) ? (row.ids ? row.ids[lo[PER_LANE]] : lo[PER_LANE]) : -1;
+      if (e0 + q * 64 + lane < e1) s_rows[wave_id()][q * 64 + lane] = row.ids ? row.ids[lo[q]] : lo[q];
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    row_before = s_rows[wave_id()][CS_CHUNK]; row_after = s_rows[wave_id()][CS_CHUNK + 1];
+    row_before = e0 > 0 ? (row.ids ? row.ids[blo] : blo) : -1;
+    row_after = e1 < nnz ? (row.ids ? row.ids[alo] : alo) : -1;
     first_row = s_rows[wave_id()][0]; last_row = s_rows[wave_id()][e1 - 1 - e0];
   } else {
     row_before = e0 > 0 ? row.of(e0 - 1) : -1;
