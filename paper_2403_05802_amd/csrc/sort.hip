@@ -454,7 +454,7 @@ __global__ __launch_bounds__(RS_T) void radix_scatter_kernel(PassArgs a) {
 // split of its own first: its tiles are counted, scanned and scattered like a digit pass, but
 // only its items move.  The pieces are then bundled, in order, into groups of at most LS_CAP
 // items that the same LDS kernel finishes (it sorts by all low bits, so a group may span
-// several pieces).  A bucket beyond LS_MAXTILES tiles, or a piece above LS_GROUP items, sets
+// several pieces; a piece above LS_GROUP items is a group of its own).  A bucket beyond LS_MAXTILES tiles, or a piece above LS_CAP items, sets
 // Flags::retry and the host sorts again with whole-array passes only.
 // (Replacing the digit passes inside LDS by one 8-bit split plus counting smaller keys inside each piece
 // was tried: the keys of a blocked layout cluster -- block columns inside a band, 16 entries per block --
@@ -571,12 +571,14 @@ __global__ __launch_bounds__(RS_BINS) void seg_scan_kernel(LocalArgs a) {
   uint32_t total;
   const uint32_t start = block_exclusive_sum<RS_BINS>(run, s_wave, &total);
   a.sdig[(size_t)k * RS_BINS + d] = start;
-  if (run > (uint32_t)LS_GROUP) a.flags->retry = RETRY_SORT_LDS;
+  if (run > (uint32_t)LS_CAP) a.flags->retry = RETRY_SORT_LDS;
   s_pos[d] = start;
   if (d == 0) s_pos[RS_BINS] = B.size;
   __syncthreads();
-  // piece d opens a group when its start falls in another LS_GROUP-sized interval than the one before
-  const bool head = d == 0 || start / LS_GROUP != s_pos[d - 1] / LS_GROUP;
+  // piece d opens a group when its start falls in another LS_GROUP-sized interval than the one before (pieces of at
+  // most LS_GROUP items bundled that way stay below LS_CAP together); a piece above LS_GROUP is a group of its own
+  // (the piece behind it starts more than LS_GROUP further on, in another interval, hence in a new group)
+  const bool head = d == 0 || run > (uint32_t)LS_GROUP || start / LS_GROUP != s_pos[d - 1] / LS_GROUP;
   uint32_t nheads;
   const uint32_t rank = block_exclusive_sum<RS_BINS>(head ? 1u : 0u, s_wave, &nheads);
   if (d == 0) s_base = atomicAdd(&a.counters[2], nheads);
@@ -1011,7 +1013,7 @@ static bool sort_generic(Env &env, int in_mode, const int32_t *row, const int32_
   LocalArgs la{};
   la.big_cap = (uint32_t)(nnz / LS_CAP) + 1;                 // a big bucket holds more than LS_CAP items
   la.tile_cap = (uint32_t)(nnz / RS_TILE) + la.big_cap;      // each has at most size/RS_TILE + 1 tiles
-  la.work_cap = (uint32_t)(nnz / LS_GROUP) + la.big_cap;     // ... and at most size/LS_GROUP + 1 groups
+  la.work_cap = 2 * (uint32_t)(nnz / LS_GROUP) + la.big_cap; // ... and at most size/LS_GROUP + 1 groups that an interval opens, size/LS_GROUP that a large piece opens
   {  // everything below in one allocation
     auto g = [](size_t b) { return Env::granule(b); };
     size_t need = (nrec < 2 ? nrec : 2) * g(sizeof(Rec) * nnz) + (npass - 1 < 2 ? npass - 1 : 2) * g(nnz + 16) +
