@@ -188,3 +188,19 @@ def test_duplicates_are_found_whichever_way_a_bucket_is_finished(ctx, bh, bw, fi
             with lds_finish(ctx), pytest.raises(B.UnisparseError) as ei:
                 B.us_convert(ctx, nr, nc, dev(r2[p]), dev(c2[p]), dev(v2[p]), us_desc_of(d))
             assert ei.value.code == "US_ERR_DUPLICATE"
+
+
+def test_pieces_between_half_and_full_capacity_are_groups_of_their_own(ctx):
+    """8 rows share the top key bits; one of them holds 100,000 entries: the 8-bit split of that bucket leaves pieces
+    of ~3,100 entries (row, 32,768 columns), more than pieces may have to be bundled and still small enough for one
+    workgroup: no second attempt."""
+    rng = np.random.default_rng(15)
+    nr, nc = 1024, 1 << 20
+    r = np.concatenate([rng.integers(0, nr, 60_000), np.full(100_000, 5)])
+    c = np.concatenate([rng.integers(0, nc, 60_000), rng.choice(nc, 100_000, replace=False)])
+    r, c = distinct(nr, nc, r, c)
+    per_piece = np.bincount(c[r == 5] >> 15)
+    assert 2048 < per_piece.max() <= 4096
+    r, c, v = shuffled(rng, r, c)
+    check(ctx, nr, nc, r, c, v, [O.CSR(), O.DCSR(), O.COO(), O.BCSR(4), O.BDIA(2)])
+    assert scatter_passes(ctx, nr, nc, r, c, v, O.CSR()) == 1
